@@ -1,0 +1,234 @@
+"""ctypes access to the CPU oracle (oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the bench's CPU-baseline leg may import this
+package.  It shares nothing with the HIP library and never imports it.
+
+Arrays are numpy, in host memory: float32 for F32 inputs and uint16 bit
+patterns for BF16 / F16 inputs.  Results come back as float64, unrounded.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+F32, BF16, F16 = 0, 1, 2
+EPI_NONE, EPI_BIAS, EPI_RELU, EPI_BIAS_RELU, EPI_BIAS_GELU_TANH, EPI_GELU_TANH = range(6)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.c")
+_HDR = os.path.join(_HERE, "oracle.h")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile oracle.c with gcc into liboracle.so (next to the source)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        i64, vp, f32, i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_float, ctypes.c_int
+        L.oracle_matmul.argtypes = [vp, vp, vp, vp, vp] + [i64] * 6 + [i32, i32, f32, i32]
+        L.oracle_batched_matmul.argtypes = [vp, vp, vp, vp, vp] + [i64] * 10 + [i32, i32, f32, i32]
+        L.oracle_conv2d_nhwc.argtypes = [vp, vp, vp, vp, vp] + [i64] * 13 + [i32, f32, i32]
+        L.oracle_batched_matmul_at.argtypes = ([vp, vp, vp, vp, vp] + [i64] * 8
+                                               + [i32, i32, f32, i32, i64, vp, vp, vp])
+        L.oracle_conv2d_nhwc_at.argtypes = ([vp, vp, vp, vp, vp] + [i64] * 13
+                                            + [i32, f32, i32, i64, vp, vp, vp, vp])
+        L.oracle_conv_out_dim.argtypes = [i64] * 5
+        L.oracle_conv_out_dim.restype = i64
+        L.oracle_epilogue.argtypes = [ctypes.c_double, ctypes.c_double, f32, i32]
+        L.oracle_epilogue.restype = ctypes.c_double
+        L.oracle_gelu_tanh.argtypes = [ctypes.c_double]
+        L.oracle_gelu_tanh.restype = ctypes.c_double
+        L.oracle_widen.argtypes = [ctypes.c_uint32, i32]
+        L.oracle_widen.restype = ctypes.c_double
+        L.oracle_round_bf16.argtypes = [ctypes.c_double]
+        L.oracle_round_bf16.restype = ctypes.c_uint16
+        L.oracle_round_f16.argtypes = [ctypes.c_double]
+        L.oracle_round_f16.restype = ctypes.c_uint16
+        L.oracle_num_threads.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data
+
+
+def _check_in(a: np.ndarray, dtype: int) -> np.ndarray:
+    want = np.float32 if dtype == F32 else np.uint16
+    if a.dtype != want:
+        raise TypeError(f"dtype code {dtype} needs a {want.__name__} array, got {a.dtype}")
+    return a
+
+
+def _check_bias(bias):
+    if bias is None:
+        return None
+    if bias.dtype != np.float32 or not bias.flags.c_contiguous:
+        raise TypeError("bias must be contiguous float32")
+    return bias
+
+
+def _rc(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"{what}: oracle rejected the arguments (code {rc})")
+
+
+def matmul(A, B, bias=None, *, dtype, trans_b=0, alpha=1.0, epi=EPI_NONE,
+           M=None, N=None, K=None, lda=None, ldb=None, want_preact=False):
+    """act(alpha*A.B + bias) as float64 [M][N]; A, B are 2-d arrays (or views
+    described by M, N, K, lda, ldb over a contiguous parent)."""
+    out = batched_matmul(A, B, bias, dtype=dtype, trans_b=trans_b, alpha=alpha, epi=epi,
+                         batch=1, M=M if M is not None else A.shape[0],
+                         N=N if N is not None else (B.shape[0] if trans_b else B.shape[1]),
+                         K=K if K is not None else A.shape[1],
+                         lda=lda if lda is not None else A.shape[1],
+                         ldb=ldb if ldb is not None else B.shape[1],
+                         stride_a=0, stride_b=0, want_preact=want_preact)
+    if want_preact:
+        return out[0][0], out[1][0]
+    return out[0]
+
+
+def batched_matmul(A, B, bias=None, *, dtype, trans_b=0, alpha=1.0, epi=EPI_NONE,
+                   batch=None, M=None, N=None, K=None, lda=None, ldb=None,
+                   stride_a=None, stride_b=None, want_preact=False):
+    A = _check_in(np.ascontiguousarray(A), dtype)
+    B = _check_in(np.ascontiguousarray(B), dtype)
+    bias = _check_bias(bias)
+    if batch is None:
+        batch = A.shape[0]
+    if M is None:
+        M = A.shape[-2]
+    if K is None:
+        K = A.shape[-1]
+    if N is None:
+        N = B.shape[-2] if trans_b else B.shape[-1]
+    if lda is None:
+        lda = A.shape[-1]
+    if ldb is None:
+        ldb = B.shape[-1]
+    if stride_a is None:
+        stride_a = A.shape[-2] * A.shape[-1] if A.ndim == 3 else 0
+    if stride_b is None:
+        stride_b = B.shape[-2] * B.shape[-1] if B.ndim == 3 else 0
+    out = np.empty((batch, M, N), dtype=np.float64)
+    pre = np.empty_like(out) if want_preact else None
+    rc = lib().oracle_batched_matmul(_ptr(A), _ptr(B), _ptr(bias), _ptr(out), _ptr(pre),
+                                     batch, M, N, K, lda, ldb, N, stride_a, stride_b, M * N,
+                                     dtype, int(trans_b), float(alpha), epi)
+    _rc(rc, "batched_matmul")
+    return (out, pre) if want_preact else out
+
+
+def batched_matmul_at(A, B, bias, sb, si, sj, *, dtype, trans_b=0, alpha=1.0, epi=EPI_NONE,
+                      batch, M, N, K, lda=None, ldb=None, stride_a=None, stride_b=None):
+    """(out, preact) at the listed (batch, row, col) coordinates only."""
+    A = _check_in(np.ascontiguousarray(A), dtype)
+    B = _check_in(np.ascontiguousarray(B), dtype)
+    bias = _check_bias(bias)
+    sb = np.ascontiguousarray(sb, dtype=np.int64)
+    si = np.ascontiguousarray(si, dtype=np.int64)
+    sj = np.ascontiguousarray(sj, dtype=np.int64)
+    if lda is None:
+        lda = K
+    if ldb is None:
+        ldb = K if trans_b else N
+    if stride_a is None:
+        stride_a = M * lda
+    if stride_b is None:
+        stride_b = (N if trans_b else K) * ldb
+    out = np.empty(len(si), dtype=np.float64)
+    pre = np.empty_like(out)
+    rc = lib().oracle_batched_matmul_at(_ptr(A), _ptr(B), _ptr(bias), _ptr(out), _ptr(pre),
+                                        batch, M, N, K, lda, ldb, stride_a, stride_b,
+                                        dtype, int(trans_b), float(alpha), epi,
+                                        len(si), _ptr(sb), _ptr(si), _ptr(sj))
+    _rc(rc, "batched_matmul_at")
+    return out, pre
+
+
+def conv_out_dim(size, k, stride, pad, dil) -> int:
+    return int(lib().oracle_conv_out_dim(size, k, stride, pad, dil))
+
+
+def conv2d_nhwc(x, w, bias=None, *, dtype, stride=(1, 1), pad=(0, 0), dil=(1, 1),
+                alpha=1.0, epi=EPI_NONE, want_preact=False):
+    """x [N][H][W][Cin], w [KH][KW][Cin][Cout] -> float64 [N][OH][OW][Cout]."""
+    x = _check_in(np.ascontiguousarray(x), dtype)
+    w = _check_in(np.ascontiguousarray(w), dtype)
+    bias = _check_bias(bias)
+    n, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    OH = conv_out_dim(H, KH, stride[0], pad[0], dil[0])
+    OW = conv_out_dim(W, KW, stride[1], pad[1], dil[1])
+    if OH < 0 or OW < 0:
+        raise ValueError("empty output")
+    out = np.empty((n, OH, OW, Cout), dtype=np.float64)
+    pre = np.empty_like(out) if want_preact else None
+    rc = lib().oracle_conv2d_nhwc(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), _ptr(pre),
+                                  n, H, W, Cin, Cout, KH, KW, stride[0], stride[1],
+                                  pad[0], pad[1], dil[0], dil[1], dtype, float(alpha), epi)
+    _rc(rc, "conv2d_nhwc")
+    return (out, pre) if want_preact else out
+
+
+def conv2d_nhwc_at(x, w, bias, sn, soh, sow, sco, *, dtype, stride=(1, 1), pad=(0, 0),
+                   dil=(1, 1), alpha=1.0, epi=EPI_NONE):
+    x = _check_in(np.ascontiguousarray(x), dtype)
+    w = _check_in(np.ascontiguousarray(w), dtype)
+    bias = _check_bias(bias)
+    n, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    idx = [np.ascontiguousarray(v, dtype=np.int64) for v in (sn, soh, sow, sco)]
+    out = np.empty(len(idx[0]), dtype=np.float64)
+    pre = np.empty_like(out)
+    rc = lib().oracle_conv2d_nhwc_at(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), _ptr(pre),
+                                     n, H, W, Cin, Cout, KH, KW, stride[0], stride[1],
+                                     pad[0], pad[1], dil[0], dil[1], dtype, float(alpha), epi,
+                                     len(out), *[_ptr(v) for v in idx])
+    _rc(rc, "conv2d_nhwc_at")
+    return out, pre
+
+
+def epilogue(s, bias, alpha, epi) -> float:
+    return float(lib().oracle_epilogue(float(s), float(bias), float(alpha), epi))
+
+
+def gelu_tanh(t) -> float:
+    return float(lib().oracle_gelu_tanh(float(t)))
+
+
+def widen_bits(bits: int, dtype: int) -> float:
+    return float(lib().oracle_widen(int(bits), dtype))
+
+
+def round_bf16(v: float) -> int:
+    return int(lib().oracle_round_bf16(float(v)))
+
+
+def round_f16(v: float) -> int:
+    return int(lib().oracle_round_f16(float(v)))
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())

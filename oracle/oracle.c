@@ -1,0 +1,346 @@
+/*
+ * CPU oracle: plain definitions in double.  TEST INFRASTRUCTURE ONLY; see
+ * oracle.h.  No tiling, no blocking, no reordering of the sums: every output
+ * is one ascending-k sum of exact products, then the epilogue.
+ * OpenMP only spreads independent outputs over cores.
+ */
+#include "oracle.h"
+
+#include <math.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- exact widening of stored bits ------------------------------------ */
+
+static double widen_bf16(uint16_t b)
+{
+    /* bf16 is the upper half of an IEEE binary32 */
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double widen_f16(uint16_t b)
+{
+    int sign = (b >> 15) & 1;
+    int e = (b >> 10) & 0x1F;
+    int m = b & 0x3FF;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -24);                  /* zero and subnormals */
+    else if (e == 31)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexp((double)(m | 0x400), e - 25);     /* 1.m * 2^(e-15) */
+    return sign ? -v : v;
+}
+
+double oracle_widen(uint32_t bits, int dtype)
+{
+    if (dtype == ORACLE_BF16) return widen_bf16((uint16_t)bits);
+    if (dtype == ORACLE_F16) return widen_f16((uint16_t)bits);
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static inline double load(const void* p, int dtype, int64_t idx)
+{
+    if (dtype == ORACLE_F32) return (double)((const float*)p)[idx];
+    if (dtype == ORACLE_BF16) return widen_bf16(((const uint16_t*)p)[idx]);
+    return widen_f16(((const uint16_t*)p)[idx]);
+}
+
+/* ---- rounding to 16-bit formats (for tests of the conversion only) ----- */
+
+/* Round v to a binary format with `prec` significant bits, smallest normal
+ * exponent emin (value 2^emin) and overflow threshold 2^emax_plus1. */
+static double round_to_format(double v, int prec, int emin, int emax_plus1)
+{
+    if (isnan(v) || isinf(v) || v == 0.0) return v;
+    int e;
+    (void)frexp(fabs(v), &e);              /* |v| in [2^(e-1), 2^e) */
+    int ulp_exp = e - prec;                /* spacing of the format there */
+    int min_ulp_exp = emin - (prec - 1);   /* subnormal spacing */
+    if (ulp_exp < min_ulp_exp) ulp_exp = min_ulp_exp;
+    double q = ldexp(v, -ulp_exp);         /* exact */
+    double r = ldexp(rint(q), ulp_exp);    /* rint: nearest, ties to even */
+    if (fabs(r) >= ldexp(1.0, emax_plus1)) return copysign(INFINITY, v);
+    return r;
+}
+
+uint16_t oracle_round_bf16(double v)
+{
+    if (isnan(v)) return 0x7FC0;
+    double r = round_to_format(v, 8, -126, 128);
+    float f = (float)r;                    /* exact: r is a bf16 value */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
+uint16_t oracle_round_f16(double v)
+{
+    if (isnan(v)) return 0x7E00;
+    double r = round_to_format(v, 11, -14, 16);
+    uint16_t s = signbit(r) ? 0x8000 : 0;
+    double a = fabs(r);
+    if (isinf(a)) return s | 0x7C00;
+    if (a == 0.0) return s;
+    if (a < ldexp(1.0, -14))               /* subnormal: a = m * 2^-24 */
+        return s | (uint16_t)ldexp(a, 24);
+    int e;
+    double m = frexp(a, &e);               /* a = m * 2^e, m in [0.5,1) */
+    uint16_t mant = (uint16_t)(ldexp(m, 11)) & 0x3FF;   /* 1.xxx -> 10 bits */
+    return s | (uint16_t)((e - 1 + 15) << 10) | mant;
+}
+
+/* ---- epilogue --------------------------------------------------------- */
+
+double oracle_gelu_tanh(double t)
+{
+    const double c = 0.7978845608028654;   /* sqrt(2/pi) */
+    return 0.5 * t * (1.0 + tanh(c * (t + 0.044715 * t * t * t)));
+}
+
+static int epi_has_bias(int epi)
+{
+    return epi == ORACLE_EPI_BIAS || epi == ORACLE_EPI_BIAS_RELU ||
+           epi == ORACLE_EPI_BIAS_GELU_TANH;
+}
+
+static double preactivation(double s, double bias, float alpha, int epi)
+{
+    double t = (double)alpha * s;
+    if (epi_has_bias(epi)) t += bias;
+    return t;
+}
+
+static double activation(double t, int epi)
+{
+    switch (epi) {
+    case ORACLE_EPI_RELU:
+    case ORACLE_EPI_BIAS_RELU:
+        return isnan(t) ? t : (t > 0.0 ? t : 0.0);
+    case ORACLE_EPI_BIAS_GELU_TANH:
+    case ORACLE_EPI_GELU_TANH:
+        return oracle_gelu_tanh(t);
+    default:
+        return t;
+    }
+}
+
+double oracle_epilogue(double s, double bias, float alpha, int epi)
+{
+    return activation(preactivation(s, bias, alpha, epi), epi);
+}
+
+static int check_common(int dtype, int epi, const float* bias)
+{
+    if (dtype < ORACLE_F32 || dtype > ORACLE_F16) return -1;
+    if (epi < ORACLE_EPI_NONE || epi > ORACLE_EPI_GELU_TANH) return -2;
+    if (epi_has_bias(epi) && !bias) return -3;
+    return 0;
+}
+
+/* ---- matmul ------------------------------------------------------------ */
+
+/* one output of one batch entry: sum over k ascending of A[i][k]*B[k][j] */
+static double dot_ik_kj(const void* A, const void* B, int dtype, int trans_b,
+                        int64_t a_off, int64_t b_off, int64_t lda, int64_t ldb,
+                        int64_t i, int64_t j, int64_t K)
+{
+    double s = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+        double a = load(A, dtype, a_off + i * lda + k);
+        double b = trans_b ? load(B, dtype, b_off + j * ldb + k)
+                           : load(B, dtype, b_off + k * ldb + j);
+        s += a * b;
+    }
+    return s;
+}
+
+int oracle_batched_matmul(const void* A, const void* B, const float* bias,
+                          double* out, double* preact,
+                          int64_t batch, int64_t M, int64_t N, int64_t K,
+                          int64_t lda, int64_t ldb, int64_t ldo,
+                          int64_t stride_a, int64_t stride_b, int64_t stride_o,
+                          int dtype, int trans_b, float alpha, int epi)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (batch < 0 || M < 0 || N < 0 || K < 0) return -4;
+    if (lda < K || ldo < N || ldb < (trans_b ? K : N)) return -5;
+    if (!out || ((!A || !B) && K > 0 && M > 0 && N > 0 && batch > 0)) return -6;
+
+    for (int64_t b = 0; b < batch; ++b) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t i = 0; i < M; ++i) {
+            for (int64_t j = 0; j < N; ++j) {
+                double s = dot_ik_kj(A, B, dtype, trans_b, b * stride_a, b * stride_b,
+                                     lda, ldb, i, j, K);
+                double t = preactivation(s, epi_has_bias(epi) ? (double)bias[j] : 0.0,
+                                         alpha, epi);
+                int64_t o = b * stride_o + i * ldo + j;
+                if (preact) preact[o] = t;
+                out[o] = activation(t, epi);
+            }
+        }
+    }
+    return 0;
+}
+
+int oracle_matmul(const void* A, const void* B, const float* bias,
+                  double* out, double* preact,
+                  int64_t M, int64_t N, int64_t K,
+                  int64_t lda, int64_t ldb, int64_t ldo,
+                  int dtype, int trans_b, float alpha, int epi)
+{
+    return oracle_batched_matmul(A, B, bias, out, preact, 1, M, N, K, lda, ldb, ldo,
+                                 0, 0, 0, dtype, trans_b, alpha, epi);
+}
+
+int oracle_batched_matmul_at(const void* A, const void* B, const float* bias,
+                             double* out, double* preact,
+                             int64_t batch, int64_t M, int64_t N, int64_t K,
+                             int64_t lda, int64_t ldb,
+                             int64_t stride_a, int64_t stride_b,
+                             int dtype, int trans_b, float alpha, int epi,
+                             int64_t nsamp, const int64_t* sb,
+                             const int64_t* si, const int64_t* sj)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (batch < 1 || M < 1 || N < 1 || K < 0 || nsamp < 0) return -4;
+    if (lda < K || ldb < (trans_b ? K : N)) return -5;
+    if (!out || !A || !B || !sb || !si || !sj) return -6;
+    for (int64_t s = 0; s < nsamp; ++s)
+        if (sb[s] < 0 || sb[s] >= batch || si[s] < 0 || si[s] >= M || sj[s] < 0 || sj[s] >= N)
+            return -7;
+
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t s = 0; s < nsamp; ++s) {
+        double acc = dot_ik_kj(A, B, dtype, trans_b, sb[s] * stride_a, sb[s] * stride_b,
+                               lda, ldb, si[s], sj[s], K);
+        double t = preactivation(acc, epi_has_bias(epi) ? (double)bias[sj[s]] : 0.0,
+                                 alpha, epi);
+        if (preact) preact[s] = t;
+        out[s] = activation(t, epi);
+    }
+    return 0;
+}
+
+/* ---- direct convolution ------------------------------------------------ */
+
+int64_t oracle_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad, int64_t dil)
+{
+    if (in < 1 || k < 1 || stride < 1 || pad < 0 || dil < 1) return -1;
+    int64_t span = in + 2 * pad - dil * (k - 1) - 1;
+    if (span < 0) return -1;
+    return span / stride + 1;
+}
+
+/* one output pixel/channel: sum over kh, kw, c ascending */
+static double conv_point(const void* x, const void* w, int dtype,
+                         int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                         int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                         int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                         int64_t n, int64_t oh, int64_t ow, int64_t co)
+{
+    double s = 0.0;
+    for (int64_t kh = 0; kh < KH; ++kh) {
+        int64_t ih = oh * stride_h - pad_h + kh * dil_h;
+        if (ih < 0 || ih >= H) continue;
+        for (int64_t kw = 0; kw < KW; ++kw) {
+            int64_t iw = ow * stride_w - pad_w + kw * dil_w;
+            if (iw < 0 || iw >= W) continue;
+            for (int64_t c = 0; c < Cin; ++c) {
+                double xv = load(x, dtype, ((n * H + ih) * W + iw) * Cin + c);
+                double wv = load(w, dtype, ((kh * KW + kw) * Cin + c) * Cout + co);
+                s += xv * wv;
+            }
+        }
+    }
+    return s;
+}
+
+int oracle_conv2d_nhwc(const void* x, const void* w, const float* bias,
+                       double* out, double* preact,
+                       int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                       int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                       int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                       int dtype, float alpha, int epi)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (N < 0 || Cin < 1 || Cout < 1) return -4;
+    int64_t OH = oracle_conv_out_dim(H, KH, stride_h, pad_h, dil_h);
+    int64_t OW = oracle_conv_out_dim(W, KW, stride_w, pad_w, dil_w);
+    if (OH < 0 || OW < 0) return -5;
+    if (!x || !w || !out) return -6;
+
+    for (int64_t n = 0; n < N; ++n) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t oh = 0; oh < OH; ++oh) {
+            for (int64_t ow = 0; ow < OW; ++ow) {
+                for (int64_t co = 0; co < Cout; ++co) {
+                    double s = conv_point(x, w, dtype, H, W, Cin, Cout, KH, KW,
+                                          stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                                          n, oh, ow, co);
+                    double t = preactivation(s, epi_has_bias(epi) ? (double)bias[co] : 0.0,
+                                             alpha, epi);
+                    int64_t o = ((n * OH + oh) * OW + ow) * Cout + co;
+                    if (preact) preact[o] = t;
+                    out[o] = activation(t, epi);
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+int oracle_conv2d_nhwc_at(const void* x, const void* w, const float* bias,
+                          double* out, double* preact,
+                          int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                          int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                          int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                          int dtype, float alpha, int epi,
+                          int64_t nsamp, const int64_t* sn, const int64_t* soh,
+                          const int64_t* sow, const int64_t* sco)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (N < 1 || Cin < 1 || Cout < 1 || nsamp < 0) return -4;
+    int64_t OH = oracle_conv_out_dim(H, KH, stride_h, pad_h, dil_h);
+    int64_t OW = oracle_conv_out_dim(W, KW, stride_w, pad_w, dil_w);
+    if (OH < 0 || OW < 0) return -5;
+    if (!x || !w || !out || !sn || !soh || !sow || !sco) return -6;
+    for (int64_t s = 0; s < nsamp; ++s)
+        if (sn[s] < 0 || sn[s] >= N || soh[s] < 0 || soh[s] >= OH ||
+            sow[s] < 0 || sow[s] >= OW || sco[s] < 0 || sco[s] >= Cout)
+            return -7;
+
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t s = 0; s < nsamp; ++s) {
+        double acc = conv_point(x, w, dtype, H, W, Cin, Cout, KH, KW,
+                                stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                                sn[s], soh[s], sow[s], sco[s]);
+        double t = preactivation(acc, epi_has_bias(epi) ? (double)bias[sco[s]] : 0.0,
+                                 alpha, epi);
+        if (preact) preact[s] = t;
+        out[s] = activation(t, epi);
+    }
+    return 0;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,108 @@
+/*
+ * CPU oracle for the fused dense contraction  out = act(alpha * (A . B) + bias).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the plain mathematical definition written
+ * out in IEEE double: a triple loop for matmul, a seven-deep loop nest for the
+ * direct convolution, the epilogue in double, results returned unrounded.  It
+ * shares no code with the HIP library and must never be called from it; only
+ * tests, the smoke check and the bench's CPU-baseline leg use it.
+ *
+ * Operator semantics follow the paper: convolution as LHS.RHS with the index
+ * map of the "convolution lowered as a 3-d matmul nest" figure (Sec. 4.5),
+ * 16-bit inputs extended before the multiply (Sec. 5, evaluation setup), the
+ * pointwise tail fused on the output tile (Sec. 4.3).  Accumulation is fp64
+ * here (the paper's generated code accumulates in fp32).
+ *
+ * All pointers are host pointers.  16-bit inputs are raw bit patterns
+ * (uint16_t), widened exactly.  Every function returns 0 on success and a
+ * negative value on an invalid argument.
+ */
+#ifndef PBK_ORACLE_H
+#define PBK_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types of A, B, image, weights */
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
+
+/* epilogues: t = alpha*s (+ bias[j]);  out = act(t) */
+enum {
+    ORACLE_EPI_NONE = 0,
+    ORACLE_EPI_BIAS = 1,
+    ORACLE_EPI_RELU = 2,
+    ORACLE_EPI_BIAS_RELU = 3,
+    ORACLE_EPI_BIAS_GELU_TANH = 4,
+    ORACLE_EPI_GELU_TANH = 5
+};
+
+/* out[i*ldo + j] = act(alpha * sum_k A[i][k]*B[k][j] + bias[j]).
+ * A is M x K with leading dimension lda.  B is K x N (ldb) or, if trans_b,
+ * stored N x K (ldb) and read as B[k][j] = Bt[j][k].  preact (may be NULL)
+ * receives t before the activation, same layout as out. */
+int oracle_matmul(const void* A, const void* B, const float* bias,
+                  double* out, double* preact,
+                  int64_t M, int64_t N, int64_t K,
+                  int64_t lda, int64_t ldb, int64_t ldo,
+                  int dtype, int trans_b, float alpha, int epi);
+
+/* batch independent problems; element strides between consecutive batches
+ * (stride_a / stride_b may be 0 to broadcast). */
+int oracle_batched_matmul(const void* A, const void* B, const float* bias,
+                          double* out, double* preact,
+                          int64_t batch, int64_t M, int64_t N, int64_t K,
+                          int64_t lda, int64_t ldb, int64_t ldo,
+                          int64_t stride_a, int64_t stride_b, int64_t stride_o,
+                          int dtype, int trans_b, float alpha, int epi);
+
+/* Direct convolution (cross-correlation, no filter flip).
+ * x [N][H][W][Cin], w [KH][KW][Cin][Cout], out [N][OH][OW][Cout],
+ * OH = (H + 2*pad_h - dil_h*(KH-1) - 1)/stride_h + 1 (floor), same for OW.
+ * Taps that fall outside the image contribute nothing. */
+int oracle_conv2d_nhwc(const void* x, const void* w, const float* bias,
+                       double* out, double* preact,
+                       int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                       int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                       int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                       int dtype, float alpha, int epi);
+
+/* Same definitions evaluated only at listed output coordinates (for sizes at
+ * which the full loops would take hours).  out[s], preact[s] per sample. */
+int oracle_batched_matmul_at(const void* A, const void* B, const float* bias,
+                             double* out, double* preact,
+                             int64_t batch, int64_t M, int64_t N, int64_t K,
+                             int64_t lda, int64_t ldb,
+                             int64_t stride_a, int64_t stride_b,
+                             int dtype, int trans_b, float alpha, int epi,
+                             int64_t nsamp, const int64_t* sb,
+                             const int64_t* si, const int64_t* sj);
+
+int oracle_conv2d_nhwc_at(const void* x, const void* w, const float* bias,
+                          double* out, double* preact,
+                          int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                          int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                          int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                          int dtype, float alpha, int epi,
+                          int64_t nsamp, const int64_t* sn, const int64_t* soh,
+                          const int64_t* sow, const int64_t* sco);
+
+/* Output size of one spatial dimension, or -1 if empty/invalid. */
+int64_t oracle_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad, int64_t dil);
+
+/* scalar pieces, exported so that tests can pin them one by one */
+double   oracle_epilogue(double s, double bias, float alpha, int epi);
+double   oracle_gelu_tanh(double t);
+double   oracle_widen(uint32_t bits, int dtype);       /* stored bits -> double */
+uint16_t oracle_round_bf16(double v);                  /* round-to-nearest-even */
+uint16_t oracle_round_f16(double v);
+
+/* number of threads the loops will use (OpenMP) */
+int oracle_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

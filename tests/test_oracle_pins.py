@@ -1,0 +1,446 @@
+"""Pins for the CPU oracle: closed forms, library special cases, brute force in
+exact integer/rational arithmetic, and the shape arithmetic the paper prints.
+None of these tests touches the HIP library."""
+from fractions import Fraction
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import F32, BF16, F16
+import workloads as wl
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def as_dtype(x, dtype):
+    return wl.to_storage(np.asarray(x, dtype=np.float64), dtype)
+
+
+ALL_DTYPES = [F32, BF16, F16]
+
+
+# --------------------------------------------------------------- matmul core
+
+@pytest.mark.parametrize("dtype", ALL_DTYPES)
+def test_identity_and_permutation(dtype):
+    n = 19
+    B = rng(1).integers(-8, 9, size=(n, 23)).astype(np.float64)
+    I = np.eye(n)
+    assert np.array_equal(oracle.matmul(as_dtype(I, dtype), as_dtype(B, dtype), dtype=dtype), B)
+    perm = rng(2).permutation(n)
+    P = I[perm]
+    assert np.array_equal(oracle.matmul(as_dtype(P, dtype), as_dtype(B, dtype), dtype=dtype), B[perm])
+    # identity on the right: a transposed A operand would fail this one
+    A = rng(3).integers(-8, 9, size=(7, n)).astype(np.float64)
+    assert np.array_equal(oracle.matmul(as_dtype(A, dtype), as_dtype(I, dtype), dtype=dtype), A)
+
+
+@pytest.mark.parametrize("dtype", ALL_DTYPES)
+@pytest.mark.parametrize("mnk", [(5, 7, 1), (3, 4, 513), (64, 64, 2048)])
+def test_all_ones_gives_k(dtype, mnk):
+    m, n, k = mnk
+    out = oracle.matmul(as_dtype(np.ones((m, k)), dtype), as_dtype(np.ones((k, n)), dtype), dtype=dtype)
+    assert out.shape == (m, n) and np.all(out == k)
+
+
+@pytest.mark.parametrize("dtype", ALL_DTYPES)
+def test_rank_one(dtype):
+    u = rng(4).integers(-15, 16, size=11).astype(np.float64)
+    v = rng(5).integers(-15, 16, size=13).astype(np.float64)
+    out = oracle.matmul(as_dtype(u[:, None], dtype), as_dtype(v[None, :], dtype), dtype=dtype)
+    assert np.array_equal(out, np.outer(u, v))
+    # K > 1 with a single live column of A / row of B
+    K = 9
+    A = np.zeros((11, K)); A[:, 6] = u
+    B = rng(6).integers(-3, 4, size=(K, 13)).astype(np.float64); B[6] = v
+    assert np.array_equal(oracle.matmul(as_dtype(A, dtype), as_dtype(B, dtype), dtype=dtype), np.outer(u, v))
+
+
+def brute_matmul_int(A, B):
+    """Exact integer matmul, written j-outer / i-inner with Python ints."""
+    m, k = len(A), len(A[0])
+    n = len(B[0])
+    C = [[0] * n for _ in range(m)]
+    for j in range(n):
+        for i in range(m):
+            C[i][j] = sum(int(A[i][kk]) * int(B[kk][j]) for kk in range(k))
+    return C
+
+
+@pytest.mark.parametrize("dtype", ALL_DTYPES)
+@pytest.mark.parametrize("mnk", [(1, 1, 1), (2, 3, 5), (17, 13, 11), (7, 31, 3)])
+def test_bruteforce_small_integers(dtype, mnk):
+    m, n, k = mnk
+    A = rng(m * 100 + k).integers(-16, 17, size=(m, k))
+    B = rng(n * 100 + k).integers(-16, 17, size=(k, n))
+    want = np.array(brute_matmul_int(A.tolist(), B.tolist()), dtype=np.float64)
+    got = oracle.matmul(as_dtype(A, dtype), as_dtype(B, dtype), dtype=dtype)
+    assert np.array_equal(got, want)
+    # stored transposed
+    got_t = oracle.matmul(as_dtype(A, dtype), as_dtype(B.T.copy(), dtype), dtype=dtype, trans_b=1)
+    assert np.array_equal(got_t, want)
+
+
+@pytest.mark.parametrize("dtype", ALL_DTYPES)
+def test_against_numpy_float64_matmul(dtype):
+    m, n, k = 37, 29, 301
+    A = as_dtype(rng(7).standard_normal((m, k)), dtype)
+    B = as_dtype(rng(8).standard_normal((k, n)), dtype)
+    want = wl.widen(A, dtype) @ wl.widen(B, dtype)
+    got = oracle.matmul(A, B, dtype=dtype)
+    scale = np.abs(wl.widen(A, dtype)) @ np.abs(wl.widen(B, dtype))
+    assert np.max(np.abs(got - want) / scale) < 1e-14
+    # (A.B)^T = B^T.A^T through the transposed-storage flag
+    got2 = oracle.matmul(np.ascontiguousarray(B.T), A, dtype=dtype, trans_b=1)
+    assert got2.shape == (n, m)
+    assert np.max(np.abs(got2 - want.T) / scale.T) < 1e-14
+
+
+def test_exact_fraction_sum_bf16():
+    """Every bf16 product is exact in double; for a short sum the double result
+    must equal the correctly rounded exact rational sum."""
+    m, n, k = 3, 4, 6
+    A = as_dtype(rng(9).standard_normal((m, k)), BF16)
+    B = as_dtype(rng(10).standard_normal((k, n)), BF16)
+    Af, Bf = wl.widen(A, BF16), wl.widen(B, BF16)
+    got = oracle.matmul(A, B, dtype=BF16)
+    for i in range(m):
+        for j in range(n):
+            exact = sum(Fraction(Af[i, kk]) * Fraction(Bf[kk, j]) for kk in range(k))
+            assert abs(Fraction(got[i, j]) - exact) <= abs(exact) * Fraction(1, 2 ** 50)
+
+
+def test_leading_dimensions_ignore_outside_values():
+    M, N, K, lda, ldb = 5, 6, 7, 11, 9
+    Ap = rng(11).integers(-4, 5, size=(M, lda)).astype(np.float32)
+    Bp = rng(12).integers(-4, 5, size=(K, ldb)).astype(np.float32)
+    want = Ap[:, :K].astype(np.float64) @ Bp[:, :N].astype(np.float64)
+    Ap[:, K:] = np.nan
+    Bp[:, N:] = np.nan
+    got = oracle.matmul(Ap, Bp, dtype=F32, M=M, N=N, K=K, lda=lda, ldb=ldb)
+    assert np.array_equal(got, want)
+
+
+def test_linearity():
+    A = as_dtype(rng(13).integers(-5, 6, size=(6, 8)), F16)
+    B1 = rng(14).integers(-5, 6, size=(8, 5))
+    B2 = rng(15).integers(-5, 6, size=(8, 5))
+    s = oracle.matmul(A, as_dtype(B1 + B2, F16), dtype=F16)
+    assert np.array_equal(s, oracle.matmul(A, as_dtype(B1, F16), dtype=F16)
+                          + oracle.matmul(A, as_dtype(B2, F16), dtype=F16))
+
+
+# -------------------------------------------------------------------- batched
+
+def test_batched_is_loop_of_singles_and_broadcast():
+    b, m, n, k = 3, 4, 5, 6
+    A = as_dtype(rng(16).integers(-7, 8, size=(b, m, k)), BF16)
+    B = as_dtype(rng(17).integers(-7, 8, size=(b, k, n)), BF16)
+    got = oracle.batched_matmul(A, B, dtype=BF16)
+    for i in range(b):
+        assert np.array_equal(got[i], oracle.matmul(A[i], B[i], dtype=BF16))
+    # stride 0 on B: every batch entry uses the same matrix
+    got0 = oracle.batched_matmul(A, B[1], dtype=BF16, batch=b, stride_b=0)
+    for i in range(b):
+        assert np.array_equal(got0[i], oracle.matmul(A[i], B[1], dtype=BF16))
+    got1 = oracle.batched_matmul(A[2], B, dtype=BF16, batch=b, stride_a=0)
+    for i in range(b):
+        assert np.array_equal(got1[i], oracle.matmul(A[2], B[i], dtype=BF16))
+
+
+def test_sampled_matmul_matches_full():
+    b, m, n, k = 2, 9, 10, 12
+    A = as_dtype(rng(18).standard_normal((b, m, k)), BF16)
+    B = as_dtype(rng(19).standard_normal((b, k, n)), BF16)
+    bias = rng(20).standard_normal(n).astype(np.float32)
+    full, pre = oracle.batched_matmul(A, B, bias, dtype=BF16, alpha=0.5, epi=oracle.EPI_BIAS_RELU,
+                                      want_preact=True)
+    sb, si, sj = np.array([0, 1, 1, 0]), np.array([0, 8, 3, 5]), np.array([9, 0, 4, 4])
+    o, p = oracle.batched_matmul_at(A, B, bias, sb, si, sj, dtype=BF16, alpha=0.5,
+                                    epi=oracle.EPI_BIAS_RELU, batch=b, M=m, N=n, K=k)
+    assert np.array_equal(o, full[sb, si, sj]) and np.array_equal(p, pre[sb, si, sj])
+
+
+# ------------------------------------------------------------------- epilogue
+
+def test_epilogue_order_scale_then_bias_then_activation():
+    # act(alpha*s + bias): s=2, alpha=0.5, bias=3 -> 4 (alpha*(s+bias) would give 2.5)
+    assert oracle.epilogue(2.0, 3.0, 0.5, oracle.EPI_BIAS) == 4.0
+    assert oracle.epilogue(2.0, 3.0, 0.5, oracle.EPI_NONE) == 1.0          # bias ignored
+    assert oracle.epilogue(-2.0, 0.5, 1.0, oracle.EPI_BIAS_RELU) == 0.0
+    assert oracle.epilogue(-2.0, 2.5, 1.0, oracle.EPI_BIAS_RELU) == 0.5
+    assert oracle.epilogue(-2.0, 2.5, 1.0, oracle.EPI_RELU) == 0.0         # bias ignored
+    assert oracle.epilogue(3.0, 0.0, -1.0, oracle.EPI_RELU) == 0.0
+    assert math.isnan(oracle.epilogue(float("nan"), 0.0, 1.0, oracle.EPI_RELU))
+    assert oracle.epilogue(1.0, 1.0, 1.0, oracle.EPI_BIAS_GELU_TANH) == oracle.gelu_tanh(2.0)
+    assert oracle.epilogue(1.0, 1.0, 1.0, oracle.EPI_GELU_TANH) == oracle.gelu_tanh(1.0)
+
+
+def test_alpha_is_float32():
+    a32 = np.float32(1.0 / math.sqrt(128.0))
+    assert oracle.epilogue(3.0, 0.0, float(a32), oracle.EPI_NONE) == float(a32) * 3.0
+
+
+def test_bias_broadcasts_over_rows_and_alpha_scales():
+    n = 6
+    bias = np.arange(n, dtype=np.float32) - 2.5
+    Z = np.zeros((4, 3), dtype=np.float32)
+    B = rng(21).standard_normal((3, n)).astype(np.float32)
+    out = oracle.matmul(Z, B, bias, dtype=F32, epi=oracle.EPI_BIAS_RELU)
+    assert np.array_equal(out, np.broadcast_to(np.maximum(bias.astype(np.float64), 0), (4, n)))
+    I = np.eye(n, dtype=np.float32)
+    Bn = rng(22).standard_normal((n, n)).astype(np.float32)
+    out = oracle.matmul(I, Bn, bias, dtype=F32, alpha=0.25, epi=oracle.EPI_BIAS, want_preact=True)
+    assert np.array_equal(out[0], 0.25 * Bn.astype(np.float64) + bias)
+    assert np.array_equal(out[0], out[1])
+
+
+def test_gelu_tanh_closed_forms_and_library():
+    g = oracle.gelu_tanh
+    assert g(0.0) == 0.0
+    # value of the tanh approximation at 1, computed from its formula by hand:
+    # 0.5*(1+tanh(0.7978845608*(1.044715))) = 0.8411919906...
+    assert abs(g(1.0) - 0.8411919906082768) < 1e-15
+    for x in [0.1, 0.7, 1.3, 2.9, 6.0]:
+        assert abs((g(x) - g(-x)) - x) < 1e-15 * max(1, x)      # odd part is x/2
+    assert g(12.0) == 12.0 and abs(g(-12.0)) == 0.0
+    xs = np.linspace(0, 8, 400)
+    ys = np.array([g(float(x)) for x in xs])
+    assert np.all(np.diff(ys) > 0)
+    t = torch.linspace(-6, 6, 241, dtype=torch.float64)
+    ref = torch.nn.functional.gelu(t, approximate="tanh").numpy()
+    got = np.array([g(float(x)) for x in t.numpy()])
+    assert np.max(np.abs(got - ref)) < 1e-14
+
+
+# ------------------------------------------------------- widening / rounding
+
+def test_widen_matches_numpy_and_definition():
+    for bits in [0x0000, 0x8000, 0x3C00, 0x0001, 0x03FF, 0x0400, 0x7BFF, 0xFBFF, 0x7C00, 0x3555]:
+        want = float(np.array([bits], dtype=np.uint16).view(np.float16)[0])
+        assert oracle.widen_bits(bits, F16) == want
+    assert math.isnan(oracle.widen_bits(0x7E00, F16))
+    assert oracle.widen_bits(0x3F80, BF16) == 1.0
+    assert oracle.widen_bits(0x3F81, BF16) == 1.0 + 2.0 ** -7
+    assert oracle.widen_bits(0xC000, BF16) == -2.0
+    assert oracle.widen_bits(0x0001, BF16) == 2.0 ** -133
+    assert oracle.widen_bits(0x7F7F, BF16) == (2 - 2.0 ** -7) * 2.0 ** 127
+
+
+def test_bf16_rounding_ties_and_edges():
+    r = oracle.round_bf16
+    assert r(1.0) == 0x3F80
+    assert r(1 + 2.0 ** -8) == 0x3F80            # tie -> even (down)
+    assert r(1 + 3 * 2.0 ** -8) == 0x3F82        # tie -> even (up)
+    assert r(1 + 2.0 ** -8 + 2.0 ** -30) == 0x3F81
+    assert r(-(1 + 3 * 2.0 ** -8)) == 0xBF82
+    assert r(3.4e38) == 0x7F80 and r(-3.4e38) == 0xFF80      # overflow -> inf
+    assert r((2 - 2.0 ** -7) * 2.0 ** 127) == 0x7F7F
+    assert r(2.0 ** -133) == 0x0001 and r(2.0 ** -134) == 0x0000 and r(1.5 * 2.0 ** -133) == 0x0002
+    assert r(float("nan")) & 0x7FC0 == 0x7FC0
+    assert r(0.0) == 0 and r(-0.0) == 0x8000
+
+
+def test_bf16_round_trip_exhaustive():
+    for bits in range(0, 65536):
+        e = (bits >> 7) & 0xFF
+        if e == 0xFF and (bits & 0x7F):
+            continue                                        # NaN payloads
+        assert oracle.round_bf16(oracle.widen_bits(bits, BF16)) == bits
+
+
+def test_f16_rounding_matches_numpy():
+    for bits in range(0, 65536, 7):
+        v = np.array([bits], dtype=np.uint16).view(np.float16)[0]
+        if np.isnan(v):
+            continue
+        assert oracle.round_f16(float(v)) == bits
+    xs = rng(23).standard_normal(4000) * np.exp(rng(24).uniform(-20, 12, 4000))
+    xs = np.concatenate([xs, [65504.0, 65519.9, 65520.0, 1e-8, 5.96e-8, 2.98e-8, 2.9802322387695312e-08]])
+    with np.errstate(over="ignore"):
+        want = xs.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.round_f16(float(x)) for x in xs], dtype=np.uint16)
+    assert np.array_equal(got, want)
+
+
+def test_bf16_rounding_against_exact_rational():
+    xs = rng(25).standard_normal(2000) * np.exp(rng(26).uniform(-30, 30, 2000))
+    for x in xs:
+        got = Fraction(oracle.widen_bits(oracle.round_bf16(float(x)), BF16))
+        e = math.frexp(abs(x))[1]
+        ulp = Fraction(2) ** (e - 8)
+        q = Fraction(float(x)) / ulp
+        fl = q.numerator // q.denominator
+        rem = q - fl
+        n = fl + (1 if (rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2)) else 0)
+        assert got == n * ulp
+
+
+# ------------------------------------------------------------- convolution
+
+def conv_args(x, w, dtype):
+    return as_dtype(x, dtype), as_dtype(w, dtype)
+
+
+@pytest.mark.parametrize("dtype", ALL_DTYPES)
+def test_conv_1x1_is_matmul(dtype):
+    n, H, W, Cin, Cout = 2, 5, 4, 7, 3
+    x = rng(27).integers(-6, 7, size=(n, H, W, Cin)).astype(np.float64)
+    w = rng(28).integers(-6, 7, size=(1, 1, Cin, Cout)).astype(np.float64)
+    xs, ws = conv_args(x, w, dtype)
+    got = oracle.conv2d_nhwc(xs, ws, dtype=dtype)
+    assert np.array_equal(got.reshape(-1, Cout), x.reshape(-1, Cin) @ w.reshape(Cin, Cout))
+
+
+def test_conv_delta_and_shift_filters():
+    n, H, W, C = 1, 6, 7, 3
+    x = rng(29).integers(1, 9, size=(n, H, W, C)).astype(np.float64)
+    w = np.zeros((3, 3, C, C)); w[1, 1] = np.eye(C)
+    xs, ws = conv_args(x, w, F32)
+    assert np.array_equal(oracle.conv2d_nhwc(xs, ws, dtype=F32, pad=(1, 1)), x)
+    # single tap at (kh,kw)=(0,2): y[oh][ow] = x[oh-1][ow+1], zero outside.
+    # A flipped filter (true convolution) or padding on the wrong side fails.
+    w = np.zeros((3, 3, C, C)); w[0, 2] = np.eye(C)
+    want = np.zeros_like(x)
+    want[:, 1:, :-1] = x[:, :-1, 1:]
+    got = oracle.conv2d_nhwc(as_dtype(x, F32), as_dtype(w, F32), dtype=F32, pad=(1, 1))
+    assert np.array_equal(got, want)
+
+
+def test_conv_all_ones_counts_inbounds_taps():
+    H, W, Cin, Cout = 5, 6, 4, 2
+    x = np.ones((1, H, W, Cin)); w = np.ones((3, 3, Cin, Cout))
+    got = oracle.conv2d_nhwc(as_dtype(x, BF16), as_dtype(w, BF16), dtype=BF16, pad=(1, 1))
+    want = np.full((H, W), 9.0)
+    want[0, :] = want[-1, :] = 6; want[:, 0] = want[:, -1] = 6
+    want[0, 0] = want[0, -1] = want[-1, 0] = want[-1, -1] = 4
+    assert np.array_equal(got[0, :, :, 0], want * Cin) and np.array_equal(got[..., 0], got[..., 1])
+
+
+CONV_CASES = [
+    # n, H, W, Cin, Cout, KH, KW, stride, pad, dil
+    (2, 9, 8, 3, 4, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (1, 11, 10, 5, 2, 3, 2, (2, 1), (0, 1), (1, 1)),
+    (1, 13, 12, 2, 3, 3, 3, (2, 2), (2, 1), (2, 2)),
+    (2, 7, 7, 4, 4, 5, 5, (1, 2), (2, 2), (1, 1)),
+    (1, 10, 9, 3, 2, 2, 3, (3, 2), (1, 0), (2, 3)),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_against_torch_float64(case):
+    n, H, W, Cin, Cout, KH, KW, stride, pad, dil = case
+    x = as_dtype(rng(30).standard_normal((n, H, W, Cin)), BF16)
+    w = as_dtype(rng(31).standard_normal((KH, KW, Cin, Cout)), BF16)
+    xt = torch.from_numpy(wl.widen(x, BF16)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(wl.widen(w, BF16)).permute(3, 2, 0, 1)
+    ref = torch.nn.functional.conv2d(xt, wt, stride=stride, padding=pad, dilation=dil)
+    ref = ref.permute(0, 2, 3, 1).numpy()
+    got = oracle.conv2d_nhwc(x, w, dtype=BF16, stride=stride, pad=pad, dil=dil)
+    assert got.shape == ref.shape
+    assert np.max(np.abs(got - ref)) < 1e-12
+
+
+@pytest.mark.parametrize("case", CONV_CASES[:3])
+def test_conv_bruteforce_integers(case):
+    n, H, W, Cin, Cout, KH, KW, stride, pad, dil = case
+    x = rng(32).integers(-5, 6, size=(n, H, W, Cin))
+    w = rng(33).integers(-5, 6, size=(KH, KW, Cin, Cout))
+    got = oracle.conv2d_nhwc(as_dtype(x, F16), as_dtype(w, F16), dtype=F16, stride=stride, pad=pad, dil=dil)
+    OH, OW = got.shape[1:3]
+    xl, wlst = x.tolist(), w.tolist()
+    for b, oh, ow, co in itertools.product(range(n), range(OH), range(OW), range(Cout)):
+        acc = 0
+        for c, kw, kh in itertools.product(range(Cin), range(KW), range(KH)):   # other loop order
+            ih = oh * stride[0] - pad[0] + kh * dil[0]
+            iw = ow * stride[1] - pad[1] + kw * dil[1]
+            if 0 <= ih < H and 0 <= iw < W:
+                acc += xl[b][ih][iw][c] * wlst[kh][kw][c][co]
+        assert got[b, oh, ow, co] == acc
+
+
+def test_conv_epilogue_and_sampled_points():
+    n, H, W, Cin, Cout = 2, 6, 5, 4, 3
+    x = as_dtype(rng(34).standard_normal((n, H, W, Cin)), BF16)
+    w = as_dtype(rng(35).standard_normal((3, 3, Cin, Cout)), BF16)
+    bias = rng(36).standard_normal(Cout).astype(np.float32)
+    plain = oracle.conv2d_nhwc(x, w, dtype=BF16, pad=(1, 1))
+    out, pre = oracle.conv2d_nhwc(x, w, bias, dtype=BF16, pad=(1, 1), alpha=0.5,
+                                  epi=oracle.EPI_BIAS_RELU, want_preact=True)
+    assert np.array_equal(pre, 0.5 * plain + bias.astype(np.float64))
+    assert np.array_equal(out, np.maximum(pre, 0))
+    sn, soh, sow, sco = np.array([0, 1, 1]), np.array([0, 5, 2]), np.array([4, 0, 2]), np.array([2, 1, 0])
+    o, p = oracle.conv2d_nhwc_at(x, w, bias, sn, soh, sow, sco, dtype=BF16, pad=(1, 1), alpha=0.5,
+                                 epi=oracle.EPI_BIAS_RELU)
+    assert np.array_equal(o, out[sn, soh, sow, sco]) and np.array_equal(p, pre[sn, soh, sow, sco])
+
+
+def read_paper_shapes(golden_dir):
+    rows = []
+    with open(f"{golden_dir}/paper_conv_shapes.txt") as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            l, r = line.split("|")
+            rows.append((list(map(int, l.split())), list(map(int, r.split()))))
+    return rows
+
+
+def test_paper_worked_shapes(golden_dir):
+    """Output sizes and GEMM dimensions of the two convolutions worked through
+    in Sec. 4.5 / 4.6 of the paper."""
+    for (n, H, W, Cin, KH, KW, Cout, s, p, d), (OH, OW, gm, gn, gk, blocks) in read_paper_shapes(golden_dir):
+        oh = oracle.conv_out_dim(H, KH, s, p, d)
+        ow = oracle.conv_out_dim(W, KW, s, p, d)
+        assert (oh, ow) == (OH, OW)
+        assert (n * oh * ow, Cout, KH * KW * Cin) == (gm, gn, gk)
+        assert -(-gm // 128) == blocks
+        w = wl.Workload("paper", "conv", BF16, F32, 0, n=n, H=H, W=W, Cin=Cin, Cout=Cout, KH=KH, KW=KW,
+                        stride=(s, s), pad=(p, p), dil=(d, d))
+        assert w.gemm_mnk == (gm, gn, gk)
+
+
+def test_paper_virtual_matmul_index_map():
+    """The paper's 3-d "virtual matmul" nest for the 8x44x44x127 (*) 3x3x127x512
+    stride-2 convolution (Sec. 4.5) reads image[i/441, ((i%441)/21)*2 + (k/127)/3,
+    i*2 - (i/21)*42 + k/127 - ((k/127)/3)*3, k%127] and weights[(k/127)/3,
+    (k/127)%3, k%127, j].  Build that LHS explicitly and multiply with a library
+    matmul; the direct convolution must agree.  (16 of the 512 output channels.)"""
+    n, H, W, Cin, Cout = 8, 44, 44, 127, 16
+    x = as_dtype(rng(37).standard_normal((n, H, W, Cin)), F16)
+    w = as_dtype(rng(38).standard_normal((3, 3, Cin, Cout)), F16)
+    i = np.arange(3528)[:, None]
+    k = np.arange(1143)[None, :]
+    tap = k // 127
+    lhs = wl.widen(x, F16)[i // 441, ((i % 441) // 21) * 2 + tap // 3,
+                           i * 2 - (i // 21) * 42 + tap - (tap // 3) * 3, k % 127]
+    rhs = wl.widen(w, F16)[(k.T // 127) // 3, (k.T // 127) % 3, k.T % 127, np.arange(Cout)[None, :]]
+    want = lhs @ rhs
+    got = oracle.conv2d_nhwc(x, w, dtype=F16, stride=(2, 2))
+    assert got.shape == (8, 21, 21, Cout)
+    scale = np.abs(lhs) @ np.abs(rhs)
+    assert np.max(np.abs(got.reshape(3528, Cout) - want) / scale) < 1e-14
+
+
+# ------------------------------------------------------------ argument checks
+
+def test_oracle_rejects_bad_arguments():
+    A = np.zeros((2, 2), dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.matmul(A, A, None, dtype=F32, epi=oracle.EPI_BIAS)         # bias missing
+    with pytest.raises(ValueError):
+        oracle.matmul(A, A, dtype=F32, K=3, lda=2)                          # lda < K
+    with pytest.raises(TypeError):
+        oracle.matmul(A, A, dtype=BF16)
+    assert oracle.conv_out_dim(2, 5, 1, 0, 1) == -1
+    out = oracle.matmul(np.zeros((0, 3), np.float32), np.zeros((3, 4), np.float32), dtype=F32)
+    assert out.shape == (0, 4)
+    out = oracle.matmul(np.zeros((2, 0), np.float32), np.zeros((0, 4), np.float32),
+                        np.ones(4, np.float32), dtype=F32, epi=oracle.EPI_BIAS)
+    assert np.array_equal(out, np.ones((2, 4)))                             # empty sum + bias

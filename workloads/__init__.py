@@ -1,0 +1,13 @@
+"""Seeded synthetic inputs and workload shapes.
+
+This package holds no arithmetic of the contraction itself: it only draws
+numbers and names shapes, so that both the CPU oracle's tests and the HIP
+path's tests/bench can be fed identical bits.
+"""
+from .gen import (MASTER_SEED, uniform_f64, normal_f64, to_storage, widen,
+                  tensor, DTYPE_F32, DTYPE_BF16, DTYPE_F16)
+from .configs import CONFIGS, Workload, make_inputs
+
+__all__ = ["MASTER_SEED", "uniform_f64", "normal_f64", "to_storage", "widen",
+           "tensor", "DTYPE_F32", "DTYPE_BF16", "DTYPE_F16", "CONFIGS",
+           "Workload", "make_inputs"]
