@@ -1,0 +1,126 @@
+/*
+ * libpbk: fused dense contractions for AMD MI355X (gfx950).
+ *
+ *     out = act(alpha * (A . B) + bias)
+ *
+ * as matmul, batched matmul, and 2-d convolution lowered as an implicit GEMM
+ * (the tile of im2col rows is packed on the fly; the im2col matrix never
+ * exists in memory).  This is the operator the paper's code generator targets:
+ * a tiled matmul/convolution nest with its pointwise tail fused into the
+ * output tile (paper Sec. 4.3, 4.5, 4.6).
+ *
+ * Conventions shared by every entry point
+ *  - All data pointers are DEVICE pointers valid on the device that `stream`
+ *    belongs to.  The library never allocates, frees or keeps them.  The
+ *    output must not alias any input.
+ *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL
+ *    = the default stream) and return; ordering is stream ordering.
+ *  - Matrices are row-major with leading dimensions in ELEMENTS.
+ *  - in_dtype is the element type of A and B (image and weights);
+ *    out_dtype must be PBK_F32 or equal to in_dtype.  bias is always float.
+ *    16-bit inputs are widened exactly, products are accumulated in fp32,
+ *    the epilogue runs in fp32, and the result is rounded once to out_dtype
+ *    (round-to-nearest-even).  PBK_F32 inputs use true fp32 multiply-add.
+ *  - Epilogue: t = alpha * acc (+ bias[n] for the BIAS variants);
+ *    out = t | max(t,0) | 0.5*t*(1+tanh(sqrt(2/pi)*(t+0.044715*t^3))).
+ *    bias must be non-NULL exactly for the BIAS variants' use; it is ignored
+ *    otherwise.
+ *  - Every function returns a pbk_status.  On any status other than PBK_OK
+ *    nothing was launched and the output is untouched.  A dimension of zero
+ *    gives PBK_OK and does nothing (K == 0 still writes act(bias)).
+ *  - Elements outside the M x K / K x N views (beyond K up to lda, etc.) are
+ *    never allowed to influence the result, even if they hold NaN or Inf.
+ *  - Re-entrant; no global mutable state besides a read-only cache of device
+ *    properties.
+ */
+#ifndef PBK_H
+#define PBK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PBK_OK = 0,
+    PBK_ERR_NULL = 1,        /* a required pointer is NULL */
+    PBK_ERR_SHAPE = 2,       /* negative dimension, empty conv output, size overflow */
+    PBK_ERR_STRIDE = 3,      /* leading dimension or batch stride too small */
+    PBK_ERR_ALIGN = 4,       /* pointer not aligned to its element size */
+    PBK_ERR_DTYPE = 5,       /* unknown dtype or unsupported in/out pair */
+    PBK_ERR_EPILOGUE = 6,    /* unknown epilogue, or bias missing */
+    PBK_ERR_UNSUPPORTED = 7, /* valid request this build cannot run */
+    PBK_ERR_HIP = 8          /* the HIP runtime reported an error at launch */
+} pbk_status;
+
+typedef enum { PBK_F32 = 0, PBK_BF16 = 1, PBK_F16 = 2 } pbk_dtype;
+
+typedef enum {
+    PBK_EPI_NONE = 0,
+    PBK_EPI_BIAS = 1,
+    PBK_EPI_RELU = 2,
+    PBK_EPI_BIAS_RELU = 3,
+    PBK_EPI_BIAS_GELU_TANH = 4,
+    PBK_EPI_GELU_TANH = 5
+} pbk_epilogue;
+
+/*
+ * C[M][N] = act(alpha * A[M][K] . B[K][N] + bias[N])          (paper Sec. 4.3/4.6)
+ * A: M x K, lda >= K.  B: K x N with ldb >= N, or if trans_b != 0 stored as
+ * N x K with ldb >= K (B[k][n] = Bt[n][k]).  C: M x N, ldc >= N.
+ */
+pbk_status pbk_matmul(const void* A, const void* B, void* C, const float* bias,
+                      int64_t M, int64_t N, int64_t K,
+                      int64_t lda, int64_t ldb, int64_t ldc,
+                      pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
+                      float alpha, pbk_epilogue epi, void* stream);
+
+/*
+ * `batch` independent matmuls; entry b uses A + b*stride_a, B + b*stride_b,
+ * C + b*stride_c (strides in elements).  stride_a or stride_b may be 0 to
+ * share one operand among all entries; stride_c must be >= (M-1)*ldc + N.
+ * bias[N] is shared by all entries.
+ */
+pbk_status pbk_batched_matmul(const void* A, const void* B, void* C, const float* bias,
+                              int64_t batch, int64_t M, int64_t N, int64_t K,
+                              int64_t lda, int64_t ldb, int64_t ldc,
+                              int64_t stride_a, int64_t stride_b, int64_t stride_c,
+                              pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
+                              float alpha, pbk_epilogue epi, void* stream);
+
+/*
+ * y[N][OH][OW][Cout] = act(alpha * conv(x, w) + bias[Cout])      (paper Sec. 4.5)
+ * x: [N][H][W][Cin] (NHWC, dense).  w: [KH][KW][Cin][Cout] (dense).
+ * Cross-correlation (no filter flip):
+ *   y[n][oh][ow][co] = sum_{kh,kw,c} x[n][oh*stride_h - pad_h + kh*dil_h]
+ *                                       [ow*stride_w - pad_w + kw*dil_w][c] * w[kh][kw][c][co]
+ * with taps outside the image contributing zero, i.e. the GEMM with
+ * M = N*OH*OW rows (n, oh, ow), N = Cout, K = KH*KW*Cin ordered (kh, kw, c).
+ * OH = (H + 2*pad_h - dil_h*(KH-1) - 1) / stride_h + 1 (floor), OW likewise;
+ * an empty output is PBK_ERR_SHAPE.
+ */
+pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* bias,
+                           int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                           int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                           int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                           pbk_dtype in_dtype, pbk_dtype out_dtype,
+                           float alpha, pbk_epilogue epi, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* pbk_status_string(pbk_status s);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int pbk_version(void);
+
+/*
+ * Name of the kernel configuration the most recent successful call ON THIS
+ * THREAD dispatched to (for benchmarks and tests; e.g. "mfma_256x256x64_w2x4",
+ * "generic_64x64").  Never NULL; "" before the first call.
+ */
+const char* pbk_last_kernel(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBK_H */

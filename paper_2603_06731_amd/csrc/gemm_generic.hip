@@ -1,0 +1,152 @@
+// Generic contraction kernel: any dtype, any alignment, any leading dimension,
+// transposed B, and the implicit-GEMM view of a convolution.  True fp32
+// multiply-add on widened inputs.  LDS-tiled 64x64x16, 4x4 outputs per lane.
+// It is the fp32 path and the safety net for shapes the MFMA path declines.
+//
+// Tiling and staging follow the paper's scheme (Sec. 4.3 tiling + fast
+// buffers, Sec. 4.5 on-the-fly packing of the im2col tile, partial tiles
+// zero-filled) at a tile size picked for VALU rather than matrix units.
+#include <hip/hip_runtime.h>
+#include "pbk_problem.h"
+#include "pbk_epilogue.h"
+
+namespace pbk {
+namespace {
+
+constexpr int GT = 64;     // tile edge in M and N
+constexpr int GK = 16;     // tile depth
+constexpr int GPAD = 4;
+
+template <typename T> __device__ __forceinline__ float ld_elem(const T* p, int64_t i) { return (float)p[i]; }
+
+// A(i, k) of the implicit GEMM: im2col element, zero outside the image.
+template <typename T>
+__device__ __forceinline__ float conv_a(const T* x, const ConvGeom& g, int i, int k) {
+    int pix = g.OH * g.OW;
+    int n = i / pix;
+    int r = i - n * pix;
+    int oh = r / g.OW;
+    int ow = r - oh * g.OW;
+    int tap = k / g.Cin;
+    int c = k - tap * g.Cin;
+    int kh = tap / g.KW;
+    int kw = tap - kh * g.KW;
+    int ih = oh * g.stride_h - g.pad_h + kh * g.dil_h;
+    int iw = ow * g.stride_w - g.pad_w + kw * g.dil_w;
+    if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0.0f;
+    return (float)x[(((int64_t)n * g.H + ih) * g.W + iw) * g.Cin + c];
+}
+
+template <typename T, bool CONV>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_m, int tiles_n) {
+    __shared__ float As[GK][GT + GPAD];
+    __shared__ float Bs[GK][GT + GPAD];
+
+    int bid = blockIdx.x;
+    int tn = bid % tiles_n;
+    int rest = bid / tiles_n;
+    int tm = rest % tiles_m;
+    int b = rest / tiles_m;
+    int m0 = tm * GT, n0 = tn * GT;
+
+    const T* A = (const T*)p.A + (int64_t)b * p.stride_a;
+    const T* B = (const T*)p.B + (int64_t)b * p.stride_b;
+
+    int t = threadIdx.x;
+    int tx = t % 16, ty = t / 16;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
+
+    for (int k0 = 0; k0 < p.K; k0 += GK) {
+        // A tile: 64 rows x 16 k; lanes run along k (contiguous in memory)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int e = t + 256 * r;
+            int mm = e / GK, kk = e % GK;
+            int gm = m0 + mm, gk = k0 + kk;
+            float v = 0.0f;
+            if (gm < p.M && gk < p.K) {
+                if (CONV) v = conv_a<T>(A, p.conv, gm, gk);
+                else v = ld_elem<T>(A, (int64_t)gm * p.lda + gk);
+            }
+            As[kk][mm] = v;
+        }
+        // B tile: 16 k x 64 n
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int e = t + 256 * r;
+            int kk, nn;
+            if (p.trans_b) { nn = e / GK; kk = e % GK; }
+            else { kk = e / GT; nn = e % GT; }
+            int gk = k0 + kk, gn = n0 + nn;
+            float v = 0.0f;
+            if (gk < p.K && gn < p.N)
+                v = p.trans_b ? ld_elem<T>(B, (int64_t)gn * p.ldb + gk)
+                              : ld_elem<T>(B, (int64_t)gk * p.ldb + gn);
+            Bs[kk][nn] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < GK; ++kk) {
+            float a[4], bv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], bv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+
+    const bool has_bias = epi_has_bias(p.epi);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int gm = m0 + ty * 4 + i;
+        if (gm >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int gn = n0 + tx * 4 + j;
+            if (gn >= p.N) continue;
+            float bias = has_bias ? p.bias[gn] : 0.0f;
+            float v = apply_epilogue(acc[i][j], p.alpha, bias, p.epi);
+            int64_t o = (int64_t)b * p.stride_c + (int64_t)gm * p.ldc + gn;
+            if (p.out_dtype == DT_F32) ((float*)p.C)[o] = v;
+            else if (p.out_dtype == DT_BF16) ((uint16_t*)p.C)[o] = to_bits16<bf16_t>(v);
+            else ((uint16_t*)p.C)[o] = to_bits16<f16_t>(v);
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_t(const Problem& p, hipStream_t stream) {
+    int tiles_m = (p.M + GT - 1) / GT, tiles_n = (p.N + GT - 1) / GT;
+    long long blocks = (long long)tiles_m * tiles_n * p.batch;
+    if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    if (p.is_conv)
+        hipLaunchKernelGGL((gemm_generic_kernel<T, true>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           p, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((gemm_generic_kernel<T, false>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           p, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_generic(const Problem& p, hipStream_t stream, const char** name) {
+    *name = "generic_64x64x16_fma";
+    switch (p.in_dtype) {
+    case DT_F32: return launch_t<float>(p, stream);
+    case DT_BF16: return launch_t<bf16_t>(p, stream);
+    case DT_F16: return launch_t<f16_t>(p, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace pbk

@@ -1,0 +1,42 @@
+// Eligibility test and tile-configuration choice for the MFMA path.
+#include <cstdlib>
+#include "gemm_mfma_launch.h"
+
+namespace pbk {
+
+static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// The MFMA path moves operands in whole 16-byte pieces (8 elements): bases,
+// leading dimensions, batch strides and K must keep every piece aligned and
+// entirely inside or outside the matrix; likewise N for row-major B and Cin
+// for the convolution (a piece must not straddle two filter taps).
+bool mfma_supported(const Problem& p) {
+    if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16) return false;
+    if (p.K < 8 || p.K % 8) return false;
+    if (!al16(p.A) || !al16(p.B)) return false;
+    if (p.stride_a % 8 || p.stride_b % 8) return false;
+    if (p.is_conv) {
+        if (p.conv.Cin % 8 || p.N % 8) return false;
+    } else {
+        if (p.lda % 8 || p.ldb % 8) return false;
+        if (!p.trans_b && p.N % 8) return false;
+    }
+    return true;
+}
+
+static int choose_config(const Problem& p) {
+    long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
+    if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 0;
+    return 2;
+}
+
+hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name) {
+    int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
+    int group_m = 8;
+    if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) group_m = g; }
+    *name = kMfmaConfigs[cfg].name;
+    return p.in_dtype == DT_BF16 ? launch_mfma_bf16(p, stream, cfg, group_m)
+                                 : launch_mfma_f16(p, stream, cfg, group_m);
+}
+
+}  // namespace pbk

@@ -1,0 +1,73 @@
+// Instantiation and launch of the MFMA kernel for one element type.
+// Included by one translation unit per dtype so they compile in parallel.
+#pragma once
+#include <atomic>
+#include "gemm_mfma_kernel.h"
+
+namespace pbk {
+
+struct MfmaConfig {
+    int id;
+    int bm, bn, bk, wm, wn;
+    const char* name;
+};
+
+// Tile configurations (the static stand-in for the paper's analytical tile
+// size model, Sec. 4.3): id -> workgroup tile and wave grid.
+static const MfmaConfig kMfmaConfigs[] = {
+    {0, 256, 256, 64, 2, 4, "mfma_256x256x64_w2x4"},
+    {1, 256, 256, 64, 2, 2, "mfma_256x256x64_w2x2"},
+    {2, 128, 128, 64, 2, 2, "mfma_128x128x64_w2x2"},
+    {3, 128, 256, 64, 1, 4, "mfma_128x256x64_w1x4"},
+};
+static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool CONV, bool TRANS_B>
+hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
+    constexpr int LDS_BYTES = 2 * (BM * BK * 2 + BN * BK * 2);
+    auto kern = gemm_mfma_kernel<T, BM, BN, BK, WM, WN, CONV, TRANS_B>;
+    static std::atomic<unsigned> attr_done{0};      // bit per device
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    unsigned bit = 1u << (dev & 31);
+    if (!(attr_done.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done.fetch_or(bit, std::memory_order_release);
+    }
+    TileMap tm;
+    tm.tiles_m = (p.M + BM - 1) / BM;
+    tm.tiles_n = (p.N + BN - 1) / BN;
+    tm.tiles_per_batch = tm.tiles_m * tm.tiles_n;
+    long long total = (long long)tm.tiles_per_batch * p.batch;
+    if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    tm.total = (int)total;
+    tm.group_m = group_m < 1 ? 1 : group_m;
+    tm.xcds = 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), LDS_BYTES, stream, p, tm);
+    return hipGetLastError();
+}
+
+template <typename T, int BM, int BN, int BK, int WM, int WN>
+hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
+    if (p.is_conv) return launch_one<T, BM, BN, BK, WM, WN, true, false>(p, stream, group_m);
+    if (p.trans_b) return launch_one<T, BM, BN, BK, WM, WN, false, true>(p, stream, group_m);
+    return launch_one<T, BM, BN, BK, WM, WN, false, false>(p, stream, group_m);
+}
+
+template <typename T>
+hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int group_m) {
+    switch (cfg) {
+    case 0: return launch_modes<T, 256, 256, 64, 2, 4>(p, stream, group_m);
+    case 1: return launch_modes<T, 256, 256, 64, 2, 2>(p, stream, group_m);
+    case 2: return launch_modes<T, 128, 128, 64, 2, 2>(p, stream, group_m);
+    case 3: return launch_modes<T, 128, 256, 64, 1, 4>(p, stream, group_m);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_mfma_bf16(const Problem& p, hipStream_t stream, int cfg, int group_m);
+hipError_t launch_mfma_f16(const Problem& p, hipStream_t stream, int cfg, int group_m);
+
+}  // namespace pbk

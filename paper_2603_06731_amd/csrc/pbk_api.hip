@@ -1,0 +1,165 @@
+// C ABI of libpbk: argument validation and dispatch.  No allocation, no
+// synchronisation; every call enqueues at most one kernel on the caller's stream.
+#include <hip/hip_runtime.h>
+#include <cstdlib>
+#include <cstring>
+#include <climits>
+#include "../../include/pbk.h"
+#include "pbk_problem.h"
+
+namespace {
+
+thread_local const char* g_last_kernel = "";
+
+int64_t elem_size(int dt) { return dt == pbk::DT_F32 ? 4 : 2; }
+
+bool valid_dtype(int dt) { return dt == PBK_F32 || dt == PBK_BF16 || dt == PBK_F16; }
+
+bool aligned(const void* p, int64_t a) { return (reinterpret_cast<uintptr_t>(p) % (uintptr_t)a) == 0; }
+
+// PBK_FORCE_KERNEL: "generic" forces the fallback kernel, "mfma:<id>" forces an
+// MFMA tile configuration (benchmarking aid; unset = automatic choice).
+int forced_choice(int* cfg) {
+    *cfg = -1;
+    const char* e = std::getenv("PBK_FORCE_KERNEL");
+    if (!e || !*e) return 0;
+    if (!std::strcmp(e, "generic")) return 1;
+    if (!std::strncmp(e, "mfma:", 5)) { *cfg = std::atoi(e + 5); return 2; }
+    if (!std::strcmp(e, "mfma")) return 2;
+    return 0;
+}
+
+pbk_status check_common(int in_dtype, int out_dtype, int epi, const float* bias) {
+    if (!valid_dtype(in_dtype) || !valid_dtype(out_dtype)) return PBK_ERR_DTYPE;
+    if (out_dtype != PBK_F32 && out_dtype != in_dtype) return PBK_ERR_DTYPE;
+    if (epi < PBK_EPI_NONE || epi > PBK_EPI_GELU_TANH) return PBK_ERR_EPILOGUE;
+    if (pbk::epi_has_bias(epi) && !bias) return PBK_ERR_EPILOGUE;
+    if (bias && !aligned(bias, 4)) return PBK_ERR_ALIGN;
+    return PBK_OK;
+}
+
+pbk_status dispatch(const pbk::Problem& p, void* stream) {
+    int cfg = -1;
+    int force = forced_choice(&cfg);
+    const char* name = "";
+    hipError_t e;
+    bool can_mfma = pbk::mfma_supported(p);
+    if (force == 2 && !can_mfma) return PBK_ERR_UNSUPPORTED;
+    if (can_mfma && force != 1)
+        e = pbk::launch_mfma(p, (hipStream_t)stream, cfg, &name);
+    else
+        e = pbk::launch_generic(p, (hipStream_t)stream, &name);
+    if (e != hipSuccess) return PBK_ERR_HIP;
+    g_last_kernel = name;
+    return PBK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+pbk_status pbk_batched_matmul(const void* A, const void* B, void* C, const float* bias,
+                              int64_t batch, int64_t M, int64_t N, int64_t K,
+                              int64_t lda, int64_t ldb, int64_t ldc,
+                              int64_t stride_a, int64_t stride_b, int64_t stride_c,
+                              pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
+                              float alpha, pbk_epilogue epi, void* stream) {
+    pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
+    if (s != PBK_OK) return s;
+    if (batch < 0 || M < 0 || N < 0 || K < 0) return PBK_ERR_SHAPE;
+    if (M > INT_MAX || N > INT_MAX || K > INT_MAX || batch > INT_MAX) return PBK_ERR_SHAPE;
+    if (batch == 0 || M == 0 || N == 0) return PBK_OK;
+    if (!C || (K > 0 && (!A || !B))) return PBK_ERR_NULL;
+    if (lda < K || ldc < N || ldb < (trans_b ? K : N)) return PBK_ERR_STRIDE;
+    if (stride_a < 0 || stride_b < 0 || stride_c < 0) return PBK_ERR_STRIDE;
+    if (batch > 1 && stride_c < (M - 1) * ldc + N) return PBK_ERR_STRIDE;
+    if (!aligned(A, elem_size(in_dtype)) || !aligned(B, elem_size(in_dtype)) ||
+        !aligned(C, elem_size(out_dtype)))
+        return PBK_ERR_ALIGN;
+
+    pbk::Problem p{};
+    p.A = A; p.B = B; p.C = C; p.bias = bias;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K; p.batch = (int)batch;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
+    p.in_dtype = in_dtype; p.out_dtype = out_dtype;
+    p.trans_b = trans_b ? 1 : 0;
+    p.is_conv = 0;
+    p.epi = epi; p.alpha = alpha;
+    return dispatch(p, stream);
+}
+
+pbk_status pbk_matmul(const void* A, const void* B, void* C, const float* bias,
+                      int64_t M, int64_t N, int64_t K,
+                      int64_t lda, int64_t ldb, int64_t ldc,
+                      pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
+                      float alpha, pbk_epilogue epi, void* stream) {
+    return pbk_batched_matmul(A, B, C, bias, 1, M, N, K, lda, ldb, ldc, 0, 0, 0,
+                              in_dtype, out_dtype, trans_b, alpha, epi, stream);
+}
+
+pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* bias,
+                           int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                           int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                           int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                           pbk_dtype in_dtype, pbk_dtype out_dtype,
+                           float alpha, pbk_epilogue epi, void* stream) {
+    pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
+    if (s != PBK_OK) return s;
+    if (N < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 1 || KH < 1 || KW < 1) return PBK_ERR_SHAPE;
+    if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
+        return PBK_ERR_SHAPE;
+    const int64_t lim = 1 << 24;   // keeps every 32-bit index computation in range
+    if (H > lim || W > lim || Cin > lim || Cout > lim || KH > 4096 || KW > 4096 ||
+        stride_h > 4096 || stride_w > 4096 || pad_h > lim || pad_w > lim || dil_h > 4096 || dil_w > 4096)
+        return PBK_ERR_SHAPE;
+    int64_t span_h = H + 2 * pad_h - dil_h * (KH - 1) - 1;
+    int64_t span_w = W + 2 * pad_w - dil_w * (KW - 1) - 1;
+    if (span_h < 0 || span_w < 0) return PBK_ERR_SHAPE;
+    int64_t OH = span_h / stride_h + 1, OW = span_w / stride_w + 1;
+    if (N == 0) return PBK_OK;
+    if (!x || !w || !y) return PBK_ERR_NULL;
+    int64_t gm = N * OH * OW, gk = KH * KW * Cin;
+    if (gm > INT_MAX || gk > INT_MAX || N * H * W > INT_MAX) return PBK_ERR_SHAPE;
+    if (!aligned(x, elem_size(in_dtype)) || !aligned(w, elem_size(in_dtype)) ||
+        !aligned(y, elem_size(out_dtype)))
+        return PBK_ERR_ALIGN;
+
+    pbk::Problem p{};
+    p.A = x; p.B = w; p.C = y; p.bias = bias;
+    p.M = (int)gm; p.N = (int)Cout; p.K = (int)gk; p.batch = 1;
+    p.lda = gk;            // of the virtual im2col matrix; never dereferenced as such
+    p.ldb = Cout; p.ldc = Cout;
+    p.in_dtype = in_dtype; p.out_dtype = out_dtype;
+    p.trans_b = 0;
+    p.is_conv = 1;
+    p.epi = epi; p.alpha = alpha;
+    p.conv.H = (int)H; p.conv.W = (int)W; p.conv.Cin = (int)Cin;
+    p.conv.OH = (int)OH; p.conv.OW = (int)OW;
+    p.conv.KH = (int)KH; p.conv.KW = (int)KW;
+    p.conv.stride_h = (int)stride_h; p.conv.stride_w = (int)stride_w;
+    p.conv.pad_h = (int)pad_h; p.conv.pad_w = (int)pad_w;
+    p.conv.dil_h = (int)dil_h; p.conv.dil_w = (int)dil_w;
+    return dispatch(p, stream);
+}
+
+const char* pbk_status_string(pbk_status s) {
+    switch (s) {
+    case PBK_OK: return "ok";
+    case PBK_ERR_NULL: return "required pointer is NULL";
+    case PBK_ERR_SHAPE: return "invalid shape";
+    case PBK_ERR_STRIDE: return "leading dimension or batch stride too small";
+    case PBK_ERR_ALIGN: return "pointer not aligned to its element size";
+    case PBK_ERR_DTYPE: return "unsupported dtype combination";
+    case PBK_ERR_EPILOGUE: return "unknown epilogue or missing bias";
+    case PBK_ERR_UNSUPPORTED: return "request not supported by this build";
+    case PBK_ERR_HIP: return "HIP runtime error at launch";
+    default: return "unknown status";
+    }
+}
+
+int pbk_version(void) { return 100; }
+
+const char* pbk_last_kernel(void) { return g_last_kernel; }
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Fused pointwise tail applied to fp32 accumulators in registers, and the
+// single rounding to the output type (paper Sec. 4.3: pointwise consumers are
+// fused into the copy-out of the tiled nest; here they run before any store).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "pbk_problem.h"
+
+namespace pbk {
+
+typedef __bf16 bf16_t;
+typedef _Float16 f16_t;
+
+__device__ __forceinline__ float gelu_tanh_f32(float t) {
+    // 0.5*t*(1+tanh(u)), u = sqrt(2/pi)*(t + 0.044715 t^3); tanh(u) = 1 - 2/(exp(2u)+1)
+    const float c = 0.7978845608028654f;
+    float u = c * (t + 0.044715f * t * t * t);
+    float e = __expf(2.0f * u);
+    float th = 1.0f - 2.0f / (e + 1.0f);
+    return 0.5f * t * (1.0f + th);
+}
+
+// t = alpha*acc + bias ; act(t).  `bias` must be 0 when the epilogue has none.
+__device__ __forceinline__ float apply_epilogue(float acc, float alpha, float bias, int epi) {
+    float t = fmaf(alpha, acc, bias);
+    switch (epi) {
+    case EPI_RELU:
+    case EPI_BIAS_RELU:
+        return fmaxf(t, 0.0f);
+    case EPI_BIAS_GELU_TANH:
+    case EPI_GELU_TANH:
+        return gelu_tanh_f32(t);
+    default:
+        return t;
+    }
+}
+
+// fp32 -> 16-bit storage, round to nearest even (hardware conversions).
+template <typename T> __device__ __forceinline__ uint16_t to_bits16(float v);
+template <> __device__ __forceinline__ uint16_t to_bits16<bf16_t>(float v) {
+    return __builtin_bit_cast(uint16_t, (bf16_t)v);
+}
+template <> __device__ __forceinline__ uint16_t to_bits16<f16_t>(float v) {
+    return __builtin_bit_cast(uint16_t, (f16_t)v);
+}
+
+template <typename T> __device__ __forceinline__ float widen(T v) { return (float)v; }
+
+}  // namespace pbk

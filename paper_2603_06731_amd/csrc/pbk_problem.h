@@ -1,0 +1,49 @@
+// Internal description of one contraction, shared by the dispatcher and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pbk {
+
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+enum : int { EPI_NONE = 0, EPI_BIAS = 1, EPI_RELU = 2, EPI_BIAS_RELU = 3,
+             EPI_BIAS_GELU_TANH = 4, EPI_GELU_TANH = 5 };
+
+// Geometry of the convolution whose im2col rows form the A operand
+// (paper Sec. 4.5: row i = (n, oh, ow), column k = (kh, kw, c)).
+struct ConvGeom {
+    int H, W, Cin;
+    int OH, OW;
+    int KH, KW;
+    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+};
+
+struct Problem {
+    const void* A;        // M x K (lda), or the NHWC image when is_conv
+    const void* B;        // K x N (ldb), or N x K (ldb) when trans_b
+    void* C;              // M x N (ldc)
+    const float* bias;    // [N] or nullptr
+    int M, N, K, batch;
+    int64_t lda, ldb, ldc;
+    int64_t stride_a, stride_b, stride_c;   // elements between batch entries
+    int in_dtype, out_dtype;
+    int trans_b;
+    int is_conv;
+    int epi;
+    float alpha;
+    ConvGeom conv;
+};
+
+__host__ __device__ inline bool epi_has_bias(int epi) {
+    return epi == EPI_BIAS || epi == EPI_BIAS_RELU || epi == EPI_BIAS_GELU_TANH;
+}
+
+// Launchers.  Each returns hipSuccess or the launch error; `name` receives a
+// static string naming the configuration that ran.
+hipError_t launch_generic(const Problem& p, hipStream_t stream, const char** name);
+
+// Returns false if this problem cannot take the MFMA path (alignment, dtype).
+bool mfma_supported(const Problem& p);
+hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name);
+
+}  // namespace pbk

@@ -1,0 +1,83 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects invalid arguments before any
+launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pbk():
+    import paper_2603_06731_amd as m
+    if not os.path.exists(m.lib_path()):
+        from paper_2603_06731_amd import build
+        build.build()
+    return m
+
+
+def declared_symbols():
+    src = open(os.path.join(ROOT, "include", "pbk.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(pbk_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_header_symbols_are_exported(pbk):
+    names = declared_symbols()
+    assert set(names) == set(pbk.EXPORTED_SYMBOLS)
+    L = ctypes.CDLL(pbk.lib_path())
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_strings(pbk):
+    assert pbk.pbk_version() >= 100
+    seen = {pbk.pbk_status_string(s) for s in range(9)}
+    assert len(seen) == 9 and pbk.pbk_status_string(0) == "ok"
+    assert pbk.pbk_status_string(99) == "unknown status"
+
+
+def test_matmul_argument_errors(pbk):
+    F32, BF16, F16 = 0, 1, 2
+    P = 0x1000           # fake, aligned, never dereferenced: every call below fails validation
+    mm = pbk.pbk_matmul
+    assert mm(P, P, P, None, -1, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 0) == 2          # shape
+    assert mm(P, P, P, None, 2, 2, 2, 1, 2, 2, F32, F32, 0, 1.0, 0) == 3           # lda < K
+    assert mm(P, P, P, None, 2, 4, 2, 2, 2, 4, F32, F32, 0, 1.0, 0) == 3           # ldb < N
+    assert mm(P, P, P, None, 2, 4, 3, 3, 2, 4, F32, F32, 1, 1.0, 0) == 3           # ldb < K (trans)
+    assert mm(P, P, P, None, 2, 4, 2, 2, 4, 3, F32, F32, 0, 1.0, 0) == 3           # ldc < N
+    assert mm(None, P, P, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 0) == 1        # null A
+    assert mm(P, P, None, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 0) == 1        # null C
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, 7, F32, 0, 1.0, 0) == 5             # dtype
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, BF16, F16, 0, 1.0, 0) == 5          # in/out pair
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, F32, BF16, 0, 1.0, 0) == 5
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 9) == 6           # epilogue
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 3) == 6           # bias missing
+    assert mm(P + 2, P, P, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 0) == 4       # alignment
+    assert mm(P, P, P + 1, None, 2, 2, 2, 2, 2, 2, BF16, BF16, 0, 1.0, 0) == 4
+    assert mm(P, P, P, None, 0, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 0) == 0           # empty: ok, no launch
+
+
+def test_batched_argument_errors(pbk):
+    P = 0x1000
+    bm = pbk.pbk_batched_matmul
+    assert bm(P, P, P, None, 2, 4, 4, 4, 4, 4, 4, 16, 16, 15, 1, 1, 0, 1.0, 0) == 3   # stride_c overlaps
+    assert bm(P, P, P, None, 2, 4, 4, 4, 4, 4, 4, -1, 16, 16, 1, 1, 0, 1.0, 0) == 3
+    assert bm(P, P, P, None, -2, 4, 4, 4, 4, 4, 4, 16, 16, 16, 1, 1, 0, 1.0, 0) == 2
+    assert bm(P, P, P, None, 0, 4, 4, 4, 4, 4, 4, 16, 16, 16, 1, 1, 0, 1.0, 0) == 0
+
+
+def test_conv_argument_errors(pbk):
+    P = 0x1000
+    cv = pbk.pbk_conv2d_nhwc
+    ok_tail = (1, 1, 1.0, 0)
+    assert cv(P, P, P, None, 1, 2, 2, 8, 8, 3, 3, 1, 1, 0, 0, 1, 1, *ok_tail) == 2    # empty output
+    assert cv(P, P, P, None, 1, 8, 8, 8, 8, 3, 3, 0, 1, 0, 0, 1, 1, *ok_tail) == 2    # stride 0
+    assert cv(P, P, P, None, 1, 8, 8, 8, 8, 3, 3, 1, 1, -1, 0, 1, 1, *ok_tail) == 2   # negative pad
+    assert cv(P, P, P, None, 1, 8, 8, 0, 8, 3, 3, 1, 1, 0, 0, 1, 1, *ok_tail) == 2    # Cin 0
+    assert cv(None, P, P, None, 1, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 1, 1, *ok_tail) == 1
+    assert cv(P, P, P, None, 1, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 1, 1, 1, 1, 1.0, 1) == 6  # bias missing
+    assert cv(P, P, P, None, 0, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 1, 1, *ok_tail) == 0    # no images

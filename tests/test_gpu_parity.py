@@ -1,0 +1,251 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on seeded
+inputs.  Small cases are compared element by element; the full-size workloads
+are compared on sampled outputs the oracle computes one by one."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from workloads import configs as C
+import pbk_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+BF16, F16, F32 = wl.DTYPE_BF16, wl.DTYPE_F16, wl.DTYPE_F32
+MFMA_CONFIGS = [0, 1, 2, 3]
+
+
+def tol_for(w):
+    return T.TOL_F32 if w.in_dtype == F32 else T.TOL_16BIT
+
+
+def tight_for(w):
+    if w.in_dtype == F32:
+        return T.TOL_F32
+    return T.TIGHT[w.out_dtype]
+
+
+def check_full(w, force=None, expect_kernel=None):
+    import paper_2603_06731_amd as pbk
+    host = wl.make_inputs(w)
+    dev = T.upload(host)
+    with T.forced_kernel(force):
+        st, out = T.run_workload(w, dev)
+    assert st == 0, pbk.pbk_status_string(st)
+    if expect_kernel:
+        assert expect_kernel in pbk.pbk_last_kernel(), pbk.pbk_last_kernel()
+    ref, pre = T.oracle_full(w, host)
+    got = T.to_host_f64(out, w.out_dtype).reshape(ref.shape)
+    err = T.rel_err(got, ref, pre)
+    print(f"{w.name} force={force} kernel={pbk.pbk_last_kernel()} err={err:.3e}", flush=True)
+    assert err <= tol_for(w), (w.name, force, err)
+    assert err <= tight_for(w), (w.name, force, err)
+    return err
+
+
+# --------------------------------------------------------------- matmul, small
+
+SMALL_MM = [
+    # M, N, K  (several tiles, ragged tails in M and N, K not a multiple of the k-tile)
+    (300, 264, 200),
+    (256, 256, 64),
+    (520, 136, 72),
+    (33, 520, 136),
+    (64, 8, 8),
+]
+
+
+@pytest.mark.parametrize("cfg", MFMA_CONFIGS)
+@pytest.mark.parametrize("mnk", SMALL_MM)
+def test_matmul_bf16_mfma_configs(cfg, mnk):
+    m, n, k = mnk
+    w = wl.Workload(f"mm_{m}x{n}x{k}", "matmul", BF16, BF16, C.EPI_BIAS_RELU, M=m, N=n, K=k,
+                    dist_b=("normal", 1.0 / np.sqrt(k)), dist_bias=("normal", 0.5))
+    check_full(w, force=f"mfma:{cfg}", expect_kernel="mfma")
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("out_dtype", ["same", "f32"])
+@pytest.mark.parametrize("epi", [C.EPI_NONE, C.EPI_BIAS, C.EPI_RELU, C.EPI_BIAS_RELU,
+                                 C.EPI_BIAS_GELU_TANH, C.EPI_GELU_TANH])
+def test_matmul_epilogues_and_dtypes(dtype, out_dtype, epi):
+    od = dtype if out_dtype == "same" else F32
+    w = wl.Workload("mm_epi", "matmul", dtype, od, epi, alpha=0.75, M=200, N=264, K=136,
+                    dist_b=("normal", 1.0 / np.sqrt(136)), dist_bias=("normal", 0.5))
+    check_full(w, expect_kernel="mfma")
+
+
+@pytest.mark.parametrize("cfg", MFMA_CONFIGS)
+@pytest.mark.parametrize("dtype", [BF16, F16])
+def test_matmul_trans_b(cfg, dtype):
+    w = wl.Workload("mm_tb", "matmul", dtype, dtype, C.EPI_BIAS, M=264, N=301, K=200, trans_b=1,
+                    dist_b=("normal", 1.0 / np.sqrt(200)))
+    check_full(w, force=f"mfma:{cfg}", expect_kernel="mfma")
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16])
+@pytest.mark.parametrize("mnk", [(67, 45, 33), (1, 1, 1), (130, 129, 70), (5, 300, 7)])
+@pytest.mark.parametrize("trans_b", [0, 1])
+def test_matmul_generic_odd_shapes(dtype, mnk, trans_b):
+    m, n, k = mnk
+    w = wl.Workload("mm_odd", "matmul", dtype, dtype, C.EPI_BIAS_GELU_TANH, alpha=0.5, M=m, N=n, K=k,
+                    trans_b=trans_b, dist_b=("normal", 1.0 / np.sqrt(k)))
+    check_full(w, expect_kernel="generic")
+
+
+def test_cfg1_fp32_256():
+    check_full(wl.CONFIGS["cfg1_f32_256"])
+
+
+# ------------------------------------------------------------------- batched
+
+@pytest.mark.parametrize("trans_b", [0, 1])
+def test_batched_small(trans_b):
+    w = wl.Workload("bmm", "batched", BF16, BF16, C.EPI_NONE, alpha=float(np.float32(1 / np.sqrt(128))),
+                    batch=5, M=264, N=200, K=128, trans_b=trans_b)
+    check_full(w, expect_kernel="mfma")
+
+
+def test_batched_broadcast_b():
+    import paper_2603_06731_amd as pbk
+    import oracle
+    batch, m, n, k = 3, 136, 264, 72
+    a = wl.tensor((batch, m, k), BF16, 1, "normal")
+    b = wl.tensor((k, n), BF16, 2, "normal", 0.1)
+    da, db = T.to_device(a), T.to_device(b)
+    out = T.device_empty(batch * m * n, BF16)
+    st = pbk.pbk_batched_matmul(da, db, out, None, batch, m, n, k, k, n, n, m * k, 0, m * n,
+                                BF16, BF16, 0, 1.0, C.EPI_NONE)
+    assert st == 0
+    ref, pre = oracle.batched_matmul(a, b, None, dtype=BF16, batch=batch, stride_b=0, want_preact=True)
+    err = T.rel_err(T.to_host_f64(out, BF16).reshape(ref.shape), ref, pre)
+    assert err <= T.TIGHT[BF16], err
+
+
+# ---------------------------------------------------------------------- conv
+
+CONV_SMALL = [
+    # n, H, W, Cin, Cout, KH, KW, stride, pad, dil
+    (2, 14, 14, 32, 64, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (1, 23, 21, 16, 136, 3, 3, (2, 2), (0, 0), (1, 1)),
+    (2, 17, 19, 8, 264, 5, 3, (1, 2), (2, 1), (2, 1)),
+    (3, 9, 9, 64, 8, 1, 1, (1, 1), (0, 0), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", CONV_SMALL)
+@pytest.mark.parametrize("cfg", [None, 0, 2, 3])
+def test_conv_small_mfma(case, cfg):
+    n, H, W, Cin, Cout, KH, KW, stride, pad, dil = case
+    w = wl.Workload("conv_s", "conv", BF16, BF16, C.EPI_BIAS_RELU, n=n, H=H, W=W, Cin=Cin, Cout=Cout,
+                    KH=KH, KW=KW, stride=stride, pad=pad, dil=dil,
+                    dist_b=("normal", float(np.sqrt(2.0 / (KH * KW * Cin)))))
+    check_full(w, force=None if cfg is None else f"mfma:{cfg}", expect_kernel="mfma")
+
+
+@pytest.mark.parametrize("dtype,out_dtype", [(F16, F32), (F32, F32), (BF16, BF16)])
+def test_conv_generic_tiny_channels(dtype, out_dtype):
+    # Cin = 3, Cout = 3, 5x5 filter: the shape family of the paper's second worked example
+    w = wl.Workload("conv_c3", "conv", dtype, out_dtype, C.EPI_BIAS, n=1, H=40, W=36, Cin=3, Cout=3,
+                    KH=5, KW=5, dist_b=("normal", 0.2))
+    check_full(w, expect_kernel="generic")
+
+
+def test_conv_paper_example_shape_reduced():
+    # stride-2 3x3 over 127 channels (paper's first worked example, fewer images/outputs)
+    w = wl.Workload("conv_p1", "conv", F16, F32, C.EPI_NONE, n=2, H=44, W=44, Cin=127, Cout=24,
+                    KH=3, KW=3, stride=(2, 2), dist_b=("normal", 0.03))
+    check_full(w, expect_kernel="generic")
+
+
+# ---------------------------------------------------- full-size, sampled outputs
+
+@pytest.mark.parametrize("name", ["cfg2_bf16_8192", "cfg3_bf16_attn_scores", "cfg4_bf16_mlp",
+                                  "cfg5_bf16_conv3x3"])
+def test_full_size_sampled(name):
+    import paper_2603_06731_amd as pbk
+    w = wl.CONFIGS[name]
+    host = wl.make_inputs(w)
+    dev = T.upload(host)
+    st, out = T.run_workload(w, dev)
+    assert st == 0
+    kern = pbk.pbk_last_kernel()
+    b, i, j = T.sample_coords(w, 3000)
+    ref, pre = T.oracle_sampled(w, host, b, i, j)
+    got = T.gather_output(out, w, b, i, j)
+    err = T.rel_err(got, ref, pre)
+    print(f"{name} kernel={kern} samples={len(i)} err={err:.3e}", flush=True)
+    assert "mfma" in kern
+    assert err <= T.TOL_16BIT and err <= T.TIGHT[w.out_dtype], err
+    if name == "cfg2_bf16_8192":
+        # bias dominates that output; also check the bare contraction
+        w2 = wl.Workload("cfg2_noepi", "matmul", BF16, BF16, C.EPI_NONE, M=w.M, N=w.N, K=w.K,
+                         dist_a=w.dist_a, dist_b=w.dist_b)
+        st, out2 = T.run_workload(w2, {"a": dev["a"], "b": dev["b"], "bias": None})
+        assert st == 0
+        ref2, pre2 = T.oracle_sampled(w2, {"a": host["a"], "b": host["b"], "bias": None}, b, i, j)
+        err2 = T.rel_err(T.gather_output(out2, w2, b, i, j), ref2, pre2)
+        print(f"cfg2 without epilogue err={err2:.3e}", flush=True)
+        assert err2 <= T.TIGHT[BF16], err2
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_views_ignore_nan_outside_and_guard_band_survives():
+    import paper_2603_06731_amd as pbk
+    import oracle
+    M, N, K, lda, ldb, ldc = 136, 264, 72, 96, 280, 272
+    a = wl.tensor((M, lda), BF16, 1, "normal")
+    b = wl.tensor((K, ldb), BF16, 2, "normal", 0.1)
+    a[:, K:] = 0x7FC0            # NaN beyond K
+    b[:, N:] = 0x7FC0            # NaN beyond N
+    da, db = T.to_device(a), T.to_device(b)
+    sentinel = 0x5A5A
+    out = T.device_empty(M * ldc + 64, BF16, fill=np.array(sentinel, dtype=np.uint16).view(np.int16).item())
+    for force in ("mfma:0", "mfma:2", "generic"):
+        with T.forced_kernel(force):
+            st = pbk.pbk_matmul(da, db, out, None, M, N, K, lda, ldb, ldc, BF16, BF16, 0, 1.0, C.EPI_NONE)
+        assert st == 0
+        raw = out.cpu().numpy().view(np.uint16)
+        body = raw[:M * ldc].reshape(M, ldc)
+        assert np.all(body[:, N:] == sentinel) and np.all(raw[M * ldc:] == sentinel)
+        ref, pre = oracle.matmul(a, b, None, dtype=BF16, M=M, N=N, K=K, lda=lda, ldb=ldb, want_preact=True)
+        got = wl.widen(np.ascontiguousarray(body[:, :N]), BF16)
+        assert T.rel_err(got, ref, pre) <= T.TIGHT[BF16], force
+
+
+def test_run_to_run_bit_exact():
+    w = wl.Workload("det", "matmul", BF16, BF16, C.EPI_BIAS_GELU_TANH, M=520, N=520, K=520,
+                    dist_b=("normal", 0.05))
+    dev = T.upload(wl.make_inputs(w))
+    outs = []
+    for _ in range(3):
+        st, out = T.run_workload(w, dev)
+        assert st == 0
+        outs.append(out.cpu().numpy().copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_zero_sizes_and_k_zero():
+    import paper_2603_06731_amd as pbk
+    out = T.device_empty(16, F32, fill=7.0)
+    assert pbk.pbk_matmul(None, None, out, None, 0, 4, 4, 4, 4, 4, F32, F32, 0, 1.0, 0) == 0
+    assert pbk.pbk_matmul(None, None, out, None, 4, 0, 4, 4, 4, 4, F32, F32, 0, 1.0, 0) == 0
+    assert np.all(out.cpu().numpy() == 7.0)
+    bias = T.to_device(np.array([1.0, -2.0, 3.0, -4.0], dtype=np.float32))
+    assert pbk.pbk_matmul(None, None, out, bias, 4, 4, 0, 4, 4, 4, F32, F32, 0, 1.0, C.EPI_BIAS_RELU) == 0
+    assert np.array_equal(out.cpu().numpy().reshape(4, 4), np.tile([1.0, 0.0, 3.0, 0.0], (4, 1)))
+
+
+def test_non_default_stream():
+    import torch
+    w = wl.Workload("stream", "matmul", F16, F16, C.EPI_RELU, M=264, N=264, K=264, dist_b=("normal", 0.06))
+    host = wl.make_inputs(w)
+    dev = T.upload(host)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        st, out = T.run_workload(w, dev, stream=s)
+    s.synchronize()
+    assert st == 0
+    ref, pre = T.oracle_full(w, host)
+    assert T.rel_err(T.to_host_f64(out, F16).reshape(ref.shape), ref, pre) <= T.TIGHT[F16]
