@@ -161,6 +161,9 @@ def main():
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--all", action="store_true", help="also time the other workloads (table on stderr)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a 1 GiB device-to-device copy (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the contraction shards by output tiles without "
@@ -173,6 +176,16 @@ def main():
         sys.exit("bench.py: no GPU visible")
     pbk.lib()       # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": args.steps}))
+        return
 
     w = wl.CONFIGS[args.workload]
     r = time_workload(w, args.steps, args.warmup)
