@@ -15,12 +15,19 @@ bool mfma_supported(const Problem& p) {
     if (p.K < 8 || p.K % 8) return false;
     if (!al16(p.A) || !al16(p.B)) return false;
     if (p.stride_a % 8 || p.stride_b % 8) return false;
+    // per-lane buffer offsets are 32-bit and must stay below 2^31
+    const int64_t lim = (int64_t)1 << 31;
     if (p.is_conv) {
         if (p.conv.Cin % 8 || p.N % 8) return false;
+        int64_t img = (int64_t)(p.M / (p.conv.OH * p.conv.OW)) * p.conv.H * p.conv.W * p.conv.Cin * 2;
+        int64_t halo = ((int64_t)p.conv.pad_h * p.conv.W + p.conv.pad_w + p.conv.W) * p.conv.Cin * 2;
+        if (img + halo >= lim) return false;
     } else {
         if (p.lda % 8 || p.ldb % 8) return false;
         if (!p.trans_b && p.N % 8) return false;
+        if (256 * p.lda * 2 + 256 >= lim) return false;
     }
+    if (256 * p.ldb * 2 + 1024 >= lim) return false;
     return true;
 }
 

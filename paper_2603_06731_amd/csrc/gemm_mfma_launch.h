@@ -22,10 +22,10 @@ static const MfmaConfig kMfmaConfigs[] = {
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool CONV, bool TRANS_B>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE>
 hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     constexpr int LDS_BYTES = 2 * (BM * BK * 2 + BN * BK * 2);
-    auto kern = gemm_mfma_kernel<T, BM, BN, BK, WM, WN, CONV, TRANS_B>;
+    auto kern = gemm_mfma_kernel<T, BM, BN, BK, WM, WN, MODE>;
     static std::atomic<unsigned> attr_done{0};      // bit per device
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -51,9 +51,9 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
 
 template <typename T, int BM, int BN, int BK, int WM, int WN>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
-    if (p.is_conv) return launch_one<T, BM, BN, BK, WM, WN, true, false>(p, stream, group_m);
-    if (p.trans_b) return launch_one<T, BM, BN, BK, WM, WN, false, true>(p, stream, group_m);
-    return launch_one<T, BM, BN, BK, WM, WN, false, false>(p, stream, group_m);
+    if (p.is_conv) return launch_one<T, BM, BN, BK, WM, WN, MODE_CONV>(p, stream, group_m);
+    if (p.trans_b) return launch_one<T, BM, BN, BK, WM, WN, MODE_TRANS_B>(p, stream, group_m);
+    return launch_one<T, BM, BN, BK, WM, WN, MODE_DENSE>(p, stream, group_m);
 }
 
 template <typename T>
