@@ -42,8 +42,10 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
     int group_m = 8;
     if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) group_m = g; }
     *name = kMfmaConfigs[cfg].name;
-    return p.in_dtype == DT_BF16 ? launch_mfma_bf16(p, stream, cfg, group_m)
-                                 : launch_mfma_f16(p, stream, cfg, group_m);
+    Problem q = p;
+    if (const char* e = std::getenv("PBK_DEBUG")) q.debug = std::atoi(e);
+    return p.in_dtype == DT_BF16 ? launch_mfma_bf16(q, stream, cfg, group_m)
+                                 : launch_mfma_f16(q, stream, cfg, group_m);
 }
 
 }  // namespace pbk

@@ -131,7 +131,160 @@ __device__ __forceinline__ unsigned lds_addr_of(const char* p) {
     return (unsigned)(uintptr_t)PBK_LDS_PTR(const char, p);
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE>
+template <int V> struct IntTag { static constexpr int value = V; };
+struct TailYes { static constexpr bool value = true; };
+struct TailNo { static constexpr bool value = false; };
+
+// Two floats -> two 16-bit values packed in one dword (round to nearest even).
+template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b);
+template <> __device__ __forceinline__ uint32_t pack2<bf16_t>(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+template <> __device__ __forceinline__ uint32_t pack2<f16_t>(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
+// Epilogue of one wave: its WTM x WTN register tile -> global memory.
+template <typename T, int FM, int FN, int WTM, int WTN, int LDS_PER_WAVE>
+struct EpiCtx {
+    const Problem& p;
+    f32x16 (&acc)[FM][FN];
+    char* wlds;            // this wave's private LDS slice
+    int row0, col0;        // global coordinates of the wave tile's corner
+    int lane;
+    int64_t c_batch;
+
+    template <int ACT> __device__ __forceinline__ float act_of(float acc_v, float bias_v) const {
+        float t = fmaf(p.alpha, acc_v, bias_v);
+        if (ACT == 1) t = fmaxf(t, 0.0f);
+        if (ACT == 2) t = gelu_tanh_f32(t);
+        return t;
+    }
+
+    // bias for columns gn..gn+3 (zero where there is none)
+    __device__ __forceinline__ void bias4(int gn, bool vec, float (&bv)[4]) const {
+        bv[0] = bv[1] = bv[2] = bv[3] = 0.0f;
+        if (!epi_has_bias(p.epi)) return;
+        if (vec && gn + 3 < p.N) {
+            f32x4 q = *(const f32x4*)(p.bias + gn);
+            bv[0] = q[0]; bv[1] = q[1]; bv[2] = q[2]; bv[3] = q[3];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (gn + e < p.N) bv[e] = p.bias[gn + e];
+        }
+    }
+
+    template <int ACT, bool OUT_F32> __device__ __forceinline__ void run() {
+        constexpr int ESZ = OUT_F32 ? 4 : 2;
+        constexpr int EPC = 16 / ESZ;                       // elements per 16-byte chunk
+        // the coalesced path needs whole, aligned 16-byte chunks of C
+        const bool fast = (p.N % EPC == 0) && (p.ldc % EPC == 0) &&
+                          (((uintptr_t)p.C + (uintptr_t)c_batch * ESZ) % 16 == 0);
+        const bool bias_vec = ((uintptr_t)p.bias % 16) == 0;
+        if (fast) run_staged<ACT, OUT_F32>(bias_vec); else run_direct<ACT, OUT_F32>(bias_vec);
+    }
+
+    // ---- fast path: registers -> (epilogue) -> LDS slice -> 16-byte row stores
+    template <int ACT, bool OUT_F32> __device__ __forceinline__ void run_staged(bool bias_vec) {
+        constexpr int ESZ = OUT_F32 ? 4 : 2;
+        constexpr int ROW_BYTES = WTN * ESZ;
+        constexpr int CPR = ROW_BYTES / 16;                 // 16-byte chunks per row
+        constexpr int RP = ROW_BYTES >= 256 ? 1 : 256 / ROW_BYTES;   // rows per 256 bytes
+        constexpr int MAX_ROWS = LDS_PER_WAVE / ROW_BYTES;
+        constexpr int PASS_BLOCKS = (MAX_ROWS / 32) < FM ? (MAX_ROWS / 32) : FM;   // 32-row blocks per pass
+        static_assert(PASS_BLOCKS >= 1, "LDS slice too small for one 32-row block");
+        static_assert(CPR <= 64 && 64 % CPR == 0, "row chunks must divide the wave");
+        constexpr int ROWS_PER_LD = 64 / CPR;               // rows covered by one wave-wide 16-byte read
+        const int ld_row = lane / CPR, ld_chunk = lane % CPR;
+
+#pragma unroll
+        for (int i0 = 0; i0 < FM; i0 += PASS_BLOCKS) {
+            // registers -> LDS (row-major [rows][WTN], 16-byte chunks XOR-swizzled by row)
+#pragma unroll
+            for (int ii = 0; ii < PASS_BLOCKS; ++ii) {
+                const int i = i0 + ii;
+                if (i >= FM) break;
+                const int lrow = ii * 32 + (lane & 31);
+                const int sw = (lrow / RP) % CPR;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int lcol = j * 32 + g * 8 + ((lane >> 5) << 2);
+                        float bv[4];
+                        bias4(col0 + lcol, bias_vec, bv);
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(acc[i][j][g * 4 + e], bv[e]);
+                        const int cbyte = lcol * ESZ;
+                        char* dst = wlds + lrow * ROW_BYTES + ((((cbyte >> 4) ^ sw)) << 4) + (cbyte & 15);
+                        if (OUT_F32) {
+                            f32x4 w = {v[0], v[1], v[2], v[3]};
+                            *(f32x4*)dst = w;
+                        } else {
+                            int2v w;
+                            w[0] = (int)pack2<T>(v[0], v[1]);
+                            w[1] = (int)pack2<T>(v[2], v[3]);
+                            *(int2v*)dst = w;
+                        }
+                    }
+                }
+            }
+            // LDS -> global, 16 bytes per lane, lanes running along rows
+            constexpr int PASS_ROWS = PASS_BLOCKS * 32;
+#pragma unroll
+            for (int r0 = 0; r0 < PASS_ROWS; r0 += ROWS_PER_LD) {
+                const int lrow = r0 + ld_row;
+                const int sw = (lrow / RP) % CPR;
+                int4v w = *(const int4v*)(wlds + lrow * ROW_BYTES + ((ld_chunk ^ sw) << 4));
+                const int gm = row0 + i0 * 32 + lrow;
+                const int gn = col0 + ld_chunk * (16 / ESZ);
+                if (i0 * 32 + lrow < WTM && gm < p.M && gn < p.N)
+                    *(int4v*)((char*)p.C + (c_batch + (int64_t)gm * p.ldc + gn) * ESZ) = w;
+            }
+        }
+    }
+
+    // ---- general path (ragged N, unaligned C): stores straight from registers
+    template <int ACT, bool OUT_F32> __device__ __forceinline__ void run_direct(bool bias_vec) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int gn = col0 + j * 32 + g * 8 + ((lane >> 5) << 2);
+                float bv[4];
+                bias4(gn, bias_vec, bv);
+#pragma unroll
+                for (int i = 0; i < FM; ++i) {
+                    const int gm = row0 + i * 32 + (lane & 31);
+                    if (gm >= p.M || gn >= p.N) continue;
+                    const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (gn + e >= p.N) break;
+                        float v = act_of<ACT>(acc[i][j][g * 4 + e], bv[e]);
+                        if (OUT_F32) ((float*)p.C)[o + e] = v;
+                        else ((uint16_t*)p.C)[o + e] = to_bits16<T>(v);
+                    }
+                }
+            }
+        }
+    }
+};
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    // s_waitcnt vmcnt(N) only: vmcnt is split over bits [3:0] and [15:14]; lgkmcnt/expcnt left at maximum
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, TileMap tmap) {
     constexpr bool CONV = MODE == MODE_CONV;
     constexpr bool TRANS_B = MODE == MODE_TRANS_B;
@@ -146,9 +299,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
     static_assert(A_BLKS % NW == 0 && B_BLKS % NW == 0, "tile must split evenly over waves");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
     static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 5, "LDS stages");
+    constexpr int LOADS = CA + CB;             // direct-to-LDS loads per wave per k-tile
+    static_assert((NSTAGE - 2) * LOADS < 64, "vmcnt range");
     static_assert(TRANS_B || BN == 128 || BN == 256, "n-major B tile needs BN of 128 or 256");
 
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    extern __shared__ __attribute__((aligned(1024))) char lds[];   // NSTAGE x (A tile | B tile)
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -223,51 +379,67 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
     const char* b_tile = TRANS_B ? Bbase + (int64_t)n0 * p.ldb * 2 : Bbase + (int64_t)n0 * 2;
 
     const unsigned lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr_of(lds));
-    auto issue_loads = [&](int k0, int stage) {
+
+    // Convolution: filter tap (kh, kw) and first channel of the current k-tile,
+    // advanced incrementally (uniform) when a k-tile lies inside one tap.
+    const bool one_tap = CONV && (p.conv.Cin % BK) == 0;
+    int tap_kh = 0, tap_kw = 0, tap_c = 0;
+
+    // Issue this wave's share of the loads of the k-tile starting at k0 into
+    // `stage`.  TAIL: the k-tile may reach beyond K (only the last one can).
+    auto issue_loads = [&](int k0, int stage, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        if (p.debug & 1) return;
         const unsigned sa = lds_base + stage * STAGE;
         const unsigned sb = sa + A_BYTES;
-        const bool tail = k0 + BK > p.K;         // uniform: only the last k-tile can be partial
         if (CONV) {
             int4v ra = make_rsrc(a_tile);
-            const bool one_tap = (p.conv.Cin % BK) == 0;   // whole k-tile inside one filter tap
-            int tap_u = 0, c_u = 0, kh_u = 0, kw_u = 0;
-            if (one_tap) {
-                tap_u = k0 / p.conv.Cin; c_u = k0 - tap_u * p.conv.Cin;
-                kh_u = tap_u / p.conv.KW; kw_u = tap_u - kh_u * p.conv.KW;
-            }
+            int dh_u = tap_kh * p.conv.dil_h, dw_u = tap_kw * p.conv.dil_w;
+            unsigned delta_u = (unsigned)(((dh_u * p.conv.W + dw_u) * p.conv.Cin + tap_c) * 2);
 #pragma unroll
             for (int r = 0; r < CA; ++r) {
-                int k = k0 + a_kofs[r];
-                int kh, kw, c;
-                if (one_tap) { kh = kh_u; kw = kw_u; c = c_u + a_kofs[r]; }
-                else {
+                int dh, dw;
+                unsigned off;
+                if (one_tap) {
+                    dh = dh_u; dw = dw_u;
+                    off = a_voff[r] + delta_u + (unsigned)(a_kofs[r] * 2);
+                } else {
+                    int k = k0 + a_kofs[r];
                     int tap = k / p.conv.Cin;
-                    c = k - tap * p.conv.Cin;
-                    kh = tap / p.conv.KW;
-                    kw = tap - kh * p.conv.KW;
+                    int c = k - tap * p.conv.Cin;
+                    int kh = tap / p.conv.KW;
+                    int kw = tap - kh * p.conv.KW;
+                    dh = kh * p.conv.dil_h; dw = kw * p.conv.dil_w;
+                    off = a_voff[r] + (unsigned)(((dh * p.conv.W + dw) * p.conv.Cin + c) * 2);
                 }
-                int dh = kh * p.conv.dil_h, dw = kw * p.conv.dil_w;
                 int ih = a_ih0[r] + dh, iw = a_iw0[r] + dw;
-                bool ok = a_ok[r] && k < p.K && ih >= 0 && ih < p.conv.H && iw >= 0 && iw < p.conv.W;
-                unsigned off = a_voff[r] + (unsigned)(((dh * p.conv.W + dw) * p.conv.Cin + c) * 2);
+                bool ok = a_ok[r] && ih >= 0 && ih < p.conv.H && iw >= 0 && iw < p.conv.W;
+                if (TAIL) ok = ok && (k0 + a_kofs[r] < p.K);
                 dma16(ra, sa + (wave * CA + r) * 1024, ok ? off : kOob);
+            }
+            if (one_tap) {              // advance to the next k-tile
+                tap_c += BK;
+                if (tap_c >= p.conv.Cin) {
+                    tap_c = 0;
+                    if (++tap_kw == p.conv.KW) { tap_kw = 0; ++tap_kh; }
+                }
             }
         } else {
             int4v ra = make_rsrc(a_tile + (int64_t)k0 * 2);
 #pragma unroll
             for (int r = 0; r < CA; ++r) {
                 unsigned off = a_voff[r];
-                if (tail && k0 + a_kofs[r] >= p.K) off = kOob;
+                if (TAIL && k0 + a_kofs[r] >= p.K) off = kOob;
                 dma16(ra, sa + (wave * CA + r) * 1024, off);
             }
         }
         {
             int4v rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2
-                                                          : b_tile + (int64_t)k0 * p.ldb * 2);
+                                         : b_tile + (int64_t)k0 * p.ldb * 2);
 #pragma unroll
             for (int r = 0; r < CB; ++r) {
                 unsigned off = b_voff[r];
-                if (tail && k0 + b_kofs[r] >= p.K) off = kOob;
+                if (TAIL && k0 + b_kofs[r] >= p.K) off = kOob;
                 dma16(rb, sb + (wave * CB + r) * 1024, off);
             }
         }
@@ -289,6 +461,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     auto read_a = [&](const char* sa, int ks, short8v (&af)[FM]) {
+        if (p.debug & 4) return;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             int row = wm * WTM + i * 32 + frag_row;
@@ -296,6 +469,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
         }
     };
     auto read_b = [&](const char* sb, int ks, short8v (&bf)[FN]) {
+        if (p.debug & 4) return;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             if (TRANS_B) {
@@ -313,93 +487,115 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
         }
     };
 
-    auto compute = [&](int stage) {
-        const char* sa = lds + stage * STAGE;
-        const char* sb = sa + A_BYTES;
-        short8v af[2][FM], bf[2][FN];
-        read_a(sa, 0, af[0]);
-        read_b(sb, 0, bf[0]);
+    // Fragments are double-buffered in registers across k16 steps AND across
+    // k-tiles: the reads of step ks+1 are issued before the MFMAs of step ks,
+    // and the first fragments of the next k-tile are read (after the barrier
+    // that publishes its stage) underneath the MFMAs of this tile's last step.
+    short8v af[2][FM], bf[2][FN];
+    auto mfma_step = [&](int cur) {
+        if (p.debug & 2) return;
 #pragma unroll
-        for (int ks = 0; ks < KSUB; ++ks) {
-            const int cur = ks & 1;
-            if (ks + 1 < KSUB) {
-                read_a(sa, ks + 1, af[cur ^ 1]);
-                read_b(sb, ks + 1, bf[cur ^ 1]);
-            }
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+    };
+    static_assert(KSUB % 2 == 0, "fragment buffer parity assumes an even number of k16 steps");
+
+    // Wait until at most `newer` whole k-tiles of this wave's loads are still in
+    // flight (loads complete in order, so everything older has landed).
+    auto wait_newer = [&](int newer) {
+        switch (newer) {
+        case 0: wait_vmcnt<0>(); break;
+        case 1: wait_vmcnt<LOADS>(); break;
+        case 2: wait_vmcnt<(NSTAGE > 3 ? 2 : 0) * LOADS>(); break;
+        default: wait_vmcnt<(NSTAGE > 4 ? 3 : 0) * LOADS>(); break;
         }
     };
 
-    // ---- main loop: two LDS stages, loads of tile t+1 in flight during tile t
-    const int KT = (p.K + BK - 1) / BK;
-    if (KT > 0) issue_loads(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0): this wave's pieces have landed
-    __syncthreads();
-    for (int kt = 0; kt < KT - 1; ++kt) {
-        issue_loads((kt + 1) * BK, (kt + 1) & 1);
-        compute(kt & 1);
-        __builtin_amdgcn_s_waitcnt(0x0f70);
-        __syncthreads();
-    }
-    if (KT > 0) compute((KT - 1) & 1);
+    // One k-tile.  have_next: publish the next tile's stage (wait for this
+    // wave's pieces, barrier) and start reading it under the last MFMA group.
+    // NEWER >= 0: compile-time count of younger k-tiles in flight; -1: `newer_rt`.
+    auto tile_body = [&](int stage, int next_stage, bool have_next, auto newer_tag, int newer_rt) {
+        constexpr int NEWER = decltype(newer_tag)::value;
+        const char* sa = lds + stage * STAGE;
+        const char* sb = sa + A_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < KSUB - 1; ++ks) {
+            read_a(sa, ks + 1, af[(ks + 1) & 1]);
+            read_b(sb, ks + 1, bf[(ks + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
+            mfma_step(ks & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (have_next) {
+            if (NEWER >= 0) wait_vmcnt<(NEWER >= 0 ? NEWER : 0) * LOADS>(); else wait_newer(newer_rt);
+            if (!(p.debug & 8)) __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
+            const char* na = lds + next_stage * STAGE;
+            read_a(na, 0, af[0]);
+            read_b(na + A_BYTES, 0, bf[0]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mfma_step((KSUB - 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-    // ---- epilogue in registers, then store ---------------------------------
-    // lane holds, for block (i,j): row m = lane%32, columns 8*g + 4*(lane/32) + 0..3, g = 0..3
-    const bool has_bias = epi_has_bias(p.epi);
-    const int64_t c_batch = (int64_t)b * p.stride_c;
-    const bool out_f32 = p.out_dtype == DT_F32;
-    const int esz = out_f32 ? 4 : 2;
-    const bool vec_ok = (p.ldc % 4 == 0) && (((uintptr_t)p.C + (uintptr_t)c_batch * esz) % 16 == 0);
+    // ---- main loop: NSTAGE LDS stages; the loads of k-tiles t+1 .. t+NSTAGE-1
+    // are in flight while k-tile t is multiplied; one barrier per k-tile.
+    const int KT = (p.K + BK - 1) / BK;       // k-tiles
+    const int KF = p.K / BK;                  // of which full
+    if (KT > 0) {
+        int issued = 0;                        // k-tiles whose loads have been issued
+        int slot_in = 0;                       // stage the next issued tile goes to
+        auto issue_next = [&](auto tail_tag) {
+            issue_loads(issued * BK, slot_in, tail_tag);
+            ++issued;
+            slot_in = (slot_in + 1 == NSTAGE) ? 0 : slot_in + 1;
+        };
+        while (issued < NSTAGE - 1 && issued < KT) {
+            if (issued < KF) issue_next(TailNo{}); else issue_next(TailYes{});
+        }
+        wait_newer(issued - 1);
+        __syncthreads();
+        read_a(lds, 0, af[0]);
+        read_b(lds + A_BYTES, 0, bf[0]);
+        int kt = 0, slot = 0;
+        // steady state: every issued tile is full, NSTAGE-2 younger tiles stay in flight
+        for (; issued < KF; ++kt) {
+            issue_next(TailNo{});
+            const int nslot = (slot + 1 == NSTAGE) ? 0 : slot + 1;
+            tile_body(slot, nslot, true, IntTag<NSTAGE - 2>{}, 0);
+            slot = nslot;
+        }
+        // drain: a possibly ragged last tile, then nothing left to issue
+        for (; kt < KT; ++kt) {
+            if (issued < KT) issue_next(TailYes{});
+            const int nslot = (slot + 1 == NSTAGE) ? 0 : slot + 1;
+            tile_body(slot, nslot, kt + 1 < KT, IntTag<-1>{}, issued - (kt + 2));
+            slot = nslot;
+        }
+    }
+
+    // ---- epilogue in registers, then one coalesced store ---------------------
+    // Lane holds, for block (i,j): row m = lane%32, columns 8*g + 4*(lane/32) + 0..3.
+    // alpha/bias/activation and the rounding to the output type happen on the
+    // accumulator registers.  The rounded pieces then take one trip through this
+    // wave's own slice of LDS (free after the k loop) purely to change which lane
+    // holds what, so that the global stores are 16 bytes per lane along rows:
+    // every store instruction writes whole 128-byte (or longer) row segments.
+    __syncthreads();                           // all waves are done reading the last stage
     const int act = (p.epi == EPI_RELU || p.epi == EPI_BIAS_RELU) ? 1
                   : (p.epi == EPI_GELU_TANH || p.epi == EPI_BIAS_GELU_TANH) ? 2 : 0;
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int gn = n0 + wn * WTN + j * 32 + g * 8 + ((lane >> 5) << 2);
-            float bias[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (has_bias) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (gn + e < p.N) bias[e] = p.bias[gn + e];
-            }
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int gm = m0 + wm * WTM + i * 32 + (lane & 31);
-                if (gm >= p.M || gn >= p.N) continue;
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float tt = fmaf(p.alpha, acc[i][j][g * 4 + e], bias[e]);
-                    if (act == 1) tt = fmaxf(tt, 0.0f);
-                    else if (act == 2) tt = gelu_tanh_f32(tt);
-                    v[e] = tt;
-                }
-                const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
-                if (vec_ok && gn + 3 < p.N) {
-                    if (out_f32) {
-                        f32x4 w = {v[0], v[1], v[2], v[3]};
-                        *(f32x4*)((float*)p.C + o) = w;
-                    } else {
-                        int2v w;
-                        w[0] = (int)to_bits16<T>(v[0]) | ((int)to_bits16<T>(v[1]) << 16);
-                        w[1] = (int)to_bits16<T>(v[2]) | ((int)to_bits16<T>(v[3]) << 16);
-                        *(int2v*)((uint16_t*)p.C + o) = w;
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (gn + e >= p.N) break;
-                        if (out_f32) ((float*)p.C)[o + e] = v[e];
-                        else ((uint16_t*)p.C)[o + e] = to_bits16<T>(v[e]);
-                    }
-                }
-            }
-        }
+    const bool out_f32 = p.out_dtype == DT_F32;
+    char* wlds = lds + wave * ((NSTAGE * STAGE) / NW);
+    EpiCtx<T, FM, FN, WTM, WTN, (NSTAGE * STAGE) / NW> ctx{p, acc, wlds, m0 + wm * WTM, n0 + wn * WTN, lane,
+                                                         (int64_t)b * p.stride_c};
+    if (out_f32) {
+        if (act == 0) ctx.template run<0, true>(); else if (act == 1) ctx.template run<1, true>();
+        else ctx.template run<2, true>();
+    } else {
+        if (act == 0) ctx.template run<0, false>(); else if (act == 1) ctx.template run<1, false>();
+        else ctx.template run<2, false>();
     }
 }
 
