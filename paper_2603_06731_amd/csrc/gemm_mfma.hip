@@ -33,7 +33,7 @@ bool mfma_supported(const Problem& p) {
 
 static int choose_config(const Problem& p) {
     long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
-    if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 0;
+    if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 1;     // 256x256x32, 4 LDS stages
     return 2;
 }
 
@@ -42,10 +42,8 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
     int group_m = 8;
     if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) group_m = g; }
     *name = kMfmaConfigs[cfg].name;
-    Problem q = p;
-    if (const char* e = std::getenv("PBK_DEBUG")) q.debug = std::atoi(e);
-    return p.in_dtype == DT_BF16 ? launch_mfma_bf16(q, stream, cfg, group_m)
-                                 : launch_mfma_f16(q, stream, cfg, group_m);
+    return p.in_dtype == DT_BF16 ? launch_mfma_bf16(p, stream, cfg, group_m)
+                                 : launch_mfma_f16(p, stream, cfg, group_m);
 }
 
 }  // namespace pbk

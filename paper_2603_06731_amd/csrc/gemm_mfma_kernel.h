@@ -132,6 +132,7 @@ __device__ __forceinline__ unsigned lds_addr_of(const char* p) {
 }
 
 template <int V> struct IntTag { static constexpr int value = V; };
+template <bool V> struct BoolTag { static constexpr bool value = V; };
 struct TailYes { static constexpr bool value = true; };
 struct TailNo { static constexpr bool value = false; };
 
@@ -194,6 +195,7 @@ struct EpiCtx {
     // ---- fast path: registers -> (epilogue) -> LDS slice -> 16-byte row stores
     template <int ACT, bool OUT_F32> __device__ __forceinline__ void run_staged(bool bias_vec) {
         constexpr int ESZ = OUT_F32 ? 4 : 2;
+        constexpr int EPC = 16 / ESZ;                       // elements per 16-byte chunk
         constexpr int ROW_BYTES = WTN * ESZ;
         constexpr int CPR = ROW_BYTES / 16;                 // 16-byte chunks per row
         constexpr int RP = ROW_BYTES >= 256 ? 1 : 256 / ROW_BYTES;   // rows per 256 bytes
@@ -202,6 +204,7 @@ struct EpiCtx {
         static_assert(PASS_BLOCKS >= 1, "LDS slice too small for one 32-row block");
         static_assert(CPR <= 64 && 64 % CPR == 0, "row chunks must divide the wave");
         constexpr int ROWS_PER_LD = 64 / CPR;               // rows covered by one wave-wide 16-byte read
+        static_assert((32 % ROWS_PER_LD) == 0, "reads must tile a 32-row block");
         const int ld_row = lane / CPR, ld_chunk = lane % CPR;
 
 #pragma unroll
@@ -237,17 +240,30 @@ struct EpiCtx {
                     }
                 }
             }
-            // LDS -> global, 16 bytes per lane, lanes running along rows
+            // LDS -> global, 16 bytes per lane, lanes running along rows; reads are
+            // batched ahead of the stores so their latency is paid once per batch
             constexpr int PASS_ROWS = PASS_BLOCKS * 32;
+            constexpr int NLD = PASS_ROWS / ROWS_PER_LD;
+            constexpr int BATCH = NLD < 8 ? NLD : 8;
+            const int gn = col0 + ld_chunk * EPC;
+            const int lrow0 = i0 * 32 + ld_row;                     // row inside the wave tile
+            char* cptr = (char*)p.C + (c_batch + (int64_t)(row0 + lrow0) * p.ldc + gn) * ESZ;
+            const int64_t cstep = (int64_t)ROWS_PER_LD * p.ldc * ESZ;
+            const int rows_left = (p.M - row0 < WTM ? p.M - row0 : WTM) - lrow0;   // valid rows from lrow0 on
 #pragma unroll
-            for (int r0 = 0; r0 < PASS_ROWS; r0 += ROWS_PER_LD) {
-                const int lrow = r0 + ld_row;
-                const int sw = (lrow / RP) % CPR;
-                int4v w = *(const int4v*)(wlds + lrow * ROW_BYTES + ((ld_chunk ^ sw) << 4));
-                const int gm = row0 + i0 * 32 + lrow;
-                const int gn = col0 + ld_chunk * (16 / ESZ);
-                if (i0 * 32 + lrow < WTM && gm < p.M && gn < p.N)
-                    *(int4v*)((char*)p.C + (c_batch + (int64_t)gm * p.ldc + gn) * ESZ) = w;
+            for (int q0 = 0; q0 < NLD; q0 += BATCH) {
+                int4v w[BATCH];
+#pragma unroll
+                for (int q = 0; q < BATCH; ++q) {
+                    const int lrow = (q0 + q) * ROWS_PER_LD + ld_row;
+                    const int sw = (lrow / RP) % CPR;
+                    w[q] = *(const int4v*)(wlds + lrow * ROW_BYTES + ((ld_chunk ^ sw) << 4));
+                }
+#pragma unroll
+                for (int q = 0; q < BATCH; ++q) {
+                    if ((q0 + q) * ROWS_PER_LD < rows_left && gn < p.N)
+                        *(int4v*)(cptr + (q0 + q) * cstep) = w[q];
+                }
             }
         }
     }
@@ -385,26 +401,48 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
     const bool one_tap = CONV && (p.conv.Cin % BK) == 0;
     int tap_kh = 0, tap_kw = 0, tap_c = 0;
 
-    // Issue this wave's share of the loads of the k-tile starting at k0 into
-    // `stage`.  TAIL: the k-tile may reach beyond K (only the last one can).
-    auto issue_loads = [&](int k0, int stage, auto tail_tag) {
-        constexpr bool TAIL = decltype(tail_tag)::value;
-        if (p.debug & 1) return;
-        const unsigned sa = lds_base + stage * STAGE;
-        const unsigned sb = sa + A_BYTES;
+    // State of the k-tile whose loads are being issued (uniform across the wave).
+    int ld_k0 = 0;
+    unsigned ld_sa = 0, ld_sb = 0;
+    int4v ld_ra = make_rsrc(a_tile), ld_rb = make_rsrc(b_tile);
+    int ld_dh = 0, ld_dw = 0;
+    unsigned ld_delta = 0;
+
+    // Start issuing the k-tile at k0 into `stage`: descriptors rebased to k0.
+    auto begin_tile = [&](int k0, int stage) {
+        ld_k0 = k0;
+        ld_sa = lds_base + stage * STAGE;
+        ld_sb = ld_sa + A_BYTES;
         if (CONV) {
-            int4v ra = make_rsrc(a_tile);
-            int dh_u = tap_kh * p.conv.dil_h, dw_u = tap_kw * p.conv.dil_w;
-            unsigned delta_u = (unsigned)(((dh_u * p.conv.W + dw_u) * p.conv.Cin + tap_c) * 2);
-#pragma unroll
-            for (int r = 0; r < CA; ++r) {
+            ld_dh = tap_kh * p.conv.dil_h; ld_dw = tap_kw * p.conv.dil_w;
+            ld_delta = (unsigned)(((ld_dh * p.conv.W + ld_dw) * p.conv.Cin + tap_c) * 2);
+            if (one_tap) {              // advance the uniform tap state to the next k-tile
+                tap_c += BK;
+                if (tap_c >= p.conv.Cin) {
+                    tap_c = 0;
+                    if (++tap_kw == p.conv.KW) { tap_kw = 0; ++tap_kh; }
+                }
+            }
+        } else {
+            ld_ra = make_rsrc(a_tile + (int64_t)k0 * 2);
+        }
+        ld_rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2 : b_tile + (int64_t)k0 * p.ldb * 2);
+    };
+
+    // Issue load number r (0 .. LOADS-1) of the current tile: first this wave's
+    // CA pieces of A, then its CB pieces of B.  TAIL: the k-tile may reach
+    // beyond K (only the last one can).
+    auto issue_piece = [&](int r, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        if (r < CA) {
+            unsigned off;
+            if (CONV) {
                 int dh, dw;
-                unsigned off;
                 if (one_tap) {
-                    dh = dh_u; dw = dw_u;
-                    off = a_voff[r] + delta_u + (unsigned)(a_kofs[r] * 2);
+                    dh = ld_dh; dw = ld_dw;
+                    off = a_voff[r] + ld_delta + (unsigned)(a_kofs[r] * 2);
                 } else {
-                    int k = k0 + a_kofs[r];
+                    int k = ld_k0 + a_kofs[r];
                     int tap = k / p.conv.Cin;
                     int c = k - tap * p.conv.Cin;
                     int kh = tap / p.conv.KW;
@@ -414,35 +452,24 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
                 }
                 int ih = a_ih0[r] + dh, iw = a_iw0[r] + dw;
                 bool ok = a_ok[r] && ih >= 0 && ih < p.conv.H && iw >= 0 && iw < p.conv.W;
-                if (TAIL) ok = ok && (k0 + a_kofs[r] < p.K);
-                dma16(ra, sa + (wave * CA + r) * 1024, ok ? off : kOob);
+                if (TAIL) ok = ok && (ld_k0 + a_kofs[r] < p.K);
+                off = ok ? off : kOob;
+            } else {
+                off = a_voff[r];
+                if (TAIL && ld_k0 + a_kofs[r] >= p.K) off = kOob;
             }
-            if (one_tap) {              // advance to the next k-tile
-                tap_c += BK;
-                if (tap_c >= p.conv.Cin) {
-                    tap_c = 0;
-                    if (++tap_kw == p.conv.KW) { tap_kw = 0; ++tap_kh; }
-                }
-            }
+            dma16(ld_ra, ld_sa + (wave * CA + r) * 1024, off);
         } else {
-            int4v ra = make_rsrc(a_tile + (int64_t)k0 * 2);
-#pragma unroll
-            for (int r = 0; r < CA; ++r) {
-                unsigned off = a_voff[r];
-                if (TAIL && k0 + a_kofs[r] >= p.K) off = kOob;
-                dma16(ra, sa + (wave * CA + r) * 1024, off);
-            }
+            const int rb = r - CA;
+            unsigned off = b_voff[rb];
+            if (TAIL && ld_k0 + b_kofs[rb] >= p.K) off = kOob;
+            dma16(ld_rb, ld_sb + (wave * CB + rb) * 1024, off);
         }
-        {
-            int4v rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2
-                                         : b_tile + (int64_t)k0 * p.ldb * 2);
+    };
+    auto issue_loads = [&](int k0, int stage, auto tail_tag) {
+        begin_tile(k0, stage);
 #pragma unroll
-            for (int r = 0; r < CB; ++r) {
-                unsigned off = b_voff[r];
-                if (TAIL && k0 + b_kofs[r] >= p.K) off = kOob;
-                dma16(rb, sb + (wave * CB + r) * 1024, off);
-            }
-        }
+        for (int r = 0; r < CA + CB; ++r) issue_piece(r, tail_tag);
     };
 
     // ---- per-lane fragment read offsets -----------------------------------
@@ -461,7 +488,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     auto read_a = [&](const char* sa, int ks, short8v (&af)[FM]) {
-        if (p.debug & 4) return;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             int row = wm * WTM + i * 32 + frag_row;
@@ -469,7 +495,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
         }
     };
     auto read_b = [&](const char* sb, int ks, short8v (&bf)[FN]) {
-        if (p.debug & 4) return;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             if (TRANS_B) {
@@ -493,12 +518,30 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
     // that publishes its stage) underneath the MFMAs of this tile's last step.
     short8v af[2][FM], bf[2][FN];
     auto mfma_step = [&](int cur) {
-        if (p.debug & 2) return;
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
                 acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+    };
+    // Same, with this wave's loads of the tile being fetched spread between the
+    // MFMAs (one every GAP MFMAs) instead of issued in one burst: a burst fills
+    // the memory pipeline's queue and stalls the wave in front of its MFMAs.
+    constexpr int MFMA_BEFORE_WAIT = (KSUB - 1) * FM * FN;
+    constexpr int GAP = MFMA_BEFORE_WAIT / LOADS > 0 ? MFMA_BEFORE_WAIT / LOADS : 1;
+    static_assert(GAP * LOADS <= MFMA_BEFORE_WAIT, "not enough MFMAs to hide the loads between");
+    auto mfma_step_loading = [&](int cur, int ks) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+                const int idx = (ks * FM + i) * FN + j;         // MFMA number within the k-tile
+                if (idx % GAP == GAP - 1 && idx / GAP < LOADS) {
+                    issue_piece(idx / GAP, TailNo{});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
     };
     static_assert(KSUB % 2 == 0, "fragment buffer parity assumes an even number of k16 steps");
 
@@ -516,8 +559,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
     // One k-tile.  have_next: publish the next tile's stage (wait for this
     // wave's pieces, barrier) and start reading it under the last MFMA group.
     // NEWER >= 0: compile-time count of younger k-tiles in flight; -1: `newer_rt`.
-    auto tile_body = [&](int stage, int next_stage, bool have_next, auto newer_tag, int newer_rt) {
+    auto tile_body = [&](int stage, int next_stage, bool have_next, auto newer_tag, int newer_rt, auto spread_tag) {
         constexpr int NEWER = decltype(newer_tag)::value;
+        constexpr bool SPREAD = decltype(spread_tag)::value;
         const char* sa = lds + stage * STAGE;
         const char* sb = sa + A_BYTES;
 #pragma unroll
@@ -525,12 +569,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
             read_a(sa, ks + 1, af[(ks + 1) & 1]);
             read_b(sb, ks + 1, bf[(ks + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
-            mfma_step(ks & 1);
+            if (SPREAD) mfma_step_loading(ks & 1, ks); else mfma_step(ks & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (have_next) {
             if (NEWER >= 0) wait_vmcnt<(NEWER >= 0 ? NEWER : 0) * LOADS>(); else wait_newer(newer_rt);
-            if (!(p.debug & 8)) __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
+            __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
             const char* na = lds + next_stage * STAGE;
             read_a(na, 0, af[0]);
             read_b(na + A_BYTES, 0, bf[0]);
@@ -562,16 +606,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
         int kt = 0, slot = 0;
         // steady state: every issued tile is full, NSTAGE-2 younger tiles stay in flight
         for (; issued < KF; ++kt) {
-            issue_next(TailNo{});
+            begin_tile(issued * BK, slot_in);          // its loads are issued between the MFMAs
+            ++issued;
+            slot_in = (slot_in + 1 == NSTAGE) ? 0 : slot_in + 1;
             const int nslot = (slot + 1 == NSTAGE) ? 0 : slot + 1;
-            tile_body(slot, nslot, true, IntTag<NSTAGE - 2>{}, 0);
+            tile_body(slot, nslot, true, IntTag<NSTAGE - 2>{}, 0, BoolTag<true>{});
             slot = nslot;
         }
         // drain: a possibly ragged last tile, then nothing left to issue
         for (; kt < KT; ++kt) {
             if (issued < KT) issue_next(TailYes{});
             const int nslot = (slot + 1 == NSTAGE) ? 0 : slot + 1;
-            tile_body(slot, nslot, kt + 1 < KT, IntTag<-1>{}, issued - (kt + 2));
+            tile_body(slot, nslot, kt + 1 < KT, IntTag<-1>{}, issued - (kt + 2), BoolTag<false>{});
             slot = nslot;
         }
     }

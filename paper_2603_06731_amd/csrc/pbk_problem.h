@@ -31,7 +31,6 @@ struct Problem {
     int is_conv;
     int epi;
     float alpha;
-    int debug;            // experiment switches (0 in production)
     ConvGeom conv;
 };
 
