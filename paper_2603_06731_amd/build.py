@@ -21,12 +21,25 @@ def _headers():
     return hs
 
 
+def _extra_flags(src: str):
+    """Development aid: PBK_BUILD_CFGS="1,8" compiles only those MFMA tile
+    configurations (bf16 only); the default builds everything."""
+    only = os.environ.get("PBK_BUILD_CFGS")
+    if not only or "gemm_mfma_" not in src:
+        return []
+    mask = 0
+    if "bf16" in src:
+        for c in only.split(","):
+            mask |= 1 << int(c)
+    return [f"-DPBK_CFG_MASK={mask}u"]
+
+
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
     path = os.path.join(CSRC, src)
     newest = max([os.path.getmtime(path)] + [os.path.getmtime(h) for h in _headers()])
     if force or not os.path.exists(obj) or os.path.getmtime(obj) < newest:
-        subprocess.check_call([HIPCC, *FLAGS, "-c", path, "-o", obj], stderr=subprocess.DEVNULL
+        subprocess.check_call([HIPCC, *FLAGS, *_extra_flags(src), "-c", path, "-o", obj], stderr=subprocess.DEVNULL
                               if os.environ.get("PBK_BUILD_QUIET") else None)
     return obj
 

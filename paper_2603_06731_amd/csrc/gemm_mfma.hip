@@ -33,8 +33,13 @@ bool mfma_supported(const Problem& p) {
 
 static int choose_config(const Problem& p) {
     long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
-    if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 1;     // 256x256x32, 4 LDS stages
-    return 2;
+    if (p.M >= 256 && p.N >= 256 && t256 >= 128) {
+        // short contractions are dominated by the output store: three small
+        // workgroups per CU overlap one tile's store with another's loads
+        if (p.K <= 256) return 2;
+        return 0;                       // 256x256x32, 4 LDS stages
+    }
+    return 1;
 }
 
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name) {

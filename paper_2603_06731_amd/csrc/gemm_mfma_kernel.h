@@ -111,8 +111,10 @@ __device__ __forceinline__ int nmajor_offset(int k, int nbyte) {
 
 // Raw buffer descriptor over [base, base + 2^31): stride 0, 32-bit data format.
 __device__ __forceinline__ int4v make_rsrc(const void* base) {
+    // the base is wave-uniform; readfirstlane makes that visible to the register allocator
     uint64_t a = (uint64_t)base;
-    int4v r = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)kOob, 0x00020000};
+    int4v r = {__builtin_amdgcn_readfirstlane((int)(uint32_t)a),
+               __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32)), (int)kOob, 0x00020000};
     return r;
 }
 
@@ -123,6 +125,13 @@ __device__ __forceinline__ int4v make_rsrc(const void* base) {
 // s_waitcnt vmcnt(0) before the barrier that publishes the stage.  Nothing else
 // in this kernel depends on M0.
 __device__ __forceinline__ void dma16(int4v rsrc, unsigned lds_addr, unsigned voff) {
+    // descriptor and LDS address are wave-uniform by construction; readfirstlane pins
+    // them to scalar registers whatever the compiler's divergence analysis concluded
+    rsrc[0] = __builtin_amdgcn_readfirstlane(rsrc[0]);
+    rsrc[1] = __builtin_amdgcn_readfirstlane(rsrc[1]);
+    rsrc[2] = __builtin_amdgcn_readfirstlane(rsrc[2]);
+    rsrc[3] = __builtin_amdgcn_readfirstlane(rsrc[3]);
+    lds_addr = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
 }
@@ -189,7 +198,7 @@ struct EpiCtx {
         const bool fast = (p.N % EPC == 0) && (p.ldc % EPC == 0) &&
                           (((uintptr_t)p.C + (uintptr_t)c_batch * ESZ) % 16 == 0);
         const bool bias_vec = ((uintptr_t)p.bias % 16) == 0;
-        if (fast) run_staged<ACT, OUT_F32>(bias_vec); else run_direct<ACT, OUT_F32>(bias_vec);
+        if (fast) run_staged<ACT, OUT_F32>(bias_vec); else run_direct<OUT_F32>(bias_vec, ACT);
     }
 
     // ---- fast path: registers -> (epilogue) -> LDS slice -> 16-byte row stores
@@ -207,6 +216,14 @@ struct EpiCtx {
         static_assert((32 % ROWS_PER_LD) == 0, "reads must tile a 32-row block");
         const int ld_row = lane / CPR, ld_chunk = lane % CPR;
 
+        // every bias value this lane needs, loaded once and together
+        float bias_r[FN][4][4];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                bias4(col0 + j * 32 + g * 8 + ((lane >> 5) << 2), bias_vec, bias_r[j][g]);
+
 #pragma unroll
         for (int i0 = 0; i0 < FM; i0 += PASS_BLOCKS) {
             // registers -> LDS (row-major [rows][WTN], 16-byte chunks XOR-swizzled by row)
@@ -221,11 +238,9 @@ struct EpiCtx {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int lcol = j * 32 + g * 8 + ((lane >> 5) << 2);
-                        float bv[4];
-                        bias4(col0 + lcol, bias_vec, bv);
                         float v[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(acc[i][j][g * 4 + e], bv[e]);
+                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(acc[i][j][g * 4 + e], bias_r[j][g][e]);
                         const int cbyte = lcol * ESZ;
                         char* dst = wlds + lrow * ROW_BYTES + ((((cbyte >> 4) ^ sw)) << 4) + (cbyte & 15);
                         if (OUT_F32) {
@@ -269,7 +284,7 @@ struct EpiCtx {
     }
 
     // ---- general path (ragged N, unaligned C): stores straight from registers
-    template <int ACT, bool OUT_F32> __device__ __forceinline__ void run_direct(bool bias_vec) {
+    template <bool OUT_F32> __device__ __forceinline__ void run_direct(bool bias_vec, int act) {
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
 #pragma unroll
@@ -285,7 +300,9 @@ struct EpiCtx {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         if (gn + e >= p.N) break;
-                        float v = act_of<ACT>(acc[i][j][g * 4 + e], bv[e]);
+                        float v = fmaf(p.alpha, acc[i][j][g * 4 + e], bv[e]);
+                        if (act == 1) v = fmaxf(v, 0.0f);
+                        else if (act == 2) v = gelu_tanh_f32(v);
                         if (OUT_F32) ((float*)p.C)[o + e] = v;
                         else ((uint16_t*)p.C)[o + e] = to_bits16<T>(v);
                     }
@@ -300,8 +317,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, TileMap tmap) {
+// OCC: workgroups of this kernel meant to share a CU (bounds the register budget)
+template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
+__global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mfma_kernel(Problem p, TileMap tmap) {
     constexpr bool CONV = MODE == MODE_CONV;
     constexpr bool TRANS_B = MODE == MODE_TRANS_B;
     constexpr int NW = WM * WN;
@@ -524,12 +542,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
             for (int j = 0; j < FN; ++j)
                 acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
     };
-    // Same, with this wave's loads of the tile being fetched spread between the
-    // MFMAs (one every GAP MFMAs) instead of issued in one burst: a burst fills
-    // the memory pipeline's queue and stalls the wave in front of its MFMAs.
+    // Same, with this wave's loads of the tile being fetched spread evenly between
+    // the MFMAs of the whole k-tile (one every GAP MFMAs) instead of issued in one
+    // burst: a burst fills the memory pipeline's queue and stalls the wave in front
+    // of its MFMAs.  EARLY of the LOADS pieces are issued before the wait+barrier of
+    // the k-tile, the rest under its last MFMA group.
+    constexpr int MFMA_PER_TILE = KSUB * FM * FN;
     constexpr int MFMA_BEFORE_WAIT = (KSUB - 1) * FM * FN;
-    constexpr int GAP = MFMA_BEFORE_WAIT / LOADS > 0 ? MFMA_BEFORE_WAIT / LOADS : 1;
-    static_assert(GAP * LOADS <= MFMA_BEFORE_WAIT, "not enough MFMAs to hide the loads between");
+    // with two stages the tile being fetched is the very next one: everything goes before the wait
+    constexpr int SPAN = NSTAGE >= 3 ? MFMA_PER_TILE : MFMA_BEFORE_WAIT;
+    constexpr int GAP = SPAN / LOADS > 0 ? SPAN / LOADS : 1;
+    static_assert(GAP * LOADS <= SPAN, "not enough MFMAs to hide the loads between");
+    constexpr int EARLY = MFMA_BEFORE_WAIT / GAP < LOADS ? MFMA_BEFORE_WAIT / GAP : LOADS;
+    static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
     auto mfma_step_loading = [&](int cur, int ks) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
@@ -573,14 +598,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(Problem p, Tile
             __builtin_amdgcn_sched_barrier(0);
         }
         if (have_next) {
-            if (NEWER >= 0) wait_vmcnt<(NEWER >= 0 ? NEWER : 0) * LOADS>(); else wait_newer(newer_rt);
+            // steady state: NEWER-1 whole younger tiles plus the EARLY pieces just issued may stay in flight
+            if (NEWER >= 0) wait_vmcnt<(SPREAD && NSTAGE >= 3 ? (NEWER >= 1 ? NEWER - 1 : 0) * LOADS + EARLY : (NEWER >= 0 ? NEWER : 0) * LOADS)>();
+            else wait_newer(newer_rt);
             __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
             const char* na = lds + next_stage * STAGE;
             read_a(na, 0, af[0]);
             read_b(na + A_BYTES, 0, bf[0]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        mfma_step((KSUB - 1) & 1);
+        if (SPREAD) mfma_step_loading((KSUB - 1) & 1, KSUB - 1); else mfma_step((KSUB - 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
     };
 

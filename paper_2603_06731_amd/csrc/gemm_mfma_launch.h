@@ -16,21 +16,19 @@ struct MfmaConfig {
 // Tile configurations (the static stand-in for the paper's analytical tile
 // size model, Sec. 4.3): id -> workgroup tile and wave grid.
 static const MfmaConfig kMfmaConfigs[] = {
-    {0, 256, 256, 64, 2, 4, 2, "mfma_256x256x64_w2x4_s2"},
-    {1, 256, 256, 32, 2, 4, 4, "mfma_256x256x32_w2x4_s4"},
-    {2, 128, 128, 64, 2, 2, 2, "mfma_128x128x64_w2x2_s2"},
-    {3, 128, 256, 64, 1, 4, 2, "mfma_128x256x64_w1x4_s2"},
-    {4, 256, 256, 32, 2, 4, 5, "mfma_256x256x32_w2x4_s5"},
-    {5, 256, 256, 32, 2, 4, 3, "mfma_256x256x32_w2x4_s3"},
-    {6, 128, 128, 32, 2, 2, 4, "mfma_128x128x32_w2x2_s4"},
-    {7, 256, 128, 32, 2, 2, 4, "mfma_256x128x32_w2x2_s4"},
+    {0, 256, 256, 32, 2, 4, 4, "mfma_256x256x32_w2x4_s4"},
+    {1, 128, 128, 64, 2, 2, 2, "mfma_128x128x64_w2x2_s2"},
+    {2, 128, 128, 32, 2, 2, 3, "mfma_128x128x32_w2x2_s3_occ3"},
+    {3, 256, 128, 32, 2, 2, 4, "mfma_256x128x32_w2x2_s4"},
+    {4, 128, 256, 32, 1, 4, 4, "mfma_128x256x32_w1x4_s4"},
+    {5, 256, 256, 64, 2, 4, 2, "mfma_256x256x64_w2x4_s2"},
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
 hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     constexpr int LDS_BYTES = NSTAGE * (BM * BK * 2 + BN * BK * 2);
-    auto kern = gemm_mfma_kernel<T, BM, BN, BK, WM, WN, MODE, NSTAGE>;
+    auto kern = gemm_mfma_kernel<T, BM, BN, BK, WM, WN, MODE, NSTAGE, OCC>;
     static std::atomic<unsigned> attr_done{0};      // bit per device
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -50,29 +48,32 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     tm.total = (int)total;
     tm.group_m = group_m < 1 ? 1 : group_m;
     tm.xcds = 8;
-    if (const char* e = std::getenv("PBK_XCDS")) { int x = std::atoi(e); if (x > 0) tm.xcds = x; }
     hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), LDS_BYTES, stream, p, tm);
     return hipGetLastError();
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
-    if (p.is_conv) return launch_one<T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE>(p, stream, group_m);
-    if (p.trans_b) return launch_one<T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE>(p, stream, group_m);
-    return launch_one<T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE>(p, stream, group_m);
+    if (p.is_conv) return launch_one<T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC>(p, stream, group_m);
+    if (p.trans_b) return launch_one<T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC>(p, stream, group_m);
+    return launch_one<T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC>(p, stream, group_m);
 }
+
+// PBK_CFG_MASK (build-time, development only): bit i set = compile configuration i.
+#ifndef PBK_CFG_MASK
+#define PBK_CFG_MASK 0xFFFFFFFFu
+#endif
+#define PBK_CASE(ID, ...) case ID: if constexpr (((PBK_CFG_MASK) >> ID) & 1u) return launch_modes<T, __VA_ARGS__>(p, stream, group_m); else return hipErrorInvalidValue;
 
 template <typename T>
 hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int group_m) {
     switch (cfg) {
-    case 0: return launch_modes<T, 256, 256, 64, 2, 4, 2>(p, stream, group_m);
-    case 1: return launch_modes<T, 256, 256, 32, 2, 4, 4>(p, stream, group_m);
-    case 2: return launch_modes<T, 128, 128, 64, 2, 2, 2>(p, stream, group_m);
-    case 3: return launch_modes<T, 128, 256, 64, 1, 4, 2>(p, stream, group_m);
-    case 4: return launch_modes<T, 256, 256, 32, 2, 4, 5>(p, stream, group_m);
-    case 5: return launch_modes<T, 256, 256, 32, 2, 4, 3>(p, stream, group_m);
-    case 6: return launch_modes<T, 128, 128, 32, 2, 2, 4>(p, stream, group_m);
-    case 7: return launch_modes<T, 256, 128, 32, 2, 2, 4>(p, stream, group_m);
+    PBK_CASE(0, 256, 256, 32, 2, 4, 4)
+    PBK_CASE(1, 128, 128, 64, 2, 2, 2)
+    PBK_CASE(2, 128, 128, 32, 2, 2, 3, 3)
+    PBK_CASE(3, 256, 128, 32, 2, 2, 4)
+    PBK_CASE(4, 128, 256, 32, 1, 4, 4)
+    PBK_CASE(5, 256, 256, 64, 2, 4, 2)
     default: return hipErrorInvalidValue;
     }
 }
