@@ -555,6 +555,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     static_assert(GAP * LOADS <= SPAN, "not enough MFMAs to hide the loads between");
     constexpr int EARLY = MFMA_BEFORE_WAIT / GAP < LOADS ? MFMA_BEFORE_WAIT / GAP : LOADS;
     static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
+    static_assert(NSTAGE < 3 || MFMA_BEFORE_WAIT % GAP == 0, "EARLY must not depend on the wave's issue phase");
     auto mfma_step_loading = [&](int cur, int ks) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
