@@ -38,9 +38,13 @@ def _compile(src: str, force: bool) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
     path = os.path.join(CSRC, src)
     newest = max([os.path.getmtime(path)] + [os.path.getmtime(h) for h in _headers()])
-    if force or not os.path.exists(obj) or os.path.getmtime(obj) < newest:
-        subprocess.check_call([HIPCC, *FLAGS, *_extra_flags(src), "-c", path, "-o", obj], stderr=subprocess.DEVNULL
-                              if os.environ.get("PBK_BUILD_QUIET") else None)
+    cmd = [HIPCC, *FLAGS, *_extra_flags(src), "-c", path, "-o", obj]
+    stamp = obj + ".cmd"                     # the command line the object was built with
+    same_cmd = os.path.exists(stamp) and open(stamp).read() == " ".join(cmd)
+    if force or not same_cmd or not os.path.exists(obj) or os.path.getmtime(obj) < newest:
+        subprocess.check_call(cmd, stderr=subprocess.DEVNULL if os.environ.get("PBK_BUILD_QUIET") else None)
+        with open(stamp, "w") as f:
+            f.write(" ".join(cmd))
     return obj
 
 

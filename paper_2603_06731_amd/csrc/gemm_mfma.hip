@@ -32,13 +32,10 @@ bool mfma_supported(const Problem& p) {
 }
 
 static int choose_config(const Problem& p) {
-    long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
-    if (p.M >= 256 && p.N >= 256 && t256 >= 128) {
-        // short contractions are dominated by the output store: three small
-        // workgroups per CU overlap one tile's store with another's loads
-        if (p.K <= 256) return 2;
-        return 0;                       // 256x256x32, 4 LDS stages
-    }
+    // 128x256 tiles, two workgroups of four waves per CU: the two barrier domains
+    // fill each other's bubbles; measured best on all large shapes, long or short K
+    long long t = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256) * p.batch;
+    if (p.M >= 128 && p.N >= 256 && t >= 256) return 0;
     return 1;
 }
 

@@ -16,12 +16,11 @@ struct MfmaConfig {
 // Tile configurations (the static stand-in for the paper's analytical tile
 // size model, Sec. 4.3): id -> workgroup tile and wave grid.
 static const MfmaConfig kMfmaConfigs[] = {
-    {0, 256, 256, 32, 2, 4, 4, "mfma_256x256x32_w2x4_s4"},
+    {0, 128, 256, 32, 1, 4, 3, "mfma_128x256x32_w1x4_s3_occ2"},
     {1, 128, 128, 64, 2, 2, 2, "mfma_128x128x64_w2x2_s2"},
     {2, 128, 128, 32, 2, 2, 3, "mfma_128x128x32_w2x2_s3_occ3"},
-    {3, 256, 128, 32, 2, 2, 4, "mfma_256x128x32_w2x2_s4"},
-    {4, 128, 256, 32, 1, 4, 4, "mfma_128x256x32_w1x4_s4"},
-    {5, 256, 256, 64, 2, 4, 2, "mfma_256x256x64_w2x4_s2"},
+    {3, 256, 256, 32, 2, 4, 4, "mfma_256x256x32_w2x4_s4"},
+    {4, 256, 256, 64, 2, 4, 2, "mfma_256x256x64_w2x4_s2"},
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
@@ -68,12 +67,11 @@ hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
 template <typename T>
 hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int group_m) {
     switch (cfg) {
-    PBK_CASE(0, 256, 256, 32, 2, 4, 4)
+    PBK_CASE(0, 128, 256, 32, 1, 4, 3, 2)
     PBK_CASE(1, 128, 128, 64, 2, 2, 2)
     PBK_CASE(2, 128, 128, 32, 2, 2, 3, 3)
-    PBK_CASE(3, 256, 128, 32, 2, 2, 4)
-    PBK_CASE(4, 128, 256, 32, 1, 4, 4)
-    PBK_CASE(5, 256, 256, 64, 2, 4, 2)
+    PBK_CASE(3, 256, 256, 32, 2, 4, 4)
+    PBK_CASE(4, 256, 256, 64, 2, 4, 2)
     default: return hipErrorInvalidValue;
     }
 }
