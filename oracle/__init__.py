@@ -3,8 +3,8 @@
 Only tests, the smoke check and the bench's CPU-baseline leg may import this
 package.  It shares nothing with the HIP library and never imports it.
 
-Arrays are numpy, in host memory: float32 for F32 inputs and uint16 bit
-patterns for BF16 / F16 inputs.  Results come back as float64, unrounded.
+Arrays are numpy, in host memory: float32 for F32 inputs, uint16 bit
+patterns for BF16 / F16 inputs, uint8 for the FP8 formats.  Results come back as float64, unrounded.
 """
 from __future__ import annotations
 
@@ -14,7 +14,7 @@ import subprocess
 
 import numpy as np
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, FP8_E4M3, FP8_E5M2 = 0, 1, 2, 3, 4
 EPI_NONE, EPI_BIAS, EPI_RELU, EPI_BIAS_RELU, EPI_BIAS_GELU_TANH, EPI_GELU_TANH = range(6)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -72,7 +72,7 @@ def _ptr(a):
 
 
 def _check_in(a: np.ndarray, dtype: int) -> np.ndarray:
-    want = np.float32 if dtype == F32 else np.uint16
+    want = np.float32 if dtype == F32 else np.uint16 if dtype in (BF16, F16) else np.uint8
     if a.dtype != want:
         raise TypeError(f"dtype code {dtype} needs a {want.__name__} array, got {a.dtype}")
     return a

@@ -38,8 +38,32 @@ static double widen_f16(uint16_t b)
     return sign ? -v : v;
 }
 
+/* OCP 8-bit floating point (OFP8 specification): sign, E exponent bits with
+ * bias 2^(E-1)-1, M mantissa bits; exponent 0 = subnormal. */
+static double widen_fp8_e4m3(uint8_t b)
+{
+    int sign = b >> 7, e = (b >> 3) & 0xF, m = b & 7;
+    double v;
+    if (e == 15 && m == 7) v = NAN;                  /* the only non-finite code */
+    else if (e == 0) v = ldexp((double)m, -9);       /* m/8 * 2^-6 */
+    else v = ldexp((double)(8 + m), e - 10);         /* (1 + m/8) * 2^(e-7) */
+    return sign ? -v : v;
+}
+
+static double widen_fp8_e5m2(uint8_t b)
+{
+    int sign = b >> 7, e = (b >> 2) & 0x1F, m = b & 3;
+    double v;
+    if (e == 31) v = m ? NAN : INFINITY;
+    else if (e == 0) v = ldexp((double)m, -16);      /* m/4 * 2^-14 */
+    else v = ldexp((double)(4 + m), e - 17);         /* (1 + m/4) * 2^(e-15) */
+    return sign ? -v : v;
+}
+
 double oracle_widen(uint32_t bits, int dtype)
 {
+    if (dtype == ORACLE_FP8_E4M3) return widen_fp8_e4m3((uint8_t)bits);
+    if (dtype == ORACLE_FP8_E5M2) return widen_fp8_e5m2((uint8_t)bits);
     if (dtype == ORACLE_BF16) return widen_bf16((uint16_t)bits);
     if (dtype == ORACLE_F16) return widen_f16((uint16_t)bits);
     float f;
@@ -51,7 +75,9 @@ static inline double load(const void* p, int dtype, int64_t idx)
 {
     if (dtype == ORACLE_F32) return (double)((const float*)p)[idx];
     if (dtype == ORACLE_BF16) return widen_bf16(((const uint16_t*)p)[idx]);
-    return widen_f16(((const uint16_t*)p)[idx]);
+    if (dtype == ORACLE_F16) return widen_f16(((const uint16_t*)p)[idx]);
+    if (dtype == ORACLE_FP8_E4M3) return widen_fp8_e4m3(((const uint8_t*)p)[idx]);
+    return widen_fp8_e5m2(((const uint8_t*)p)[idx]);
 }
 
 /* ---- rounding to 16-bit formats (for tests of the conversion only) ----- */
@@ -140,7 +166,7 @@ double oracle_epilogue(double s, double bias, float alpha, int epi)
 
 static int check_common(int dtype, int epi, const float* bias)
 {
-    if (dtype < ORACLE_F32 || dtype > ORACLE_F16) return -1;
+    if (dtype < ORACLE_F32 || dtype > ORACLE_FP8_E5M2) return -1;
     if (epi < ORACLE_EPI_NONE || epi > ORACLE_EPI_GELU_TANH) return -2;
     if (epi_has_bias(epi) && !bias) return -3;
     return 0;

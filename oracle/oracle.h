@@ -14,7 +14,7 @@
  * here (the paper's generated code accumulates in fp32).
  *
  * All pointers are host pointers.  16-bit inputs are raw bit patterns
- * (uint16_t), widened exactly.  Every function returns 0 on success and a
+ * (uint16_t) and 8-bit inputs raw bytes (uint8_t), widened exactly.  Every function returns 0 on success and a
  * negative value on an invalid argument.
  */
 #ifndef PBK_ORACLE_H
@@ -27,7 +27,9 @@ extern "C" {
 #endif
 
 /* element types of A, B, image, weights */
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2,
+       ORACLE_FP8_E4M3 = 3,    /* OCP FP8 E4M3: bias 7, no infinities, S.1111.111 = NaN, max 448 */
+       ORACLE_FP8_E5M2 = 4 };  /* OCP FP8 E5M2: bias 15, IEEE-like infinities and NaNs, max 57344 */
 
 /* epilogues: t = alpha*s (+ bias[j]);  out = act(t) */
 enum {

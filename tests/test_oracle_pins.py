@@ -444,3 +444,56 @@ def test_oracle_rejects_bad_arguments():
     out = oracle.matmul(np.zeros((2, 0), np.float32), np.zeros((0, 4), np.float32),
                         np.ones(4, np.float32), dtype=F32, epi=oracle.EPI_BIAS)
     assert np.array_equal(out, np.ones((2, 4)))                             # empty sum + bias
+
+
+# ---------------------------------------------------------------------- FP8
+
+FP8 = [(oracle.FP8_E4M3, torch.float8_e4m3fn), (oracle.FP8_E5M2, torch.float8_e5m2)]
+
+
+@pytest.mark.parametrize("dtype,tdtype", FP8)
+def test_fp8_widening_matches_library_and_format_definition(dtype, tdtype):
+    codes = np.arange(256, dtype=np.uint8)
+    ref = torch.from_numpy(codes).view(tdtype).double().numpy()
+    got = np.array([oracle.widen_bits(int(c), dtype) for c in codes])
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(got[~np.isnan(got)], ref[~np.isnan(ref)])
+    assert np.array_equal(np.isnan(wl.widen(codes, dtype)), np.isnan(ref))
+    assert np.array_equal(wl.widen(codes, dtype)[~np.isnan(ref)], ref[~np.isnan(ref)])
+    # values fixed by the OFP8 format definition
+    if dtype == oracle.FP8_E4M3:
+        assert oracle.widen_bits(0x38, dtype) == 1.0 and oracle.widen_bits(0x7E, dtype) == 448.0
+        assert oracle.widen_bits(0x01, dtype) == 2.0 ** -9 and oracle.widen_bits(0x08, dtype) == 2.0 ** -6
+        assert math.isnan(oracle.widen_bits(0x7F, dtype)) and oracle.widen_bits(0xC0, dtype) == -2.0
+    else:
+        assert oracle.widen_bits(0x3C, dtype) == 1.0 and oracle.widen_bits(0x7B, dtype) == 57344.0
+        assert oracle.widen_bits(0x01, dtype) == 2.0 ** -16 and oracle.widen_bits(0x04, dtype) == 2.0 ** -14
+        assert math.isinf(oracle.widen_bits(0x7C, dtype)) and math.isnan(oracle.widen_bits(0x7D, dtype))
+
+
+@pytest.mark.parametrize("dtype,tdtype", FP8)
+def test_fp8_generator_rounding_matches_library(dtype, tdtype):
+    top = 448.0 if dtype == oracle.FP8_E4M3 else 57344.0
+    x = rng(40).standard_normal(20000) * np.exp(rng(41).uniform(-12, 6, 20000))
+    x = x[np.abs(x) < 0.95 * top]
+    assert np.array_equal(wl.to_storage(x, dtype), torch.from_numpy(x).to(tdtype).view(torch.uint8).numpy())
+    # ties go to the even code; values beyond the largest finite one saturate
+    codes = np.arange(0, 0x7E if dtype == oracle.FP8_E4M3 else 0x7B, dtype=np.uint8)
+    v = wl.widen(codes, dtype)
+    mid = (v[:-1] + v[1:]) / 2
+    got = wl.to_storage(mid, dtype)
+    assert np.all(got % 2 == 0) and np.all((got == codes[:-1]) | (got == codes[1:]))
+    assert wl.to_storage(np.array([1e9, -1e9]), dtype).tolist() == [int(codes[-1]) + 1, int(codes[-1]) + 1 + 128]
+
+
+@pytest.mark.parametrize("dtype,tdtype", FP8)
+@pytest.mark.parametrize("trans_b", [0, 1])
+def test_fp8_matmul_exact_small_integers(dtype, tdtype, trans_b):
+    m, n, k = 7, 5, 33
+    A = rng(42).integers(-4, 5, size=(m, k))
+    B = rng(43).integers(-4, 5, size=(k, n))
+    want = np.array(brute_matmul_int(A.tolist(), B.tolist()), dtype=np.float64)
+    As, Bs = as_dtype(A, dtype), as_dtype(B.T.copy() if trans_b else B, dtype)
+    assert np.array_equal(wl.widen(As, dtype), A)            # small integers are exact in both formats
+    got = oracle.matmul(As, Bs, dtype=dtype, trans_b=trans_b)
+    assert np.array_equal(got, want)

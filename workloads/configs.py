@@ -80,7 +80,7 @@ class Workload:
     @property
     def algorithmic_bytes(self) -> int:
         """Each operand read once, bias read once, output written once."""
-        esz_in = 4 if self.in_dtype == gen.DTYPE_F32 else 2
+        esz_in = {gen.DTYPE_F32: 4, gen.DTYPE_BF16: 2, gen.DTYPE_F16: 2}.get(self.in_dtype, 1)
         esz_out = 4 if self.out_dtype == gen.DTYPE_F32 else 2
         m, n, k = self.gemm_mnk
         if self.kind == "conv":

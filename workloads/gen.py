@@ -5,8 +5,8 @@ slice of any tensor can be regenerated anywhere with identical bits and no
 generator state.  The hash is SplitMix64 (Steele, Lea & Flood 2014, the
 finaliser used by java.util.SplittableRandom) applied to key + index.
 
-Storage dtypes are numpy arrays: float32 for F32 and uint16 bit patterns for
-BF16 / F16 (numpy has no bfloat16).  Rounding to storage happens once, here.
+Storage dtypes are numpy arrays: float32 for F32, uint16 bit patterns for
+BF16 / F16 (numpy has no bfloat16), uint8 codes for the OCP FP8 formats.  Rounding to storage happens once, here.
 """
 from __future__ import annotations
 
@@ -17,6 +17,8 @@ MASTER_SEED = 20260306
 DTYPE_F32 = 0
 DTYPE_BF16 = 1
 DTYPE_F16 = 2
+DTYPE_FP8_E4M3 = 3      # OCP FP8, stored as uint8
+DTYPE_FP8_E5M2 = 4
 
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
@@ -63,8 +65,37 @@ def normal_f64(seed: int, tensor_id: int, start: int, count: int,
     return std * np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
 
 
+def _fp8_tables(dtype: int):
+    """(sorted finite non-negative values, their codes) of an OCP FP8 format."""
+    if dtype == DTYPE_FP8_E4M3:
+        ebits, mbits, bias, top = 4, 3, 7, 0x7E          # 0x7F is NaN
+    else:
+        ebits, mbits, bias, top = 5, 2, 15, 0x7B         # 0x7C.. are inf / NaN
+    codes = np.arange(0, top + 1, dtype=np.int64)
+    e = codes >> mbits
+    m = codes & ((1 << mbits) - 1)
+    vals = np.where(e == 0, m * 2.0 ** (1 - bias - mbits), (m + (1 << mbits)) * 2.0 ** (e - bias - mbits))
+    return vals, codes
+
+
+def _to_fp8(x: np.ndarray, dtype: int) -> np.ndarray:
+    """Round to nearest representable value, ties to the even code, saturating at
+    the largest finite value (the generator never produces NaN or infinity)."""
+    vals, codes = _fp8_tables(dtype)
+    a = np.abs(x)
+    hi = np.clip(np.searchsorted(vals, a, side="left"), 1, len(vals) - 1)
+    lo = hi - 1
+    dlo, dhi = a - vals[lo], vals[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (codes[hi] % 2 == 0))
+    code = np.where(pick_hi, codes[hi], codes[lo])
+    code = np.where(a >= vals[-1], codes[-1], code)
+    return (code | (np.signbit(x).astype(np.int64) << 7)).astype(np.uint8)
+
+
 def to_storage(x: np.ndarray, dtype: int) -> np.ndarray:
     """Round doubles once to the storage dtype (round-to-nearest-even)."""
+    if dtype in (DTYPE_FP8_E4M3, DTYPE_FP8_E5M2):
+        return _to_fp8(x, dtype)
     if dtype == DTYPE_F32:
         return x.astype(np.float32)
     if dtype == DTYPE_F16:
@@ -78,6 +109,14 @@ def to_storage(x: np.ndarray, dtype: int) -> np.ndarray:
 
 def widen(a: np.ndarray, dtype: int) -> np.ndarray:
     """Stored bits -> float64, exactly."""
+    if dtype in (DTYPE_FP8_E4M3, DTYPE_FP8_E5M2):
+        vals, codes = _fp8_tables(dtype)
+        table = np.full(128, np.nan)
+        table[codes] = vals
+        if dtype == DTYPE_FP8_E5M2:
+            table[0x7C] = np.inf
+        mag = table[a & 0x7F]
+        return np.where(a & 0x80, -mag, mag)
     if dtype == DTYPE_F32:
         return a.astype(np.float64)
     if dtype == DTYPE_F16:
@@ -95,7 +134,8 @@ def tensor(shape, dtype: int, tensor_id: int, dist: str, scale: float = 1.0,
     Generated in chunks so the float64 temporaries stay small.
     """
     n = int(np.prod(shape))
-    out = np.empty(n, dtype=np.float32 if dtype == DTYPE_F32 else np.uint16)
+    out = np.empty(n, dtype=np.float32 if dtype == DTYPE_F32 else
+                   np.uint16 if dtype in (DTYPE_BF16, DTYPE_F16) else np.uint8)
     for s in range(0, n, _CHUNK):
         c = min(_CHUNK, n - s)
         if dist == "normal":
