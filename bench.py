@@ -26,13 +26,15 @@ HEADLINE = "cfg2_bf16_8192"
 PEAK_MFMA_16BIT_TFLOPS = 2516.6     # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16/fp16)
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-DTYPE_NAMES = {0: "f32", 1: "bf16", 2: "f16"}
+DTYPE_NAMES = {0: "f32", 1: "bf16", 2: "f16", 3: "fp8_e4m3", 4: "fp8_e5m2"}
+PEAK_MFMA_FP8_TFLOPS = 5033.2       # twice the 16-bit rate
 
 
 def bound_of(w):
     """Which roofline bounds the workload: arithmetic intensity against the ridge."""
     import workloads as wl
-    peak = PEAK_FP32_TFLOPS if w.in_dtype == wl.DTYPE_F32 else PEAK_MFMA_16BIT_TFLOPS
+    peak = (PEAK_FP32_TFLOPS if w.in_dtype == wl.DTYPE_F32 else
+            PEAK_MFMA_FP8_TFLOPS if w.in_dtype in (wl.DTYPE_FP8_E4M3, wl.DTYPE_FP8_E5M2) else PEAK_MFMA_16BIT_TFLOPS)
     ridge = peak * 1e12 / (PEAK_HBM_GBS * 1e9)
     ai = w.flops / w.algorithmic_bytes
     return ("mfma", peak) if ai >= ridge else ("hbm", PEAK_HBM_GBS)
@@ -187,7 +189,7 @@ def main():
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": args.steps}))
         return
 
-    w = wl.CONFIGS[args.workload]
+    w = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}[args.workload]
     r = time_workload(w, args.steps, args.warmup)
     line = report(w, r, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline)
     del r

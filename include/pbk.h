@@ -17,14 +17,16 @@
  *    = the default stream) and return; ordering is stream ordering.
  *  - Matrices are row-major with leading dimensions in ELEMENTS.
  *  - in_dtype is the element type of A and B (image and weights);
- *    out_dtype must be PBK_F32 or equal to in_dtype.  bias is always float.
- *    16-bit inputs are widened exactly, products are accumulated in fp32,
+ *    out_dtype must be PBK_F32 or equal to in_dtype; for the FP8 input types it
+ *    may be PBK_F32, PBK_BF16 or PBK_F16 (never FP8).  bias is always float.
+ *    16-bit and 8-bit inputs are widened exactly, products are accumulated in
+ *    fp32,
  *    the epilogue runs in fp32, and the result is rounded once to out_dtype
  *    (round-to-nearest-even).  PBK_F32 inputs use true fp32 multiply-add.
  *  - Epilogue: t = alpha * acc (+ bias[n] for the BIAS variants);
  *    out = t | max(t,0) | 0.5*t*(1+tanh(sqrt(2/pi)*(t+0.044715*t^3))).
- *    bias must be non-NULL exactly for the BIAS variants' use; it is ignored
- *    otherwise.
+ *    bias must be non-NULL for the BIAS variants and is ignored otherwise.
+ *    max(NaN, 0) is 0 (hardware maximum).
  *  - Every function returns a pbk_status.  On any status other than PBK_OK
  *    nothing was launched and the output is untouched.  A dimension of zero
  *    gives PBK_OK and does nothing (K == 0 still writes act(bias)).
@@ -54,7 +56,13 @@ typedef enum {
     PBK_ERR_HIP = 8          /* the HIP runtime reported an error at launch */
 } pbk_status;
 
-typedef enum { PBK_F32 = 0, PBK_BF16 = 1, PBK_F16 = 2 } pbk_dtype;
+typedef enum {
+    PBK_F32 = 0,
+    PBK_BF16 = 1,
+    PBK_F16 = 2,
+    PBK_FP8_E4M3 = 3,   /* OCP FP8 E4M3 (bias 7, no infinities, max 448); input type only */
+    PBK_FP8_E5M2 = 4    /* OCP FP8 E5M2 (bias 15, max 57344); input type only */
+} pbk_dtype;
 
 typedef enum {
     PBK_EPI_NONE = 0,
@@ -115,8 +123,9 @@ int pbk_version(void);
 
 /*
  * Name of the kernel configuration the most recent successful call ON THIS
- * THREAD dispatched to (for benchmarks and tests; e.g. "mfma_256x256x64_w2x4",
- * "generic_64x64").  Never NULL; "" before the first call.
+ * THREAD dispatched to (for benchmarks and tests; e.g.
+ * "mfma_128x256x32_w1x4_s3_occ2", "generic_64x64x16_fma").  Never NULL; ""
+ * before the first call.
  */
 const char* pbk_last_kernel(void);
 

@@ -10,7 +10,7 @@ import ctypes
 import os
 
 PBK_OK = 0
-PBK_F32, PBK_BF16, PBK_F16 = 0, 1, 2
+PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2 = 0, 1, 2, 3, 4
 (PBK_EPI_NONE, PBK_EPI_BIAS, PBK_EPI_RELU, PBK_EPI_BIAS_RELU,
  PBK_EPI_BIAS_GELU_TANH, PBK_EPI_GELU_TANH) = range(6)
 
@@ -39,6 +39,14 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is missing: build it first "
                               "(python -m paper_2603_06731_amd.build, or __graft_entry__.build())")
+        # One process must hold ONE HIP runtime: a second copy cannot open the
+        # device ("no ROCm-capable device").  torch ships its own libamdhip64, and
+        # callers hand this library torch's device pointers and streams, so torch's
+        # copy is loaded first and libpbk binds to it by soname.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(_LIB_PATH)
         i64, vp, f32, i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_float, ctypes.c_int
         L.pbk_matmul.argtypes = [vp, vp, vp, vp] + [i64] * 6 + [i32, i32, i32, f32, i32, vp]

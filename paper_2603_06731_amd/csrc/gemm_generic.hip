@@ -17,7 +17,7 @@ constexpr int GT = 64;     // tile edge in M and N
 constexpr int GK = 16;     // tile depth
 constexpr int GPAD = 4;
 
-template <typename T> __device__ __forceinline__ float ld_elem(const T* p, int64_t i) { return (float)p[i]; }
+template <typename T> __device__ __forceinline__ float ld_elem(const T* p, int64_t i) { return widen<T>(p[i]); }
 
 // A(i, k) of the implicit GEMM: im2col element, zero outside the image.
 template <typename T>
@@ -34,7 +34,7 @@ __device__ __forceinline__ float conv_a(const T* x, const ConvGeom& g, int i, in
     int ih = oh * g.stride_h - g.pad_h + kh * g.dil_h;
     int iw = ow * g.stride_w - g.pad_w + kw * g.dil_w;
     if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0.0f;
-    return (float)x[(((int64_t)n * g.H + ih) * g.W + iw) * g.Cin + c];
+    return widen<T>(x[(((int64_t)n * g.H + ih) * g.W + iw) * g.Cin + c]);
 }
 
 template <typename T, bool CONV>
@@ -128,13 +128,11 @@ hipError_t launch_t(const Problem& p, hipStream_t stream) {
     int tiles_m = (p.M + GT - 1) / GT, tiles_n = (p.N + GT - 1) / GT;
     long long blocks = (long long)tiles_m * tiles_n * p.batch;
     if (blocks <= 0 || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    if (p.is_conv)
-        hipLaunchKernelGGL((gemm_generic_kernel<T, true>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           p, tiles_m, tiles_n);
-    else
-        hipLaunchKernelGGL((gemm_generic_kernel<T, false>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           p, tiles_m, tiles_n);
-    return hipGetLastError();
+    Problem pa = p;
+    void* args[] = {&pa, &tiles_m, &tiles_n};
+    const void* kern = p.is_conv ? (const void*)gemm_generic_kernel<T, true>
+                                 : (const void*)gemm_generic_kernel<T, false>;
+    return hipLaunchKernel(kern, dim3((unsigned)blocks), dim3(256), args, 0, stream);
 }
 
 }  // namespace
@@ -145,6 +143,8 @@ hipError_t launch_generic(const Problem& p, hipStream_t stream, const char** nam
     case DT_F32: return launch_t<float>(p, stream);
     case DT_BF16: return launch_t<bf16_t>(p, stream);
     case DT_F16: return launch_t<f16_t>(p, stream);
+    case DT_FP8_E4M3: return launch_t<fp8_e4m3_t>(p, stream);
+    case DT_FP8_E5M2: return launch_t<fp8_e5m2_t>(p, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -11,10 +11,14 @@ static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 // entirely inside or outside the matrix; likewise N for row-major B and Cin
 // for the convolution (a piece must not straddle two filter taps).
 bool mfma_supported(const Problem& p) {
-    if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16) return false;
-    if (p.K < 8 || p.K % 8) return false;
+    const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2;
+    if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16 && !fp8) return false;
+    const int per16 = fp8 ? 16 : 8;                  // elements per 16-byte piece
+    const int esz = fp8 ? 1 : 2;
+    if (fp8 && (p.is_conv || !p.trans_b)) return false;   // FP8 path: both operands k-major
+    if (p.K < per16 || p.K % per16) return false;
     if (!al16(p.A) || !al16(p.B)) return false;
-    if (p.stride_a % 8 || p.stride_b % 8) return false;
+    if (p.stride_a % per16 || p.stride_b % per16) return false;
     // per-lane buffer offsets are 32-bit and must stay below 2^31
     const int64_t lim = (int64_t)1 << 31;
     if (p.is_conv) {
@@ -23,11 +27,11 @@ bool mfma_supported(const Problem& p) {
         int64_t halo = ((int64_t)p.conv.pad_h * p.conv.W + p.conv.pad_w + p.conv.W) * p.conv.Cin * 2;
         if (img + halo >= lim) return false;
     } else {
-        if (p.lda % 8 || p.ldb % 8) return false;
+        if (p.lda % per16 || p.ldb % per16) return false;
         if (!p.trans_b && p.N % 8) return false;
-        if (256 * p.lda * 2 + 256 >= lim) return false;
+        if (256 * p.lda * esz + 256 >= lim) return false;
     }
-    if (256 * p.ldb * 2 + 1024 >= lim) return false;
+    if (256 * p.ldb * esz + 1024 >= lim) return false;
     return true;
 }
 
@@ -40,10 +44,20 @@ static int choose_config(const Problem& p) {
 }
 
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name) {
+    const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2;
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
+    if (fp8) {
+        // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
+        // only the 64-deep configurations are built for it
+        if (cfg != 1 && cfg != 4) {
+            long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
+            cfg = (p.M >= 256 && p.N >= 256 && t256 >= 128) ? 4 : 1;
+        }
+    }
     int group_m = 8;
     if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) group_m = g; }
     *name = kMfmaConfigs[cfg].name;
+    if (fp8) return launch_mfma_fp8(p, stream, cfg, group_m);
     return p.in_dtype == DT_BF16 ? launch_mfma_bf16(p, stream, cfg, group_m)
                                  : launch_mfma_f16(p, stream, cfg, group_m);
 }

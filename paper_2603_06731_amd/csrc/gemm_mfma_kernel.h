@@ -50,17 +50,44 @@ enum : int { MODE_DENSE = 0, MODE_TRANS_B = 1, MODE_CONV = 2 };
 // build (num_records = 2^31): the load returns zeros
 constexpr unsigned kOob = 0x80000000u;
 
+// One MFMA operand fragment of a lane: CH 16-byte pieces that are consecutive
+// along k in memory.  16-bit types: 8 elements (v_mfma_f32_32x32x16);
+// FP8: 32 elements (v_mfma_f32_32x32x64_f8f6f4).  Lanes 0-31 hold the first
+// half of the instruction's k range, lanes 32-63 the second.
+template <int CH> struct Frag { short8v c[CH]; };
+
+typedef __attribute__((ext_vector_type(8))) int int8v;
+
 template <typename T> struct MfmaOp;
 template <> struct MfmaOp<bf16_t> {
-    static __device__ __forceinline__ f32x16 run(short8v a, short8v b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    static constexpr int kChunks = 1;
+    static __device__ __forceinline__ f32x16 run(const Frag<1>& a, const Frag<1>& b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a.c[0]),
+                                                       __builtin_bit_cast(bf16x8, b.c[0]), c, 0, 0, 0);
     }
 };
 template <> struct MfmaOp<f16_t> {
-    static __device__ __forceinline__ f32x16 run(short8v a, short8v b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    static constexpr int kChunks = 1;
+    static __device__ __forceinline__ f32x16 run(const Frag<1>& a, const Frag<1>& b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a.c[0]),
+                                                      __builtin_bit_cast(f16x8, b.c[0]), c, 0, 0, 0);
+    }
+};
+__device__ __forceinline__ int8v frag_bytes32(const Frag<2>& f) {
+    return __builtin_shufflevector(__builtin_bit_cast(int4v, f.c[0]), __builtin_bit_cast(int4v, f.c[1]),
+                                   0, 1, 2, 3, 4, 5, 6, 7);
+}
+// FP8: format selectors cbsz / blgp: 0 = E4M3, 1 = E5M2; all block scales zero (= unscaled instruction)
+template <> struct MfmaOp<fp8_e4m3_t> {
+    static constexpr int kChunks = 2;
+    static __device__ __forceinline__ f32x16 run(const Frag<2>& a, const Frag<2>& b, f32x16 c) {
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag_bytes32(a), frag_bytes32(b), c, 0, 0, 0, 0, 0, 0);
+    }
+};
+template <> struct MfmaOp<fp8_e5m2_t> {
+    static constexpr int kChunks = 2;
+    static __device__ __forceinline__ f32x16 run(const Frag<2>& a, const Frag<2>& b, f32x16 c) {
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag_bytes32(a), frag_bytes32(b), c, 1, 1, 0, 0, 0, 0);
     }
 };
 
@@ -318,14 +345,19 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // OCC: workgroups of this kernel meant to share a CU (bounds the register budget)
-template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
+// T: operand type fed to the MFMA; TO: 16-bit output type (used when out_dtype is not F32).
+// Sizes BK, lda, ldb, K and the batch strides are in 2-byte units whatever T is: for the FP8
+// types the host halves them (two FP8 values per unit), the staging code only moves bytes.
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
 __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mfma_kernel(Problem p, TileMap tmap) {
     constexpr bool CONV = MODE == MODE_CONV;
     constexpr bool TRANS_B = MODE == MODE_TRANS_B;
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int FM = WTM / 32, FN = WTN / 32;
-    constexpr int KSUB = BK / 16;
+    constexpr int CH = MfmaOp<T>::kChunks;         // 16-byte pieces per lane per MFMA operand
+    constexpr int KSUB = BK / (16 * CH);           // MFMA k-steps per k-tile
+    static_assert(CH == 1 || MODE == MODE_TRANS_B, "FP8 operands need both tiles k-major (trans_b)");
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE = A_BYTES + B_BYTES;
     constexpr int A_BLKS = A_BYTES / 1024, B_BLKS = B_BYTES / 1024;     // 1 KiB per wave-load
@@ -505,19 +537,23 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    auto read_a = [&](const char* sa, int ks, short8v (&af)[FM]) {
+    auto read_a = [&](const char* sa, int ks, Frag<CH> (&af)[FM]) {
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             int row = wm * WTM + i * 32 + frag_row;
-            af[i] = *(const short8v*)(sa + kmajor_offset<BK>(row, ks * 2 + frag_kc));
+#pragma unroll
+            for (int c = 0; c < CH; ++c)
+                af[i].c[c] = *(const short8v*)(sa + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
         }
     };
-    auto read_b = [&](const char* sb, int ks, short8v (&bf)[FN]) {
+    auto read_b = [&](const char* sb, int ks, Frag<CH> (&bf)[FN]) {
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             if (TRANS_B) {
                 int row = wn * WTN + j * 32 + frag_row;
-                bf[j] = *(const short8v*)(sb + kmajor_offset<BK>(row, ks * 2 + frag_kc));
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    bf[j].c[c] = *(const short8v*)(sb + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
             } else {
                 int nbyte = (wn * WTN + j * 32) * 2 + tr_nbyte;
                 int k = ks * 16 + tr_k;
@@ -525,7 +561,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k, nbyte)));
                 short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k + 4, nbyte)));
-                bf[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                bf[j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
     };
@@ -534,7 +570,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     // k-tiles: the reads of step ks+1 are issued before the MFMAs of step ks,
     // and the first fragments of the next k-tile are read (after the barrier
     // that publishes its stage) underneath the MFMAs of this tile's last step.
-    short8v af[2][FM], bf[2][FN];
+    Frag<CH> af[2][FM], bf[2][FN];
     auto mfma_step = [&](int cur) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
@@ -551,11 +587,10 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     constexpr int MFMA_BEFORE_WAIT = (KSUB - 1) * FM * FN;
     // with two stages the tile being fetched is the very next one: everything goes before the wait
     constexpr int SPAN = NSTAGE >= 3 ? MFMA_PER_TILE : MFMA_BEFORE_WAIT;
-    constexpr int GAP = SPAN / LOADS > 0 ? SPAN / LOADS : 1;
-    static_assert(GAP * LOADS <= SPAN, "not enough MFMAs to hide the loads between");
-    constexpr int EARLY = MFMA_BEFORE_WAIT / GAP < LOADS ? MFMA_BEFORE_WAIT / GAP : LOADS;
+    // piece r is issued right after MFMA number r*SPAN/LOADS of the k-tile
+    constexpr int EARLY = (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN < LOADS
+                              ? (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN : LOADS;
     static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
-    static_assert(NSTAGE < 3 || MFMA_BEFORE_WAIT % GAP == 0, "EARLY must not depend on the wave's issue phase");
     auto mfma_step_loading = [&](int cur, int ks) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
@@ -563,9 +598,12 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             for (int j = 0; j < FN; ++j) {
                 acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
                 const int idx = (ks * FM + i) * FN + j;         // MFMA number within the k-tile
-                if (idx % GAP == GAP - 1 && idx / GAP < LOADS) {
-                    issue_piece(idx / GAP, TailNo{});
-                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < LOADS; ++r) {
+                    if ((r * SPAN) / LOADS == idx) {
+                        issue_piece(r, TailNo{});
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
     };
@@ -662,7 +700,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                   : (p.epi == EPI_GELU_TANH || p.epi == EPI_BIAS_GELU_TANH) ? 2 : 0;
     const bool out_f32 = p.out_dtype == DT_F32;
     char* wlds = lds + wave * ((NSTAGE * STAGE) / NW);
-    EpiCtx<T, FM, FN, WTM, WTN, (NSTAGE * STAGE) / NW> ctx{p, acc, wlds, m0 + wm * WTM, n0 + wn * WTN, lane,
+    EpiCtx<TO, FM, FN, WTM, WTN, (NSTAGE * STAGE) / NW> ctx{p, acc, wlds, m0 + wm * WTM, n0 + wn * WTN, lane,
                                                          (int64_t)b * p.stride_c};
     if (out_f32) {
         if (act == 0) ctx.template run<0, true>(); else if (act == 1) ctx.template run<1, true>();

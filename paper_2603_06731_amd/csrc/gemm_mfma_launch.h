@@ -24,10 +24,10 @@ static const MfmaConfig kMfmaConfigs[] = {
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
 hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     constexpr int LDS_BYTES = NSTAGE * (BM * BK * 2 + BN * BK * 2);
-    auto kern = gemm_mfma_kernel<T, BM, BN, BK, WM, WN, MODE, NSTAGE, OCC>;
+    auto kern = gemm_mfma_kernel<T, TO, BM, BN, BK, WM, WN, MODE, NSTAGE, OCC>;
     static std::atomic<unsigned> attr_done{0};      // bit per device
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -47,15 +47,18 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     tm.total = (int)total;
     tm.group_m = group_m < 1 ? 1 : group_m;
     tm.xcds = 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), LDS_BYTES, stream, p, tm);
-    return hipGetLastError();
+    // hipLaunchKernel reports this launch's own status; the per-thread "last error"
+    // may hold an unrelated earlier failure of another library
+    Problem pa = p;
+    void* args[] = {&pa, &tm};
+    return hipLaunchKernel((const void*)kern, dim3((unsigned)total), dim3(WM * WN * 64), args, LDS_BYTES, stream);
 }
 
 template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
-    if (p.is_conv) return launch_one<T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC>(p, stream, group_m);
-    if (p.trans_b) return launch_one<T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC>(p, stream, group_m);
-    return launch_one<T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC>(p, stream, group_m);
+    if (p.is_conv) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC>(p, stream, group_m);
+    if (p.trans_b) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC>(p, stream, group_m);
+    return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC>(p, stream, group_m);
 }
 
 // PBK_CFG_MASK (build-time, development only): bit i set = compile configuration i.
@@ -77,6 +80,7 @@ hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int grou
 }
 
 hipError_t launch_mfma_bf16(const Problem& p, hipStream_t stream, int cfg, int group_m);
+hipError_t launch_mfma_fp8(const Problem& p, hipStream_t stream, int cfg, int group_m);
 hipError_t launch_mfma_f16(const Problem& p, hipStream_t stream, int cfg, int group_m);
 
 }  // namespace pbk

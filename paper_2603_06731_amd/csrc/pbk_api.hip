@@ -1,6 +1,7 @@
 // C ABI of libpbk: argument validation and dispatch.  No allocation, no
 // synchronisation; every call enqueues at most one kernel on the caller's stream.
 #include <hip/hip_runtime.h>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <climits>
@@ -11,9 +12,13 @@ namespace {
 
 thread_local const char* g_last_kernel = "";
 
-int64_t elem_size(int dt) { return dt == pbk::DT_F32 ? 4 : 2; }
+int64_t elem_size(int dt) {
+    return dt == pbk::DT_F32 ? 4 : (dt == pbk::DT_BF16 || dt == pbk::DT_F16) ? 2 : 1;
+}
 
-bool valid_dtype(int dt) { return dt == PBK_F32 || dt == PBK_BF16 || dt == PBK_F16; }
+bool is_fp8(int dt) { return dt == PBK_FP8_E4M3 || dt == PBK_FP8_E5M2; }
+bool valid_in_dtype(int dt) { return dt >= PBK_F32 && dt <= PBK_FP8_E5M2; }
+bool valid_out_dtype(int dt) { return dt == PBK_F32 || dt == PBK_BF16 || dt == PBK_F16; }
 
 bool aligned(const void* p, int64_t a) { return (reinterpret_cast<uintptr_t>(p) % (uintptr_t)a) == 0; }
 
@@ -30,8 +35,8 @@ int forced_choice(int* cfg) {
 }
 
 pbk_status check_common(int in_dtype, int out_dtype, int epi, const float* bias) {
-    if (!valid_dtype(in_dtype) || !valid_dtype(out_dtype)) return PBK_ERR_DTYPE;
-    if (out_dtype != PBK_F32 && out_dtype != in_dtype) return PBK_ERR_DTYPE;
+    if (!valid_in_dtype(in_dtype) || !valid_out_dtype(out_dtype)) return PBK_ERR_DTYPE;
+    if (out_dtype != PBK_F32 && out_dtype != in_dtype && !is_fp8(in_dtype)) return PBK_ERR_DTYPE;
     if (epi < PBK_EPI_NONE || epi > PBK_EPI_GELU_TANH) return PBK_ERR_EPILOGUE;
     if (pbk::epi_has_bias(epi) && !bias) return PBK_ERR_EPILOGUE;
     if (bias && !aligned(bias, 4)) return PBK_ERR_ALIGN;
@@ -49,7 +54,10 @@ pbk_status dispatch(const pbk::Problem& p, void* stream) {
         e = pbk::launch_mfma(p, (hipStream_t)stream, cfg, &name);
     else
         e = pbk::launch_generic(p, (hipStream_t)stream, &name);
-    if (e != hipSuccess) return PBK_ERR_HIP;
+    if (e != hipSuccess) {
+        std::fprintf(stderr, "libpbk: launch of %s failed: %s\n", name, hipGetErrorString(e));
+        return PBK_ERR_HIP;
+    }
     g_last_kernel = name;
     return PBK_OK;
 }

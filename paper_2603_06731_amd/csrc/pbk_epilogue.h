@@ -10,6 +10,9 @@ namespace pbk {
 
 typedef __bf16 bf16_t;
 typedef _Float16 f16_t;
+// OCP FP8 operands (OFP8 specification); storage is one byte
+struct fp8_e4m3_t { uint8_t v; };
+struct fp8_e5m2_t { uint8_t v; };
 
 __device__ __forceinline__ float gelu_tanh_f32(float t) {
     // 0.5*t*(1+tanh(u)), u = sqrt(2/pi)*(t + 0.044715 t^3); tanh(u) = 1 - 2/(exp(2u)+1)
@@ -45,5 +48,18 @@ template <> __device__ __forceinline__ uint16_t to_bits16<f16_t>(float v) {
 }
 
 template <typename T> __device__ __forceinline__ float widen(T v) { return (float)v; }
+// E5M2 is the upper byte of a binary16
+template <> __device__ __forceinline__ float widen<fp8_e5m2_t>(fp8_e5m2_t x) {
+    return (float)__builtin_bit_cast(f16_t, (uint16_t)((uint16_t)x.v << 8));
+}
+// E4M3: bias 7, subnormals m/8 * 2^-6, S.1111.111 is NaN, no infinities
+template <> __device__ __forceinline__ float widen<fp8_e4m3_t>(fp8_e4m3_t x) {
+    uint32_t b = x.v, sign = (b & 0x80u) << 24, e = (b >> 3) & 0xFu, m = b & 7u;
+    float mag;
+    if (e == 0) mag = (float)m * 0.001953125f;                       // m * 2^-9
+    else if (e == 15 && m == 7) mag = __builtin_nanf("");
+    else mag = __builtin_bit_cast(float, ((e + 120u) << 23) | (m << 20));
+    return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, mag) | sign);
+}
 
 }  // namespace pbk

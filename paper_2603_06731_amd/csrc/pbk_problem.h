@@ -5,7 +5,7 @@
 
 namespace pbk {
 
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_FP8_E4M3 = 3, DT_FP8_E5M2 = 4 };
 enum : int { EPI_NONE = 0, EPI_BIAS = 1, EPI_RELU = 2, EPI_BIAS_RELU = 3,
              EPI_BIAS_GELU_TANH = 4, EPI_GELU_TANH = 5 };
 

@@ -29,6 +29,8 @@ def to_device(a: np.ndarray):
     torch = torch_mod()
     if a.dtype == np.uint16:
         return torch.from_numpy(a.view(np.int16)).cuda()
+    if a.dtype == np.uint8:
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 

@@ -54,6 +54,10 @@ def test_matmul_argument_errors(pbk):
     assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, 7, F32, 0, 1.0, 0) == 5             # dtype
     assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, BF16, F16, 0, 1.0, 0) == 5          # in/out pair
     assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, F32, BF16, 0, 1.0, 0) == 5
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, F32, 3, 0, 1.0, 0) == 5             # FP8 is never an output type
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, 3, 4, 0, 1.0, 0) == 5
+    assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, 5, F32, 0, 1.0, 0) == 5             # unknown input type
+    assert mm(P, P, P, None, 0, 2, 2, 2, 2, 2, 3, BF16, 0, 1.0, 0) == 0            # FP8 in, bf16 out: valid pair
     assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 9) == 6           # epilogue
     assert mm(P, P, P, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 3) == 6           # bias missing
     assert mm(P + 2, P, P, None, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 0) == 4       # alignment

@@ -249,3 +249,49 @@ def test_non_default_stream():
     assert st == 0
     ref, pre = T.oracle_full(w, host)
     assert T.rel_err(T.to_host_f64(out, F16).reshape(ref.shape), ref, pre) <= T.TIGHT[F16]
+
+
+# ------------------------------------------------------------------------ FP8
+
+FP8_TYPES = [wl.DTYPE_FP8_E4M3, wl.DTYPE_FP8_E5M2]
+
+
+@pytest.mark.parametrize("dtype", FP8_TYPES)
+@pytest.mark.parametrize("out_dtype", [BF16, F16, F32])
+@pytest.mark.parametrize("cfg", [None, 1, 4])
+def test_fp8_matmul_kmajor_operands(dtype, out_dtype, cfg):
+    # both operands k-major (trans_b): MFMA path; several tiles, ragged M and N, K not a multiple of 128
+    w = wl.Workload("fp8_nt", "matmul", dtype, out_dtype, C.EPI_BIAS_GELU_TANH, alpha=0.5, M=300, N=261, K=208,
+                    trans_b=1, dist_b=("normal", 1.0 / np.sqrt(208)), dist_bias=("normal", 0.5))
+    check_full(w, force=None if cfg is None else f"mfma:{cfg}", expect_kernel="mfma")
+
+
+@pytest.mark.parametrize("dtype", FP8_TYPES)
+@pytest.mark.parametrize("mnk,trans_b", [((136, 264, 72), 0), ((67, 45, 33), 1), ((130, 129, 70), 0)])
+def test_fp8_matmul_other_layouts_take_generic_kernel(dtype, mnk, trans_b):
+    m, n, k = mnk
+    w = wl.Workload("fp8_gen", "matmul", dtype, BF16, C.EPI_BIAS_RELU, M=m, N=n, K=k, trans_b=trans_b,
+                    dist_b=("normal", 1.0 / np.sqrt(k)))
+    check_full(w, expect_kernel="generic")
+
+
+def test_fp8_batched_and_conv_generic():
+    w = wl.Workload("fp8_bmm", "batched", wl.DTYPE_FP8_E4M3, F16, C.EPI_NONE, alpha=0.25, batch=3, M=136, N=200,
+                    K=128, trans_b=1)
+    check_full(w, expect_kernel="mfma")
+    w = wl.Workload("fp8_conv", "conv", wl.DTYPE_FP8_E4M3, F32, C.EPI_BIAS_RELU, n=1, H=9, W=10, Cin=16, Cout=24,
+                    KH=3, KW=3, pad=(1, 1), dist_b=("normal", 0.1))
+    check_full(w, expect_kernel="generic")
+
+
+def test_fp8_full_size_sampled():
+    import paper_2603_06731_amd as pbk
+    w = wl.EXTRA_CONFIGS["fp8_e4m3_8192_nt"]
+    host = wl.make_inputs(w)
+    st, out = T.run_workload(w, T.upload(host))
+    assert st == 0 and "mfma" in pbk.pbk_last_kernel()
+    b, i, j = T.sample_coords(w, 3000)
+    ref, pre = T.oracle_sampled(w, host, b, i, j)
+    err = T.rel_err(T.gather_output(out, w, b, i, j), ref, pre)
+    print(f"fp8 8192^3 kernel={pbk.pbk_last_kernel()} err={err:.3e}", flush=True)
+    assert err <= T.TIGHT[BF16], err

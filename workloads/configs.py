@@ -117,6 +117,15 @@ CONFIGS = {
 }
 
 
+# Further workloads beyond the five headline ones (widening per the scope table's "next" rows).
+EXTRA_CONFIGS = {
+    "fp8_e4m3_8192_nt": Workload(
+        "fp8_e4m3_8192_nt", "matmul", gen.DTYPE_FP8_E4M3, _BF16, EPI_BIAS_RELU, M=8192, N=8192, K=8192,
+        trans_b=1, dist_a=("normal", 1.0), dist_b=("normal", 1.0 / math.sqrt(8192)),
+        dist_bias=("normal", 0.1)),
+}
+
+
 def make_inputs(w: Workload) -> dict:
     """Draw the workload's tensors (storage dtype, numpy, host memory).
 
