@@ -1,15 +1,17 @@
-// MFMA contraction kernel for gfx950: 16-bit inputs, fp32 accumulation.
+// MFMA contraction kernel for gfx950: 16-bit or FP8 inputs, fp32 accumulation.
 //
 // Structure (paper Sec. 4.3 multi-level tiling and fast buffers, Sec. 4.5
 // on-the-fly packing, Sec. 4.6 mapping to matrix units, App. A.2 overlap of
 // copy and compute), re-designed for CDNA4:
 //   workgroup tile BM x BN x BK  ->  WM x WN waves, each a (BM/WM) x (BN/WN)
-//   register tile of 32x32 MFMA blocks (v_mfma_f32_32x32x16), accumulators
-//   live in registers for the whole K loop.
+//   register tile of 32x32 MFMA blocks (v_mfma_f32_32x32x16 for 16-bit types,
+//   v_mfma_f32_32x32x64_f8f6f4 for FP8), accumulators live in registers for
+//   the whole K loop.
 //   Global -> LDS staging without passing through registers: every wave issues
 //   buffer_load_dwordx4 ... lds, each writing 64 x 16 bytes to 1 KiB of LDS.
-//   Two LDS stages: the loads of k-tile t+1 are in flight while k-tile t is
-//   multiplied; one barrier per k-tile.  Pieces that lie outside the matrix
+//   A ring of NSTAGE LDS stages: the loads of k-tiles t+1 .. t+NSTAGE-1 are in
+//   flight while k-tile t is multiplied; one barrier per k-tile; a wave's loads
+//   are spread between its MFMAs.  Pieces that lie outside the matrix
 //   (rows beyond M, columns beyond N, k beyond K, convolution taps in the
 //   padding) are given an out-of-range buffer offset, for which the hardware
 //   writes zeros to LDS: partial tiles are zero-filled for free.
@@ -23,7 +25,9 @@
 //   is [BN][BK] and is handled exactly like A.
 //   The MFMA is issued with the operands swapped (B fragment as srcA, A
 //   fragment as srcB) so each lane ends up with 4 consecutive n of one row m:
-//   the epilogue then works on 4-wide pieces and stores 8 or 16 bytes.
+//   the epilogue (scale, bias, activation, rounding) works on 4-wide pieces in
+//   registers; the rounded tile passes through the wave's LDS slice once to
+//   change lane ownership and leaves as 16-byte stores along rows.
 //   Rows/columns beyond M/N are never stored.
 #pragma once
 #include <hip/hip_runtime.h>
