@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
                                                + [i32, i32, f32, i32, i64, vp, vp, vp])
         L.oracle_conv2d_nhwc_at.argtypes = ([vp, vp, vp, vp, vp] + [i64] * 13
                                             + [i32, f32, i32, i64, vp, vp, vp, vp])
+        L.oracle_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32]
+        L.oracle_attention_rows.argtypes = [vp, vp, vp, vp, vp] + [i64] * 12 + [i32, f32, i64, vp, vp]
         L.oracle_conv_out_dim.argtypes = [i64] * 5
         L.oracle_conv_out_dim.restype = i64
         L.oracle_epilogue.argtypes = [ctypes.c_double, ctypes.c_double, f32, i32]
@@ -208,6 +210,52 @@ def conv2d_nhwc_at(x, w, bias, sn, soh, sow, sco, *, dtype, stride=(1, 1), pad=(
                                      len(out), *[_ptr(v) for v in idx])
     _rc(rc, "conv2d_nhwc_at")
     return out, pre
+
+
+def _attention_args(Q, K, V, bias, dtype):
+    Q = _check_in(np.ascontiguousarray(Q), dtype)
+    K = _check_in(np.ascontiguousarray(K), dtype)
+    V = _check_in(np.ascontiguousarray(V), dtype)
+    if Q.ndim != 3 or K.ndim != 3 or V.shape != K.shape or Q.shape[0] != K.shape[0] or Q.shape[2] != K.shape[2]:
+        raise ValueError("attention expects Q [batch][Nq][D], K and V [batch][Nk][D]")
+    batch, Nq, D = Q.shape
+    Nk = K.shape[1]
+    ld_bias = stride_bias = 0
+    if bias is not None:
+        if bias.dtype != np.float32 or not bias.flags.c_contiguous:
+            raise TypeError("attention bias must be contiguous float32")
+        if bias.shape == (Nq, Nk):
+            ld_bias, stride_bias = Nk, 0
+        elif bias.shape == (batch, Nq, Nk):
+            ld_bias, stride_bias = Nk, Nq * Nk
+        else:
+            raise ValueError("attention bias must be [Nq][Nk] or [batch][Nq][Nk]")
+    return Q, K, V, batch, Nq, Nk, D, ld_bias, stride_bias
+
+
+def attention(Q, K, V, bias=None, *, dtype, alpha=1.0):
+    """softmax(alpha * Q K^T + bias) V as float64 [batch][Nq][D]."""
+    Q, K, V, batch, Nq, Nk, D, ld_bias, stride_bias = _attention_args(Q, K, V, bias, dtype)
+    out = np.empty((batch, Nq, D), dtype=np.float64)
+    rc = lib().oracle_attention(_ptr(Q), _ptr(K), _ptr(V), _ptr(bias), _ptr(out),
+                                batch, Nq, Nk, D, D, D, D, D, Nq * D, Nk * D, Nk * D, Nq * D,
+                                ld_bias, stride_bias, dtype, float(alpha))
+    _rc(rc, "attention")
+    return out
+
+
+def attention_rows(Q, K, V, bias, sb, si, *, dtype, alpha=1.0):
+    """Rows (sb[s], si[s]) of the same result: float64 [nsamp][D]."""
+    Q, K, V, batch, Nq, Nk, D, ld_bias, stride_bias = _attention_args(Q, K, V, bias, dtype)
+    sb = np.ascontiguousarray(sb, dtype=np.int64)
+    si = np.ascontiguousarray(si, dtype=np.int64)
+    out = np.empty((sb.size, D), dtype=np.float64)
+    rc = lib().oracle_attention_rows(_ptr(Q), _ptr(K), _ptr(V), _ptr(bias), _ptr(out),
+                                     batch, Nq, Nk, D, D, D, D, Nq * D, Nk * D, Nk * D,
+                                     ld_bias, stride_bias, dtype, float(alpha),
+                                     sb.size, _ptr(sb), _ptr(si))
+    _rc(rc, "attention_rows")
+    return out
 
 
 def epilogue(s, bias, alpha, epi) -> float:

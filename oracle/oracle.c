@@ -7,6 +7,7 @@
 #include "oracle.h"
 
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -360,6 +361,123 @@ int oracle_conv2d_nhwc_at(const void* x, const void* w, const float* bias,
         out[s] = activation(t, epi);
     }
     return 0;
+}
+
+/* ---- attention ---------------------------------------------------------- */
+
+/* One output row (b, i) of  softmax(alpha * Q K^T + bias) V,  by the definition:
+ * scores s_j, weights p_j = exp(s_j) / sum_l exp(s_l), out[d] = sum_j p_j V[j][d].
+ * exp(s_j) is evaluated as exp(s_j - max_l s_l): the quotient is unchanged and
+ * nothing overflows.  `scores` is scratch for Nk doubles. */
+static void attention_row(const void* Q, const void* K, const void* V, const float* bias,
+                          int dtype, int64_t q_off, int64_t k_off, int64_t v_off,
+                          int64_t bias_off, int64_t Nk, int64_t D,
+                          int64_t ldk, int64_t ldv, float alpha,
+                          double* scores, double* out_row)
+{
+    double top = -INFINITY;
+    for (int64_t j = 0; j < Nk; ++j) {
+        double dot = 0.0;
+        for (int64_t c = 0; c < D; ++c)
+            dot += load(Q, dtype, q_off + c) * load(K, dtype, k_off + j * ldk + c);
+        double s = (double)alpha * dot;
+        if (bias) s += (double)bias[bias_off + j];
+        scores[j] = s;
+        if (s > top) top = s;
+    }
+    double denom = 0.0;
+    for (int64_t j = 0; j < Nk; ++j) {
+        scores[j] = exp(scores[j] - top);
+        denom += scores[j];
+    }
+    for (int64_t d = 0; d < D; ++d) {
+        double acc = 0.0;
+        for (int64_t j = 0; j < Nk; ++j)
+            acc += scores[j] * load(V, dtype, v_off + j * ldv + d);
+        out_row[d] = acc / denom;
+    }
+}
+
+static int check_attention(const void* Q, const void* K, const void* V, const double* out,
+                           int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                           int64_t ldq, int64_t ldk, int64_t ldv, int dtype)
+{
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return -1;
+    if (batch < 1 || Nq < 1 || Nk < 1 || D < 1) return -4;
+    if (ldq < D || ldk < D || ldv < D) return -5;
+    if (!Q || !K || !V || !out) return -6;
+    return 0;
+}
+
+int oracle_attention(const void* Q, const void* K, const void* V, const float* bias,
+                     double* out,
+                     int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                     int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                     int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                     int64_t ld_bias, int64_t stride_bias,
+                     int dtype, float alpha)
+{
+    int rc = check_attention(Q, K, V, out, batch, Nq, Nk, D, ldq, ldk, ldv, dtype);
+    if (rc) return rc;
+    if (ldo < D || (bias && ld_bias < Nk)) return -5;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* scores = (double*)malloc((size_t)Nk * sizeof(double));
+        if (!scores) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 4)
+            for (int64_t r = 0; r < batch * Nq; ++r) {
+                int64_t b = r / Nq, i = r % Nq;
+                attention_row(Q, K, V, bias, dtype, b * stride_q + i * ldq, b * stride_k,
+                              b * stride_v, b * stride_bias + i * ld_bias, Nk, D, ldk, ldv,
+                              alpha, scores, out + b * stride_o + i * ldo);
+            }
+        }
+        free(scores);
+    }
+    return failed ? -8 : 0;
+}
+
+int oracle_attention_rows(const void* Q, const void* K, const void* V, const float* bias,
+                          double* out,
+                          int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                          int64_t ldq, int64_t ldk, int64_t ldv,
+                          int64_t stride_q, int64_t stride_k, int64_t stride_v,
+                          int64_t ld_bias, int64_t stride_bias,
+                          int dtype, float alpha,
+                          int64_t nsamp, const int64_t* sb, const int64_t* si)
+{
+    int rc = check_attention(Q, K, V, out, batch, Nq, Nk, D, ldq, ldk, ldv, dtype);
+    if (rc) return rc;
+    if ((bias && ld_bias < Nk) || nsamp < 0 || !sb || !si) return -5;
+    for (int64_t s = 0; s < nsamp; ++s)
+        if (sb[s] < 0 || sb[s] >= batch || si[s] < 0 || si[s] >= Nq) return -7;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* scores = (double*)malloc((size_t)Nk * sizeof(double));
+        if (!scores) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t s = 0; s < nsamp; ++s) {
+                int64_t b = sb[s], i = si[s];
+                attention_row(Q, K, V, bias, dtype, b * stride_q + i * ldq, b * stride_k,
+                              b * stride_v, b * stride_bias + i * ld_bias, Nk, D, ldk, ldv,
+                              alpha, scores, out + s * D);
+            }
+        }
+        free(scores);
+    }
+    return failed ? -8 : 0;
 }
 
 int oracle_num_threads(void)

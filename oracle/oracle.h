@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the fused dense contraction  out = act(alpha * (A . B) + bias).
+ * CPU oracle for the fused dense contraction  out = act(alpha * (A . B) + bias)
+ * and for the attention layer  softmax(alpha * Q K^T + bias) V.
  *
  * TEST INFRASTRUCTURE ONLY.  This is the plain mathematical definition written
  * out in IEEE double: a triple loop for matmul, a seven-deep loop nest for the
@@ -90,6 +91,32 @@ int oracle_conv2d_nhwc_at(const void* x, const void* w, const float* bias,
                           int dtype, float alpha, int epi,
                           int64_t nsamp, const int64_t* sn, const int64_t* soh,
                           const int64_t* sow, const int64_t* sco);
+
+/* Attention layer (paper Sec. 4.4; the operator of its attention example):
+ *   out[b][i][d] = sum_j P[b][i][j] * V[b][j][d],
+ *   P[b][i][:]   = softmax_j( alpha * sum_c Q[b][i][c]*K[b][j][c] + bias[b][i][j] ).
+ * Q [batch][Nq][D] (row stride ldq, batch stride stride_q), K, V [batch][Nk][D]
+ * likewise, out [batch][Nq][D] doubles (ldo, stride_o), bias float
+ * [batch][Nq][Nk] (ld_bias, stride_bias; stride 0 shares one matrix; NULL = no
+ * bias).  dtype F32, BF16 or F16.  A bias of -inf removes a key from a row; a
+ * row with every key removed is 0/0 and comes back NaN. */
+int oracle_attention(const void* Q, const void* K, const void* V, const float* bias,
+                     double* out,
+                     int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                     int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                     int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                     int64_t ld_bias, int64_t stride_bias,
+                     int dtype, float alpha);
+
+/* Same definition for listed rows only: out[s][0..D) is row (sb[s], si[s]). */
+int oracle_attention_rows(const void* Q, const void* K, const void* V, const float* bias,
+                          double* out,
+                          int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                          int64_t ldq, int64_t ldk, int64_t ldv,
+                          int64_t stride_q, int64_t stride_k, int64_t stride_v,
+                          int64_t ld_bias, int64_t stride_bias,
+                          int dtype, float alpha,
+                          int64_t nsamp, const int64_t* sb, const int64_t* si);
 
 /* Output size of one spatial dimension, or -1 if empty/invalid. */
 int64_t oracle_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad, int64_t dil);
