@@ -7,7 +7,8 @@
  * (the tile of im2col rows is packed on the fly; the im2col matrix never
  * exists in memory).  This is the operator the paper's code generator targets:
  * a tiled matmul/convolution nest with its pointwise tail fused into the
- * output tile (paper Sec. 4.3, 4.5, 4.6).
+ * output tile (paper Sec. 4.3, 4.5, 4.6).  Also the attention layer
+ * softmax(alpha Q K^T + bias) V as one fused kernel (paper Sec. 4.4).
  *
  * Conventions shared by every entry point
  *  - All data pointers are DEVICE pointers valid on the device that `stream`
@@ -114,6 +115,33 @@ pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* b
                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                            pbk_dtype in_dtype, pbk_dtype out_dtype,
                            float alpha, pbk_epilogue epi, void* stream);
+
+/*
+ * Attention layer, every operator fused into one kernel          (paper Sec. 4.4)
+ *   O[b][i][:] = sum_j P[b][i][j] * V[b][j][:],
+ *   P[b][i][:] = softmax over j of ( alpha * sum_c Q[b][i][c] * K[b][j][c] + bias[b][i][j] ).
+ * `batch` independent entries (batch x heads flattened).  Q and O are Nq x D, K
+ * and V are Nk x D, row-major with row strides ldq, ldk, ldv, ldo >= D and batch
+ * strides stride_* (elements; 0 for K, V, Q shares one operand; stride_o must be
+ * >= (Nq-1)*ldo + D when batch > 1).  bias is float, Nq x Nk with row stride
+ * ld_bias >= Nk and batch stride stride_bias (0 = one matrix for all entries), or
+ * NULL.  A bias of -inf removes a key from a row (masks); a row whose keys are all
+ * removed has no defined result.  dtype (PBK_F32, PBK_BF16 or PBK_F16) is the
+ * type of Q, K, V and O.  Scores and the softmax are computed in fp32; for the
+ * 16-bit types the weights are rounded to dtype before they multiply V (fp32
+ * accumulation), and O is rounded once.  The Nq x Nk score matrix never exists
+ * in memory.  Nk must be >= 1 unless batch or Nq is 0; D must be >= 1 and, on
+ * the generic path, <= 512 (else PBK_ERR_UNSUPPORTED).  The matrix-unit kernel
+ * takes 16-bit types with D of 32, 64 or 128, 16-byte aligned Q, K, V, 8-byte
+ * aligned O, row and batch strides that are multiples of 8 (4 for O); anything
+ * else runs on the generic kernel.
+ */
+pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,
+                         int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                         int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                         int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                         int64_t ld_bias, int64_t stride_bias,
+                         pbk_dtype dtype, float alpha, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* pbk_status_string(pbk_status s);

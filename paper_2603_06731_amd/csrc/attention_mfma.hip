@@ -1,0 +1,318 @@
+// Fused attention kernel for gfx950: O = softmax(alpha Q K^T + bias) V with the
+// scores, the softmax and the weights living only in registers.
+//
+// This is the hand-written counterpart of what the paper reaches with its
+// reduce-reduce fusion (the softmax reductions and the second matmul fused
+// into the key loop of the first, with a correction applied to the running
+// output whenever the running row maximum moves) and its matrix-unit fusion
+// (nothing between the two matmuls goes back to on-chip memory), Sec. 4.4.
+//
+// Work split: a workgroup of 4 waves owns 128 query rows of one batch entry,
+// each wave 32 of them, and walks the keys in tiles of 64.  K and V tiles are
+// shared by the 4 waves: they are fetched straight into LDS
+// (buffer_load ... lds, double buffered, one barrier per tile), rows beyond Nk
+// arrive as zeros.  Two workgroups share a CU, so that one wave's softmax
+// arithmetic overlaps the other's MFMAs on every SIMD.
+//
+// Register layouts (v_mfma_f32_32x32x16, D[i][j] += sum_k A[i][k] B[k][j]; a lane
+// supplies row i = lane%32 of A and column j = lane%32 of B, 8 consecutive k
+// starting at 8*(lane/32), and receives column j = lane%32, rows
+// 8g + 4*(lane/32) + t of D in register 4g + t):
+//   S^T = K Q^T:  A = K rows from LDS (k-major, ds_read_b128), B = Q (registers,
+//                 loaded once).  A lane then holds 16 scores of ONE query per
+//                 32-key block: the row maximum and sum need one exchange with
+//                 lane^32 only, and the correction factor is a per-lane scalar.
+//   O^T = V^T P^T: B = the lane's own weights, rounded to 16 bits, taken in
+//                 the key order the lane already holds them (contraction order
+//                 is free as long as both operands agree); A = V^T produced by
+//                 the transposing LDS read from the d-contiguous V tile with the
+//                 matching key order.  No weight ever changes lane or touches LDS.
+#include "gemm_mfma_kernel.h"
+
+namespace pbk {
+namespace {
+
+constexpr int ATT_BQ = 128;     // query rows per workgroup
+constexpr int ATT_BKV = 64;     // keys per tile
+constexpr int ATT_NW = 4;
+
+// 64-byte-chunk swizzle of the d-contiguous V tile [keys][D]: rows that share
+// LDS banks (256-byte period) get different chunk positions.
+template <int D> __device__ __forceinline__ int v_swz(int key) {
+    constexpr int RPB = 256 / (D * 2) > 0 ? 256 / (D * 2) : 1;   // rows per bank period
+    constexpr int C64 = (D * 2) / 64;                            // 64-byte chunks per row
+    return (key / RPB) % C64;
+}
+template <int D> __device__ __forceinline__ int v_offset(int key, int dbyte) {
+    return key * (D * 2) + ((((dbyte >> 6) ^ v_swz<D>(key)) << 6) | (dbyte & 63));
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename T, int D>
+__global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProblem p, int q_tiles, int total) {
+    constexpr int KS = D / 16;                    // k16 steps of Q K^T
+    constexpr int JD = D / 32;                    // 32-wide blocks of the head dimension
+    constexpr int TILE = ATT_BKV * D * 2;         // bytes of one K or V tile
+    constexpr int STAGE = 2 * TILE;
+    constexpr int BLKS = TILE / 1024;             // 1 KiB wave-loads per tile
+    constexpr int CPW = BLKS / ATT_NW;            // per wave
+    static_assert(BLKS % ATT_NW == 0 && CPW >= 1, "tile must split evenly over the waves");
+    constexpr int CPR = D / 8;                    // 16-byte slots per row
+    constexpr int ROWS = 64 / CPR;                // rows per wave-load
+    constexpr float LOG2E = 1.4426950408889634f;
+
+    extern __shared__ __attribute__((aligned(1024))) char lds[];   // 2 x (K tile | V tile)
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane >> 5, col = lane & 31;
+
+    // workgroups are dealt round-robin to the 8 XCDs: regroup so that one XCD (one L2)
+    // owns a contiguous run of (batch, query tile) pairs and re-uses that batch's K and V
+    const int xq = total / 8, xr = total % 8;
+    const int xcd = blockIdx.x % 8, local = blockIdx.x / 8;
+    const int id = xcd * xq + (xcd < xr ? xcd : xr) + local;
+    const int b = id / q_tiles;
+    const int q0 = (id - b * q_tiles) * ATT_BQ + wave * 32;
+
+    const char* Kb = (const char*)p.K + (int64_t)b * p.stride_k * 2;
+    const char* Vb = (const char*)p.V + (int64_t)b * p.stride_v * 2;
+
+    // ---- per-lane source offsets of the direct-to-LDS loads (lane i lands at byte 16 i)
+    unsigned k_voff[CPW], v_voff[CPW];
+    int ld_row[CPW];
+#pragma unroll
+    for (int r = 0; r < CPW; ++r) {
+        const int row = (wave * CPW + r) * ROWS + lane / CPR;
+        const int slot = lane % CPR;
+        ld_row[r] = row;
+        k_voff[r] = (unsigned)(row * (int)p.ldk * 2 + ((slot ^ kmajor_swz<D>(row)) << 4));
+        const int c64 = (slot >> 2) ^ v_swz<D>(row);
+        v_voff[r] = (unsigned)(row * (int)p.ldv * 2 + ((c64 << 6) | ((slot & 3) << 4)));
+    }
+    const unsigned lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr_of(lds));
+    auto issue_tile = [&](int kb, int stage) {
+        const int key0 = kb * ATT_BKV;
+        const int4v rk = make_rsrc(Kb + (int64_t)key0 * p.ldk * 2);
+        const int4v rv = make_rsrc(Vb + (int64_t)key0 * p.ldv * 2);
+        const unsigned sk = lds_base + stage * STAGE, sv = sk + TILE;
+#pragma unroll
+        for (int r = 0; r < CPW; ++r) {
+            const bool ok = key0 + ld_row[r] < p.Nk;
+            dma16(rk, sk + (wave * CPW + r) * 1024, ok ? k_voff[r] : kOob);
+        }
+#pragma unroll
+        for (int r = 0; r < CPW; ++r) {
+            const bool ok = key0 + ld_row[r] < p.Nk;
+            dma16(rv, sv + (wave * CPW + r) * 1024, ok ? v_voff[r] : kOob);
+        }
+    };
+
+    const int NB = (p.Nk + ATT_BKV - 1) / ATT_BKV;
+    issue_tile(0, 0);
+
+    // ---- Q fragments: column q = lane%32, d = 16 ks + 8 h .. +8, straight from global
+    Frag<1> qf[KS];
+    {
+        const int q = q0 + col;
+        const char* qp = (const char*)p.Q + ((int64_t)b * p.stride_q + (int64_t)q * p.ldq) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            short8v v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (q < p.Nq) v = *(const short8v*)(qp + (ks * 16 + h * 8) * 2);
+            qf[ks].c[0] = v;
+        }
+    }
+
+    f32x16 o_acc[JD];
+#pragma unroll
+    for (int j = 0; j < JD; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[j][e] = 0.0f;
+    float m_run = -INFINITY;      // running row maximum (log2 domain), same in lane and lane^32
+    float l_run = 0.0f;           // this lane's share of the running row sum
+
+    const float c1 = p.alpha * LOG2E;
+    const bool bias_vec = p.bias && (((uintptr_t)p.bias & 15) == 0) && (p.ld_bias % 4 == 0) && (p.stride_bias % 4 == 0);
+    const float* bias_row = p.bias ? p.bias + (int64_t)b * p.stride_bias + (int64_t)(q0 + col) * p.ld_bias : nullptr;
+    const bool q_ok = q0 + col < p.Nq;
+
+    // transposing-read lane constants: key (lane%16)/4 + 4h within a 16-key step, d = 4*(lane%4) of a 16-wide block
+    const int tr_key = ((lane & 15) >> 2) + (h << 2);
+    const int tr_dbyte = ((((lane >> 4) & 1) << 4) + ((lane & 3) << 2)) * 2;
+
+    for (int kb = 0; kb < NB; ++kb) {
+        const int stage = kb & 1;
+        wait_vmcnt<0>();              // this wave's pieces of tile kb have landed
+        __syncthreads();              // everyone's have; everyone is done reading the other stage
+        if (kb + 1 < NB) issue_tile(kb + 1, stage ^ 1);
+        const char* sk = lds + stage * STAGE;
+        const char* sv = sk + TILE;
+        const int key0 = kb * ATT_BKV;
+
+        // ---- S^T = K Q^T for two 32-key blocks
+        f32x16 s_acc[2];
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s_acc[k2][e] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2) {
+                Frag<1> kf;
+                kf.c[0] = *(const short8v*)(sk + kmajor_offset<D>(k2 * 32 + col, ks * 2 + h));
+                s_acc[k2] = MfmaOp<T>::run(kf, qf[ks], s_acc[k2]);
+            }
+        }
+
+        // ---- scores in the log2 domain, bias, removal of keys beyond Nk
+        // register 4g + t of block k2 is key key0 + 32 k2 + 8 g + 4 h + t
+        float sc[2][16];
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[k2][e] = s_acc[k2][e] * c1;
+        if (p.bias) {
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int key = key0 + k2 * 32 + g * 8 + h * 4;
+                    float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (q_ok) {
+                        if (bias_vec && key + 3 < p.Nk) {
+                            f32x4 v4 = *(const f32x4*)(bias_row + key);
+                            bv[0] = v4[0]; bv[1] = v4[1]; bv[2] = v4[2]; bv[3] = v4[3];
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < 4; ++t)
+                                if (key + t < p.Nk) bv[t] = bias_row[key + t];
+                        }
+                    }
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) sc[k2][g * 4 + t] = fmaf(bv[t], LOG2E, sc[k2][g * 4 + t]);
+                }
+        }
+        if (key0 + ATT_BKV > p.Nk) {
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = key0 + k2 * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+                    if (key >= p.Nk) sc[k2][e] = -INFINITY;
+                }
+        }
+
+        // ---- online softmax: new maximum, correction of what was accumulated, weights
+        float bmax = -INFINITY;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) bmax = fmaxf(bmax, sc[k2][e]);
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+        const float m_new = fmaxf(m_run, bmax);
+        const float m_use = m_new == -INFINITY ? 0.0f : m_new;    // every key so far removed by a -inf bias
+        const float corr = fast_exp2(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.0f;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                sc[k2][e] = fast_exp2(sc[k2][e] - m_use);
+                psum += sc[k2][e];
+            }
+        l_run = l_run * corr + psum;
+#pragma unroll
+        for (int j = 0; j < JD; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o_acc[j][e] *= corr;
+
+        // ---- O^T += V^T P^T, four 16-key steps; step s uses registers 8 (s%2) .. +8 of block s/2,
+        // i.e. keys 16 s + 8 (e/4) + 4 h + e%4 for element e: V is read in the same order
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            Frag<1> pf;
+            int4v pw;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                pw[i] = (int)pack2<T>(sc[s >> 1][(s & 1) * 8 + 2 * i], sc[s >> 1][(s & 1) * 8 + 2 * i + 1]);
+            pf.c[0] = __builtin_bit_cast(short8v, pw);
+#pragma unroll
+            for (int j = 0; j < JD; ++j) {
+                const int key = s * 16 + tr_key;
+                const int dbyte = j * 64 + tr_dbyte;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key, dbyte)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key + 8, dbyte)));
+                Frag<1> vf;
+                vf.c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o_acc[j] = MfmaOp<T>::run(vf, pf, o_acc[j]);
+            }
+        }
+    }
+
+    // ---- normalise and store: the lane holds, for query q0 + lane%32, d = 32 j + 8 g + 4 h + 0..3
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.0f / l_tot;
+    if (q_ok) {
+        char* op = (char*)p.O + ((int64_t)b * p.stride_o + (int64_t)(q0 + col) * p.ldo) * 2;
+#pragma unroll
+        for (int j = 0; j < JD; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                int2v w;
+                w[0] = (int)pack2<T>(o_acc[j][g * 4 + 0] * inv, o_acc[j][g * 4 + 1] * inv);
+                w[1] = (int)pack2<T>(o_acc[j][g * 4 + 2] * inv, o_acc[j][g * 4 + 3] * inv);
+                *(int2v*)(op + (j * 32 + g * 8 + h * 4) * 2) = w;
+            }
+    }
+}
+
+template <typename T, int D>
+hipError_t launch_d(const AttnProblem& p, hipStream_t stream) {
+    constexpr int LDS_BYTES = 2 * 2 * ATT_BKV * D * 2;
+    auto kern = attention_mfma_kernel<T, D>;
+    int q_tiles = (p.Nq + ATT_BQ - 1) / ATT_BQ;
+    long long total = (long long)q_tiles * p.batch;
+    if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    int tot = (int)total;
+    AttnProblem pa = p;
+    void* args[] = {&pa, &q_tiles, &tot};
+    return hipLaunchKernel((const void*)kern, dim3((unsigned)total), dim3(ATT_NW * 64), args, LDS_BYTES, stream);
+}
+
+template <typename T>
+hipError_t launch_t(const AttnProblem& p, hipStream_t stream, const char** name) {
+    switch (p.D) {
+    case 32: *name = "attn_mfma_q128_kv64_d32"; return launch_d<T, 32>(p, stream);
+    case 64: *name = "attn_mfma_q128_kv64_d64"; return launch_d<T, 64>(p, stream);
+    case 128: *name = "attn_mfma_q128_kv64_d128"; return launch_d<T, 128>(p, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+bool al(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+// The fused kernel moves K and V in whole aligned 16-byte pieces and Q in
+// 16-byte, O in 8-byte pieces.
+bool attention_mfma_supported(const AttnProblem& p) {
+    if (p.dtype != DT_BF16 && p.dtype != DT_F16) return false;
+    if (p.D != 32 && p.D != 64 && p.D != 128) return false;
+    if (!al(p.Q, 16) || !al(p.K, 16) || !al(p.V, 16) || !al(p.O, 8)) return false;
+    if (p.ldq % 8 || p.ldk % 8 || p.ldv % 8 || p.ldo % 4) return false;
+    if (p.stride_q % 8 || p.stride_k % 8 || p.stride_v % 8 || p.stride_o % 4) return false;
+    // per-lane buffer offsets are 32-bit and must stay below 2^31
+    const int64_t lim = (int64_t)1 << 31;
+    if (ATT_BKV * p.ldk * 2 + 256 >= lim || ATT_BKV * p.ldv * 2 + 256 >= lim) return false;
+    return true;
+}
+
+hipError_t launch_attention_mfma(const AttnProblem& p, hipStream_t stream, const char** name) {
+    return p.dtype == DT_BF16 ? launch_t<bf16_t>(p, stream, name) : launch_t<f16_t>(p, stream, name);
+}
+
+}  // namespace pbk

@@ -151,6 +151,52 @@ pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* b
     return dispatch(p, stream);
 }
 
+pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,
+                         int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                         int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                         int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                         int64_t ld_bias, int64_t stride_bias,
+                         pbk_dtype dtype, float alpha, void* stream) {
+    if (dtype != PBK_F32 && dtype != PBK_BF16 && dtype != PBK_F16) return PBK_ERR_DTYPE;
+    if (batch < 0 || Nq < 0 || Nk < 0 || D < 1) return PBK_ERR_SHAPE;
+    if (batch > INT_MAX || Nq > INT_MAX || Nk > INT_MAX || D > INT_MAX) return PBK_ERR_SHAPE;
+    if (batch == 0 || Nq == 0) return PBK_OK;
+    if (Nk == 0) return PBK_ERR_SHAPE;                 // a softmax over no keys
+    if (batch * Nq > INT_MAX) return PBK_ERR_SHAPE;
+    if (!Q || !K || !V || !O) return PBK_ERR_NULL;
+    if (ldq < D || ldk < D || ldv < D || ldo < D) return PBK_ERR_STRIDE;
+    if (stride_q < 0 || stride_k < 0 || stride_v < 0 || stride_o < 0) return PBK_ERR_STRIDE;
+    if (batch > 1 && stride_o < (Nq - 1) * ldo + D) return PBK_ERR_STRIDE;
+    if (bias && (ld_bias < Nk || stride_bias < 0)) return PBK_ERR_STRIDE;
+    const int64_t esz = elem_size(dtype);
+    if (!aligned(Q, esz) || !aligned(K, esz) || !aligned(V, esz) || !aligned(O, esz)) return PBK_ERR_ALIGN;
+    if (bias && !aligned(bias, 4)) return PBK_ERR_ALIGN;
+
+    pbk::AttnProblem p{};
+    p.Q = Q; p.K = K; p.V = V; p.bias = bias; p.O = O;
+    p.batch = (int)batch; p.Nq = (int)Nq; p.Nk = (int)Nk; p.D = (int)D;
+    p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.ldo = ldo;
+    p.stride_q = stride_q; p.stride_k = stride_k; p.stride_v = stride_v; p.stride_o = stride_o;
+    p.ld_bias = bias ? ld_bias : 0; p.stride_bias = bias ? stride_bias : 0;
+    p.dtype = dtype; p.alpha = alpha;
+
+    int cfg = -1;
+    const int force = forced_choice(&cfg);
+    const bool can_mfma = pbk::attention_mfma_supported(p);
+    if (force == 2 && !can_mfma) return PBK_ERR_UNSUPPORTED;
+    const bool use_mfma = can_mfma && force != 1;
+    if (!use_mfma && D > 512) return PBK_ERR_UNSUPPORTED;
+    const char* name = "";
+    hipError_t e = use_mfma ? pbk::launch_attention_mfma(p, (hipStream_t)stream, &name)
+                            : pbk::launch_attention_generic(p, (hipStream_t)stream, &name);
+    if (e != hipSuccess) {
+        std::fprintf(stderr, "libpbk: launch of %s failed: %s\n", name, hipGetErrorString(e));
+        return PBK_ERR_HIP;
+    }
+    g_last_kernel = name;
+    return PBK_OK;
+}
+
 const char* pbk_status_string(pbk_status s) {
     switch (s) {
     case PBK_OK: return "ok";

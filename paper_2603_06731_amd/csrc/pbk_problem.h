@@ -34,6 +34,22 @@ struct Problem {
     ConvGeom conv;
 };
 
+// One attention layer call (paper Sec. 4.4): O = softmax(alpha Q K^T + bias) V
+// per batch entry; Q, O [Nq][D], K, V [Nk][D], bias float [Nq][Nk] or nullptr.
+struct AttnProblem {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const float* bias;
+    void* O;
+    int batch, Nq, Nk, D;
+    int64_t ldq, ldk, ldv, ldo;                          // row strides, elements
+    int64_t stride_q, stride_k, stride_v, stride_o;      // batch strides, elements
+    int64_t ld_bias, stride_bias;
+    int dtype;                                           // of Q, K, V and O
+    float alpha;
+};
+
 __host__ __device__ inline bool epi_has_bias(int epi) {
     return epi == EPI_BIAS || epi == EPI_BIAS_RELU || epi == EPI_BIAS_GELU_TANH;
 }
@@ -45,5 +61,10 @@ hipError_t launch_generic(const Problem& p, hipStream_t stream, const char** nam
 // Returns false if this problem cannot take the MFMA path (alignment, dtype).
 bool mfma_supported(const Problem& p);
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name);
+
+// Attention: generic kernel (any dtype/alignment, D <= 512) and the fused MFMA kernel.
+hipError_t launch_attention_generic(const AttnProblem& p, hipStream_t stream, const char** name);
+bool attention_mfma_supported(const AttnProblem& p);
+hipError_t launch_attention_mfma(const AttnProblem& p, hipStream_t stream, const char** name);
 
 }  // namespace pbk

@@ -160,3 +160,30 @@ def gather_output(out_t, w: wl.Workload, b, i, j) -> np.ndarray:
     m, n, _ = w.gemm_mnk
     flat = torch.from_numpy((b * m + i) * n + j).cuda()
     return to_host_f64(out_t[flat], w.out_dtype)
+
+
+# ------------------------------------------------------------------ attention
+
+def run_attention(w: wl.AttentionWorkload, dev: dict, out=None, stream=None):
+    """Enqueue the attention call on device tensors dev = {"q","k","v","bias"}
+    (dense [batch][N][D] layouts).  Returns (status, out tensor)."""
+    import paper_2603_06731_amd as pbk
+    if out is None:
+        out = device_empty(w.batch * w.Nq * w.D, w.dtype)
+    ld_bias = w.Nk if w.bias != "none" else 0
+    stride_bias = w.Nq * w.Nk if w.bias == "per_batch" else 0
+    st = pbk.pbk_attention(dev["q"], dev["k"], dev["v"], dev["bias"], out, w.batch, w.Nq, w.Nk, w.D,
+                           w.D, w.D, w.D, w.D, w.Nq * w.D, w.Nk * w.D, w.Nk * w.D, w.Nq * w.D,
+                           ld_bias, stride_bias, w.dtype, w.alpha, stream)
+    return st, out
+
+
+def oracle_attention_full(w: wl.AttentionWorkload, host: dict) -> np.ndarray:
+    import oracle
+    return oracle.attention(host["q"], host["k"], host["v"], host["bias"], dtype=w.dtype, alpha=w.alpha)
+
+
+def oracle_attention_rows(w: wl.AttentionWorkload, host: dict, sb, si) -> np.ndarray:
+    import oracle
+    return oracle.attention_rows(host["q"], host["k"], host["v"], host["bias"], sb, si,
+                                 dtype=w.dtype, alpha=w.alpha)

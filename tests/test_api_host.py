@@ -85,3 +85,25 @@ def test_conv_argument_errors(pbk):
     assert cv(None, P, P, None, 1, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 1, 1, *ok_tail) == 1
     assert cv(P, P, P, None, 1, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 1, 1, 1, 1, 1.0, 1) == 6  # bias missing
     assert cv(P, P, P, None, 0, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 1, 1, *ok_tail) == 0    # no images
+
+
+def test_attention_argument_errors(pbk):
+    F32, BF16 = 0, 1
+    P = 0x1000           # fake, aligned, never dereferenced: every call below fails validation
+    att = pbk.pbk_attention
+
+    def call(Q=P, K=P, V=P, bias=None, O=P, batch=2, Nq=8, Nk=8, D=16, ldq=16, ldk=16, ldv=16, ldo=16,
+             sq=128, sk=128, sv=128, so=128, ldb=0, sb=0, dtype=BF16):
+        return att(Q, K, V, bias, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo, sq, sk, sv, so, ldb, sb, dtype, 1.0)
+    assert call(dtype=3) == 5 and call(dtype=9) == 5          # FP8 / unknown element type
+    assert call(Nq=-1) == 2 and call(D=0) == 2 and call(batch=-3) == 2
+    assert call(Nk=0) == 2                                    # softmax over no keys
+    assert call(batch=0) == 0 and call(Nq=0) == 0             # nothing to do
+    assert call(Nq=0, Nk=0) == 0
+    assert call(Q=None) == 1 and call(K=None) == 1 and call(V=None) == 1 and call(O=None) == 1
+    assert call(ldq=15) == 3 and call(ldk=8) == 3 and call(ldv=15) == 3 and call(ldo=1) == 3
+    assert call(sq=-1) == 3 and call(so=100) == 3             # output entries would overlap
+    assert call(bias=P, ldb=7) == 3 and call(bias=P, ldb=8, sb=-1) == 3
+    assert call(Q=P + 1) == 4 and call(O=P + 1) == 4 and call(bias=P + 2, ldb=8) == 4
+    assert call(Q=P + 2, dtype=F32) == 4
+    assert call(D=600, ldq=600, ldk=600, ldv=600, ldo=600, sq=4800, sk=4800, sv=4800, so=4800, dtype=F32) == 7

@@ -1,0 +1,79 @@
+"""Synthetic attention-layer workloads: shapes of the paper's attention study
+(batch x heads, sequence length, head size) with seeded normal tensors.
+No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from . import gen
+
+
+@dataclass(frozen=True)
+class AttentionWorkload:
+    name: str
+    dtype: int                   # of Q, K, V and the output
+    batch: int                   # batch x heads, flattened
+    Nq: int
+    Nk: int
+    D: int
+    alpha: float = 1.0           # score scale (an fp32 value)
+    bias: str = "none"           # "none" | "shared" ([Nq][Nk]) | "per_batch" ([batch][Nq][Nk])
+    dist_q: tuple = ("normal", 1.0)
+    dist_k: tuple = ("normal", 1.0)
+    dist_v: tuple = ("normal", 1.0)
+    dist_bias: tuple = ("normal", 1.0)
+    seed: int = gen.MASTER_SEED
+    note: str = field(default="", compare=False)
+
+    @property
+    def flops(self) -> int:
+        """Both contractions: 2*Nq*Nk*D each."""
+        return 4 * self.batch * self.Nq * self.Nk * self.D
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """Q, K, V and the bias read once, O written once."""
+        esz = 4 if self.dtype == gen.DTYPE_F32 else 2
+        nb = {"none": 0, "shared": 1, "per_batch": self.batch}[self.bias]
+        return esz * self.batch * (2 * self.Nq * self.D + 2 * self.Nk * self.D) + 4 * nb * self.Nq * self.Nk
+
+
+def _scale(d: int) -> float:
+    return float(np.float32(1.0 / math.sqrt(d)))
+
+
+def _paper_shape(name, heads, n, d, dtype=gen.DTYPE_BF16):
+    return AttentionWorkload(name, dtype, heads, n, n, d, alpha=_scale(d))
+
+
+# (batch = 1) x heads, sequence length, head size: the rows of the paper's attention table
+ATTENTION_CONFIGS = {w.name: w for w in [
+    _paper_shape("attn_h16_n512_d64", 16, 512, 64),
+    _paper_shape("attn_h16_n2048_d64", 16, 2048, 64),
+    _paper_shape("attn_h16_n8192_d64", 16, 8192, 64),
+    _paper_shape("attn_h16_n512_d128", 16, 512, 128),
+    _paper_shape("attn_h16_n2048_d128", 16, 2048, 128),
+    _paper_shape("attn_h16_n8192_d128", 16, 8192, 128),
+    _paper_shape("attn_h16_n577_d64", 16, 577, 64),
+    _paper_shape("attn_h12_n10_d64", 12, 10, 64),
+    _paper_shape("attn_h6_n297_d64", 6, 297, 64),
+    _paper_shape("attn_h8_n500_d32", 8, 500, 32),
+    _paper_shape("attn_h32_n1024_d128", 32, 1024, 128),
+]}
+
+
+def make_attention_inputs(w: AttentionWorkload) -> dict:
+    """Keys "q", "k", "v" (storage dtype) and "bias" (float32 or None).
+    tensor ids: q=1, k=2, bias=3, v=4."""
+    q = gen.tensor((w.batch, w.Nq, w.D), w.dtype, 1, w.dist_q[0], w.dist_q[1], w.seed)
+    k = gen.tensor((w.batch, w.Nk, w.D), w.dtype, 2, w.dist_k[0], w.dist_k[1], w.seed)
+    v = gen.tensor((w.batch, w.Nk, w.D), w.dtype, 4, w.dist_v[0], w.dist_v[1], w.seed)
+    bias = None
+    if w.bias == "shared":
+        bias = gen.tensor((w.Nq, w.Nk), gen.DTYPE_F32, 3, w.dist_bias[0], w.dist_bias[1], w.seed)
+    elif w.bias == "per_batch":
+        bias = gen.tensor((w.batch, w.Nq, w.Nk), gen.DTYPE_F32, 3, w.dist_bias[0], w.dist_bias[1], w.seed)
+    return {"q": q, "k": k, "v": v, "bias": bias}
