@@ -4,9 +4,10 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all]
 
 A step is one call of the workload's entry point (pbk_matmul /
-pbk_batched_matmul / pbk_conv2d_nhwc) over seeded synthetic inputs that are
-already resident in HBM.  Prints ONE JSON line: whole-job TFLOP/s (2*M*N*K per
-step, epilogue flops not counted), the roofline position of the kernel from HIP
+pbk_batched_matmul / pbk_conv2d_nhwc / pbk_attention) over seeded synthetic
+inputs that are already resident in HBM.  Prints ONE JSON line: whole-job
+TFLOP/s (2*M*N*K per step, epilogue flops not counted; 4*Nq*Nk*D per batch
+entry for attention, softmax flops not counted), the roofline position of the kernel from HIP
 event timings of every launch, and the CPU oracle timed on a bounded sample of
 the same workload as a baseline.  --all adds a per-workload table on stderr and
 in gpurun_out/bench_all.json; the JSON line is always the headline workload.
@@ -30,9 +31,21 @@ DTYPE_NAMES = {0: "f32", 1: "bf16", 2: "f16", 3: "fp8_e4m3", 4: "fp8_e5m2"}
 PEAK_MFMA_FP8_TFLOPS = 5033.2       # twice the 16-bit rate
 
 
+def is_attention(w):
+    return hasattr(w, "Nq")
+
+
+def in_dtype_of(w):
+    return w.dtype if is_attention(w) else w.in_dtype
+
+
 def bound_of(w):
     """Which roofline bounds the workload: arithmetic intensity against the ridge."""
     import workloads as wl
+    if is_attention(w):
+        peak = PEAK_FP32_TFLOPS if w.dtype == wl.DTYPE_F32 else PEAK_MFMA_16BIT_TFLOPS
+        ridge = peak * 1e12 / (PEAK_HBM_GBS * 1e9)
+        return ("mfma", peak) if w.flops / w.algorithmic_bytes >= ridge else ("hbm", PEAK_HBM_GBS)
     peak = (PEAK_FP32_TFLOPS if w.in_dtype == wl.DTYPE_F32 else
             PEAK_MFMA_FP8_TFLOPS if w.in_dtype in (wl.DTYPE_FP8_E4M3, wl.DTYPE_FP8_E5M2) else PEAK_MFMA_16BIT_TFLOPS)
     ridge = peak * 1e12 / (PEAK_HBM_GBS * 1e9)
@@ -47,13 +60,19 @@ def time_workload(w, steps, warmup):
     import pbk_testlib as T
     import paper_2603_06731_amd as pbk
 
-    host = wl.make_inputs(w)
+    if is_attention(w):
+        host = wl.make_attention_inputs(w)
+        out = T.device_empty(w.batch * w.Nq * w.D, w.dtype)
+        run = T.run_attention
+    else:
+        host = wl.make_inputs(w)
+        m, n, _ = w.gemm_mnk
+        out = T.device_empty(w.batch * m * n, w.out_dtype)
+        run = T.run_workload
     dev = T.upload(host)
-    m, n, _ = w.gemm_mnk
-    out = T.device_empty(w.batch * m * n, w.out_dtype)
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
-        st, _o = T.run_workload(w, dev, out=out, stream=stream)
+        st, _o = run(w, dev, out=out, stream=stream)
         pbk.check(st, w.name)
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
@@ -61,7 +80,7 @@ def time_workload(w, steps, warmup):
     t0 = time.perf_counter()
     for i in range(steps):
         starts[i].record(stream)
-        st, _o = T.run_workload(w, dev, out=out, stream=stream)
+        st, _o = run(w, dev, out=out, stream=stream)
         ends[i].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -71,11 +90,36 @@ def time_workload(w, steps, warmup):
             "kernel": pbk.pbk_last_kernel(), "host": host, "out": out}
 
 
+def cpu_baseline_attention(w, host, budget_s=15.0):
+    """The attention oracle on a bounded number of query rows of the same workload."""
+    import numpy as np
+    import oracle
+    threads = oracle.num_threads()
+
+    def run(nrows):
+        r = np.random.default_rng(3)
+        sb = r.integers(0, w.batch, size=nrows)
+        si = r.integers(0, w.Nq, size=nrows)
+        t0 = time.perf_counter()
+        oracle.attention_rows(host["q"], host["k"], host["v"], host["bias"], sb, si, dtype=w.dtype, alpha=w.alpha)
+        return time.perf_counter() - t0
+    per_row = 4.0 * w.Nk * w.D
+    rows = 64
+    dt = run(rows)
+    rows2 = int(min(w.batch * w.Nq, max(rows, rows * budget_s / max(dt, 1e-6))))
+    if rows2 > 2 * rows:
+        rows, dt = rows2, run(rows2)
+    return {"value": rows * per_row / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{rows} query rows x {w.Nk} keys (D={w.D}), {dt:.1f} s", "seconds": dt}
+
+
 def cpu_baseline(w, host, budget_s=15.0):
     """The oracle, as it stands, on a bounded slice of the same workload."""
     import numpy as np
     import oracle
     import workloads as wl
+    if is_attention(w):
+        return cpu_baseline_attention(w, host, budget_s)
     threads = oracle.num_threads()
     m, n, k = w.gemm_mnk
 
@@ -140,9 +184,11 @@ def report(w, r, steps, warmup, with_cpu=True):
         "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": r["wall_ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": DTYPE_NAMES[w.in_dtype], "data": "synthetic",
-        "config": {"workload": w.name, "kind": w.kind, "gemm_mnk": list(w.gemm_mnk), "batch": w.batch,
-                   "epilogue": w.epi, "out_dtype": DTYPE_NAMES[w.out_dtype], "kernel": r["kernel"]},
+        "dtype": DTYPE_NAMES[in_dtype_of(w)], "data": "synthetic",
+        "config": ({"workload": w.name, "kind": "attention", "batch_x_heads": w.batch, "Nq": w.Nq, "Nk": w.Nk,
+                    "D": w.D, "bias": w.bias, "kernel": r["kernel"]} if is_attention(w) else
+                   {"workload": w.name, "kind": w.kind, "gemm_mnk": list(w.gemm_mnk), "batch": w.batch,
+                    "epilogue": w.epi, "out_dtype": DTYPE_NAMES[w.out_dtype], "kernel": r["kernel"]}),
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak, "traffic": load_traffic(w.name),
                      "kernel_ms_avg": avg_ms, "kernel_ms_min": min(r["event_ms"]),
@@ -189,7 +235,7 @@ def main():
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": args.steps}))
         return
 
-    w = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}[args.workload]
+    w = {**wl.CONFIGS, **wl.EXTRA_CONFIGS, **wl.ATTENTION_CONFIGS}[args.workload]
     r = time_workload(w, args.steps, args.warmup)
     line = report(w, r, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline)
     del r

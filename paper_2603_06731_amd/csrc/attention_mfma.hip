@@ -35,6 +35,7 @@ namespace {
 constexpr int ATT_BQ = 128;     // query rows per workgroup
 constexpr int ATT_BKV = 64;     // keys per tile
 constexpr int ATT_NW = 4;
+constexpr float ATT_SLACK = 8.0f; // log2 of how far a block's scores may exceed the softmax reference point
 
 // 64-byte-chunk swizzle of the d-contiguous V tile [keys][D]: rows that share
 // LDS banks (256-byte period) get different chunk positions.
@@ -49,7 +50,7 @@ template <int D> __device__ __forceinline__ int v_offset(int key, int dbyte) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <typename T, int D>
+template <typename T, int D, bool HAS_BIAS>
 __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProblem p, int q_tiles, int total) {
     constexpr int KS = D / 16;                    // k16 steps of Q K^T
     constexpr int JD = D / 32;                    // 32-wide blocks of the head dimension
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
     for (int j = 0; j < JD; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o_acc[j][e] = 0.0f;
-    float m_run = -INFINITY;      // running row maximum (log2 domain), same in lane and lane^32
+    float m_run = -INFINITY;      // softmax reference point of the row (log2 domain), same in lane and lane^32
     float l_run = 0.0f;           // this lane's share of the running row sum
 
     const float c1 = p.alpha * LOG2E;
@@ -151,105 +152,158 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         const char* sv = sk + TILE;
         const int key0 = kb * ATT_BKV;
 
-        // ---- S^T = K Q^T for two 32-key blocks
+        // ---- S^T = K Q^T for two 32-key blocks; K fragments are read KPF steps ahead of use
         f32x16 s_acc[2];
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
             for (int e = 0; e < 16; ++e) s_acc[k2][e] = 0.0f;
+        {
+            constexpr int KPF = KS < 3 ? KS : 3;
+            Frag<1> kfr[4][2];
+            auto read_k = [&](int ks) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+                for (int k2 = 0; k2 < 2; ++k2)
+                    kfr[ks & 3][k2].c[0] = *(const short8v*)(sk + kmajor_offset<D>(k2 * 32 + col, ks * 2 + h));
+            };
 #pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2) {
-                Frag<1> kf;
-                kf.c[0] = *(const short8v*)(sk + kmajor_offset<D>(k2 * 32 + col, ks * 2 + h));
-                s_acc[k2] = MfmaOp<T>::run(kf, qf[ks], s_acc[k2]);
+            for (int ks = 0; ks < KPF; ++ks) read_k(ks);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + KPF < KS) read_k(ks + KPF);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) s_acc[k2] = MfmaOp<T>::run(kfr[ks & 3][k2], qf[ks], s_acc[k2]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        // V fragments of the first steps: their LDS latency hides under the softmax arithmetic
+        constexpr int VPF = JD >= 4 ? 1 : 2;        // steps read ahead (a step is JD MFMAs)
+        constexpr int VRING = VPF + 1;
+        Frag<1> vfr[VRING][JD];
+        auto read_v = [&](int st) {
+#pragma unroll
+            for (int j = 0; j < JD; ++j) {
+                const int key = st * 16 + tr_key;
+                const int dbyte = j * 64 + tr_dbyte;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key, dbyte)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key + 8, dbyte)));
+                vfr[st % VRING][j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        };
+#pragma unroll
+        for (int st = 0; st < VPF; ++st) read_v(st);
+        __builtin_amdgcn_sched_barrier(0);
 
-        // ---- scores in the log2 domain, bias, removal of keys beyond Nk
-        // register 4g + t of block k2 is key key0 + 32 k2 + 8 g + 4 h + t
-        float sc[2][16];
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sc[k2][e] = s_acc[k2][e] * c1;
-        if (p.bias) {
+        // ---- online softmax.  Scores live in the log2 domain (alpha*log2(e) folded into one
+        // multiply-add); register 4g + t of block k2 is key key0 + 32 k2 + 8 g + 4 h + t.
+        // everything below works in place on the score registers
+        float bmax = -INFINITY;
+        const bool ragged = key0 + ATT_BKV > p.Nk;
+        const bool general = HAS_BIAS || ragged;       // wave-uniform
+        if (general) {
 #pragma unroll
             for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int key = key0 + k2 * 32 + g * 8 + h * 4;
-                    float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (q_ok) {
-                        if (bias_vec && key + 3 < p.Nk) {
-                            f32x4 v4 = *(const f32x4*)(bias_row + key);
-                            bv[0] = v4[0]; bv[1] = v4[1]; bv[2] = v4[2]; bv[3] = v4[3];
-                        } else {
+                for (int e = 0; e < 16; ++e) s_acc[k2][e] *= c1;
+            if (HAS_BIAS) {
 #pragma unroll
-                            for (int t = 0; t < 4; ++t)
-                                if (key + t < p.Nk) bv[t] = bias_row[key + t];
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int key = key0 + k2 * 32 + g * 8 + h * 4;
+                        float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (q_ok) {
+                            if (bias_vec && key + 3 < p.Nk) {
+                                f32x4 v4 = *(const f32x4*)(bias_row + key);
+                                bv[0] = v4[0]; bv[1] = v4[1]; bv[2] = v4[2]; bv[3] = v4[3];
+                            } else {
+#pragma unroll
+                                for (int t = 0; t < 4; ++t)
+                                    if (key + t < p.Nk) bv[t] = bias_row[key + t];
+                            }
                         }
-                    }
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) sc[k2][g * 4 + t] = fmaf(bv[t], LOG2E, sc[k2][g * 4 + t]);
-                }
+                        for (int t = 0; t < 4; ++t) s_acc[k2][g * 4 + t] = fmaf(bv[t], LOG2E, s_acc[k2][g * 4 + t]);
+                    }
+            }
+            if (ragged) {
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = key0 + k2 * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+                        if (key >= p.Nk) s_acc[k2][e] = -INFINITY;
+                    }
+            }
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) bmax = fmaxf(bmax, s_acc[k2][e]);
+        } else {
+            // c1 >= 0 on this path: the maximum commutes with the scaling
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) bmax = fmaxf(bmax, s_acc[k2][e]);
+            bmax *= c1;
         }
-        if (key0 + ATT_BKV > p.Nk) {
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+        // The reference point m_run only has to stay within 2^ATT_SLACK of the true running
+        // maximum for nothing to overflow: it is moved (and the accumulated sum and output
+        // corrected) only when a block exceeds it by more than that.  Weights and sum use the
+        // same reference, so the quotient is unchanged.
+        const bool move = bmax > m_run + ATT_SLACK;                 // same in lane and lane^32
+        if (__builtin_amdgcn_ballot_w64(move) != 0) {
+            const float m_new = move ? bmax : m_run;
+            const float m_sub = m_new == -INFINITY ? 0.0f : m_new;   // every key so far removed by a -inf bias
+            const float corr = fast_exp2(m_run - m_sub);             // 1 where the lane does not move
+            m_run = m_new;
+            l_run *= corr;
+#pragma unroll
+            for (int j = 0; j < JD; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o_acc[j][e] *= corr;
+        }
+        const float m_use = m_run == -INFINITY ? 0.0f : m_run;
+        float psum = 0.0f;
+        if (general) {
 #pragma unroll
             for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int key = key0 + k2 * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-                    if (key >= p.Nk) sc[k2][e] = -INFINITY;
+                    s_acc[k2][e] = fast_exp2(s_acc[k2][e] - m_use);
+                    psum += s_acc[k2][e];
+                }
+        } else {
+            const float neg_m = -m_use;
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    s_acc[k2][e] = fast_exp2(fmaf(s_acc[k2][e], c1, neg_m));
+                    psum += s_acc[k2][e];
                 }
         }
-
-        // ---- online softmax: new maximum, correction of what was accumulated, weights
-        float bmax = -INFINITY;
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) bmax = fmaxf(bmax, sc[k2][e]);
-        bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
-        const float m_new = fmaxf(m_run, bmax);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;    // every key so far removed by a -inf bias
-        const float corr = fast_exp2(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.0f;
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                sc[k2][e] = fast_exp2(sc[k2][e] - m_use);
-                psum += sc[k2][e];
-            }
-        l_run = l_run * corr + psum;
-#pragma unroll
-        for (int j = 0; j < JD; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o_acc[j][e] *= corr;
+        l_run += psum;
 
         // ---- O^T += V^T P^T, four 16-key steps; step s uses registers 8 (s%2) .. +8 of block s/2,
         // i.e. keys 16 s + 8 (e/4) + 4 h + e%4 for element e: V is read in the same order
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int st = 0; st < 4; ++st) {
+            if (st + VPF < 4) read_v(st + VPF);
             Frag<1> pf;
             int4v pw;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                pw[i] = (int)pack2<T>(sc[s >> 1][(s & 1) * 8 + 2 * i], sc[s >> 1][(s & 1) * 8 + 2 * i + 1]);
+                pw[i] = (int)pack2<T>(s_acc[st >> 1][(st & 1) * 8 + 2 * i], s_acc[st >> 1][(st & 1) * 8 + 2 * i + 1]);
             pf.c[0] = __builtin_bit_cast(short8v, pw);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < JD; ++j) {
-                const int key = s * 16 + tr_key;
-                const int dbyte = j * 64 + tr_dbyte;
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key, dbyte)));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key + 8, dbyte)));
-                Frag<1> vf;
-                vf.c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                o_acc[j] = MfmaOp<T>::run(vf, pf, o_acc[j]);
-            }
+            for (int j = 0; j < JD; ++j) o_acc[j] = MfmaOp<T>::run(vfr[st % VRING][j], pf, o_acc[j]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -273,14 +327,14 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
 template <typename T, int D>
 hipError_t launch_d(const AttnProblem& p, hipStream_t stream) {
     constexpr int LDS_BYTES = 2 * 2 * ATT_BKV * D * 2;
-    auto kern = attention_mfma_kernel<T, D>;
+    const void* kern = p.bias ? (const void*)attention_mfma_kernel<T, D, true> : (const void*)attention_mfma_kernel<T, D, false>;
     int q_tiles = (p.Nq + ATT_BQ - 1) / ATT_BQ;
     long long total = (long long)q_tiles * p.batch;
     if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     int tot = (int)total;
     AttnProblem pa = p;
     void* args[] = {&pa, &q_tiles, &tot};
-    return hipLaunchKernel((const void*)kern, dim3((unsigned)total), dim3(ATT_NW * 64), args, LDS_BYTES, stream);
+    return hipLaunchKernel(kern, dim3((unsigned)total), dim3(ATT_NW * 64), args, LDS_BYTES, stream);
 }
 
 template <typename T>
@@ -302,6 +356,7 @@ bool al(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a
 bool attention_mfma_supported(const AttnProblem& p) {
     if (p.dtype != DT_BF16 && p.dtype != DT_F16) return false;
     if (p.D != 32 && p.D != 64 && p.D != 128) return false;
+    if (!(p.alpha >= 0.0f)) return false;          // the kernel takes the row maximum before scaling
     if (!al(p.Q, 16) || !al(p.K, 16) || !al(p.V, 16) || !al(p.O, 8)) return false;
     if (p.ldq % 8 || p.ldk % 8 || p.ldv % 8 || p.ldo % 4) return false;
     if (p.stride_q % 8 || p.stride_k % 8 || p.stride_v % 8 || p.stride_o % 4) return false;
