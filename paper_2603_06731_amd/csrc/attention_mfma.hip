@@ -8,11 +8,14 @@
 // (nothing between the two matmuls goes back to on-chip memory), Sec. 4.4.
 //
 // Work split: a workgroup of 4 waves owns 128 query rows of one batch entry,
-// each wave 32 of them, and walks the keys in tiles of 64.  K and V tiles are
-// shared by the 4 waves: they are fetched straight into LDS
-// (buffer_load ... lds, double buffered, one barrier per tile), rows beyond Nk
-// arrive as zeros.  Two workgroups share a CU, so that one wave's softmax
-// arithmetic overlaps the other's MFMAs on every SIMD.
+// each wave 32 of them, and walks the keys in tiles of 64, two blocks of 32
+// each.  K and V tiles are shared by the 4 waves: they are fetched straight
+// into LDS (buffer_load ... lds, double buffered, one barrier per tile), rows
+// beyond Nk arrive as zeros.  The scores of block j+1 are computed while block
+// j's exponentials run, so the K tiles are shifted by half a tile against the V
+// tiles; the weights of block j multiply V while block j+1's row maximum is
+// found.  Two workgroups share a CU, so that one wave's softmax arithmetic
+// also overlaps the other's MFMAs on every SIMD.
 //
 // Register layouts (v_mfma_f32_32x32x16, D[i][j] += sum_k A[i][k] B[k][j]; a lane
 // supplies row i = lane%32 of A and column j = lane%32 of B, 8 consecutive k
@@ -50,12 +53,23 @@ template <int D> __device__ __forceinline__ int v_offset(int key, int dbyte) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <typename T, int D, bool HAS_BIAS>
+// dma16 for operands that are already scalar: the descriptor comes from make_rsrc (its
+// address words went through readfirstlane) and the LDS address from a scalar base plus a
+// constant, so nothing has to be made uniform again for every load.
+__device__ __forceinline__ void dma16_s(int4v rsrc, unsigned lds_addr, unsigned voff) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+}
+
+// HAS_BIAS: an additive bias is read.  PRE: scores are multiplied by alpha*log2(e) (and the
+// bias added) before the row maximum is taken; without it (no bias, alpha > 0) the maximum is
+// taken on the raw scores and the scaling rides in the multiply-add in front of the exponential.
+template <typename T, int D, bool HAS_BIAS, bool PRE>
 __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProblem p, int q_tiles, int total) {
     constexpr int KS = D / 16;                    // k16 steps of Q K^T
     constexpr int JD = D / 32;                    // 32-wide blocks of the head dimension
+    constexpr int NPV = 2 * JD;                   // MFMAs of O^T += V^T P^T per 32-key block
     constexpr int TILE = ATT_BKV * D * 2;         // bytes of one K or V tile
-    constexpr int STAGE = 2 * TILE;
     constexpr int BLKS = TILE / 1024;             // 1 KiB wave-loads per tile
     constexpr int CPW = BLKS / ATT_NW;            // per wave
     static_assert(BLKS % ATT_NW == 0 && CPW >= 1, "tile must split evenly over the waves");
@@ -63,7 +77,8 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
     constexpr int ROWS = 64 / CPR;                // rows per wave-load
     constexpr float LOG2E = 1.4426950408889634f;
 
-    extern __shared__ __attribute__((aligned(1024))) char lds[];   // 2 x (K tile | V tile)
+    // K slot 0 | K slot 1 | V slot 0 | V slot 1
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -93,25 +108,50 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         v_voff[r] = (unsigned)(row * (int)p.ldv * 2 + ((c64 << 6) | ((slot & 3) << 4)));
     }
     const unsigned lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr_of(lds));
-    auto issue_tile = [&](int kb, int stage) {
-        const int key0 = kb * ATT_BKV;
-        const int4v rk = make_rsrc(Kb + (int64_t)key0 * p.ldk * 2);
+    // V tile t: keys [64 t, 64 t + 64).
+    auto issue_v = [&](int t) {
+        const int key0 = t * ATT_BKV;
         const int4v rv = make_rsrc(Vb + (int64_t)key0 * p.ldv * 2);
-        const unsigned sk = lds_base + stage * STAGE, sv = sk + TILE;
+        const unsigned sv = lds_base + (2 + (t & 1)) * TILE;
+        if (key0 + ATT_BKV <= p.Nk) {             // whole tile inside: no per-lane test (wave-uniform)
 #pragma unroll
-        for (int r = 0; r < CPW; ++r) {
-            const bool ok = key0 + ld_row[r] < p.Nk;
-            dma16(rk, sk + (wave * CPW + r) * 1024, ok ? k_voff[r] : kOob);
+            for (int r = 0; r < CPW; ++r) dma16_s(rv, sv + (wave * CPW + r) * 1024, v_voff[r]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < CPW; ++r)
+                dma16_s(rv, sv + (wave * CPW + r) * 1024, key0 + ld_row[r] < p.Nk ? v_voff[r] : kOob);
         }
+    };
+    // K tile t is shifted by half a tile: keys [64 t + 32, 64 t + 96), because the scores of
+    // a 32-key block are computed one block ahead of its softmax.  t = -1 holds keys [0, 32)
+    // in its upper half.
+    auto issue_k = [&](int t) {
+        const int key0 = t * ATT_BKV + 32;
+        const unsigned sk = lds_base + (t & 1) * TILE;
+        if (t < 0) {
+            const int4v rk = make_rsrc(Kb);
 #pragma unroll
-        for (int r = 0; r < CPW; ++r) {
-            const bool ok = key0 + ld_row[r] < p.Nk;
-            dma16(rv, sv + (wave * CPW + r) * 1024, ok ? v_voff[r] : kOob);
+            for (int r = 0; r < CPW; ++r) {
+                const bool ok = ld_row[r] >= 32 && ld_row[r] - 32 < p.Nk;
+                dma16_s(rk, sk + (wave * CPW + r) * 1024, ok ? k_voff[r] - (unsigned)(32 * (int)p.ldk * 2) : kOob);
+            }
+        } else {
+            const int4v rk = make_rsrc(Kb + (int64_t)key0 * p.ldk * 2);
+            if (key0 + ATT_BKV <= p.Nk) {
+#pragma unroll
+                for (int r = 0; r < CPW; ++r) dma16_s(rk, sk + (wave * CPW + r) * 1024, k_voff[r]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < CPW; ++r)
+                    dma16_s(rk, sk + (wave * CPW + r) * 1024, key0 + ld_row[r] < p.Nk ? k_voff[r] : kOob);
+            }
         }
     };
 
-    const int NB = (p.Nk + ATT_BKV - 1) / ATT_BKV;
-    issue_tile(0, 0);
+    const int NT = (p.Nk + ATT_BKV - 1) / ATT_BKV;
+    issue_k(-1);
+    issue_v(0);
+    issue_k(0);
 
     // ---- Q fragments: column q = lane%32, d = 16 ks + 8 h .. +8, straight from global
     Frag<1> qf[KS];
@@ -135,125 +175,87 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
     float l_run = 0.0f;           // this lane's share of the running row sum
 
     const float c1 = p.alpha * LOG2E;
-    const bool bias_vec = p.bias && (((uintptr_t)p.bias & 15) == 0) && (p.ld_bias % 4 == 0) && (p.stride_bias % 4 == 0);
-    const float* bias_row = p.bias ? p.bias + (int64_t)b * p.stride_bias + (int64_t)(q0 + col) * p.ld_bias : nullptr;
+    const bool bias_vec = HAS_BIAS && (((uintptr_t)p.bias & 15) == 0) && (p.ld_bias % 4 == 0) && (p.stride_bias % 4 == 0);
+    const float* bias_row = HAS_BIAS ? p.bias + (int64_t)b * p.stride_bias + (int64_t)(q0 + col) * p.ld_bias : nullptr;
     const bool q_ok = q0 + col < p.Nq;
 
     // transposing-read lane constants: key (lane%16)/4 + 4h within a 16-key step, d = 4*(lane%4) of a 16-wide block
     const int tr_key = ((lane & 15) >> 2) + (h << 2);
     const int tr_dbyte = ((((lane >> 4) & 1) << 4) + ((lane & 3) << 2)) * 2;
 
-    for (int kb = 0; kb < NB; ++kb) {
-        const int stage = kb & 1;
-        wait_vmcnt<0>();              // this wave's pieces of tile kb have landed
-        __syncthreads();              // everyone's have; everyone is done reading the other stage
-        if (kb + 1 < NB) issue_tile(kb + 1, stage ^ 1);
-        const char* sk = lds + stage * STAGE;
-        const char* sv = sk + TILE;
-        const int key0 = kb * ATT_BKV;
+    // Per-lane LDS offsets of the fragment reads; slot, block and step only add constants
+    // (both swizzles are periodic in 8 rows), which go into the instructions' offset fields.
+    int koff[KS], voff[JD];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = kmajor_offset<D>(col, ks * 2 + h);
+#pragma unroll
+    for (int j = 0; j < JD; ++j) voff[j] = v_offset<D>(tr_key, j * 64 + tr_dbyte);
 
-        // ---- S^T = K Q^T for two 32-key blocks; K fragments are read KPF steps ahead of use
-        f32x16 s_acc[2];
+    // K fragments of one 32-key block are read KPF k16 steps ahead of the MFMA that uses them
+    constexpr int KPF = KS < 3 ? KS : 3;
+    Frag<1> kfr[4];
+    auto read_k = [&](int cbyte, int ks) {        // cbyte: slot and block offset, compile-time at every call
+        kfr[ks & 3].c[0] = *(const short8v*)(lds + koff[ks] + cbyte);
+    };
+    // V^T fragments of one 32-key block: 2 steps of 16 keys x JD blocks of 32 d
+    Frag<1> vfr[2][JD];
+    auto read_v = [&](int cbyte) {
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s_acc[k2][e] = 0.0f;
-        {
-            constexpr int KPF = KS < 3 ? KS : 3;
-            Frag<1> kfr[4][2];
-            auto read_k = [&](int ks) {
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
-                    kfr[ks & 3][k2].c[0] = *(const short8v*)(sk + kmajor_offset<D>(k2 * 32 + col, ks * 2 + h));
-            };
-#pragma unroll
-            for (int ks = 0; ks < KPF; ++ks) read_k(ks);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks + KPF < KS) read_k(ks + KPF);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) s_acc[k2] = MfmaOp<T>::run(kfr[ks & 3][k2], qf[ks], s_acc[k2]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        // V fragments of the first steps: their LDS latency hides under the softmax arithmetic
-        constexpr int VPF = JD >= 4 ? 1 : 2;        // steps read ahead (a step is JD MFMAs)
-        constexpr int VRING = VPF + 1;
-        Frag<1> vfr[VRING][JD];
-        auto read_v = [&](int st) {
+        for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int j = 0; j < JD; ++j) {
-                const int key = st * 16 + tr_key;
-                const int dbyte = j * 64 + tr_dbyte;
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key, dbyte)));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, sv + v_offset<D>(key + 8, dbyte)));
-                vfr[st % VRING][j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, lds + voff[j] + cbyte + (st * 16) * (D * 2)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, lds + voff[j] + cbyte + (st * 16 + 8) * (D * 2)));
+                vfr[st][j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
-        };
-#pragma unroll
-        for (int st = 0; st < VPF; ++st) read_v(st);
-        __builtin_amdgcn_sched_barrier(0);
+    };
 
-        // ---- online softmax.  Scores live in the log2 domain (alpha*log2(e) folded into one
-        // multiply-add); register 4g + t of block k2 is key key0 + 32 k2 + 8 g + 4 h + t.
-        // everything below works in place on the score registers
-        float bmax = -INFINITY;
-        const bool ragged = key0 + ATT_BKV > p.Nk;
-        const bool general = HAS_BIAS || ragged;       // wave-uniform
-        if (general) {
+    // Scores of a block, in place.  Register 4g + t is key kbase + 8 g + 4 h + t.  Elements [e0, e1).
+    // PRE: to the log2 domain (times alpha*log2 e), plus bias.  Keys beyond Nk are removed
+    // (RAGGED blocks only).
+    auto scale_scores = [&](f32x16& sv, int kbase, const float (&bias)[16], auto ragged_tag, int e0, int e1) {
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+        if (!PRE && !RAGGED) return;
 #pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) s_acc[k2][e] *= c1;
-            if (HAS_BIAS) {
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int key = key0 + k2 * 32 + g * 8 + h * 4;
-                        float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                        if (q_ok) {
-                            if (bias_vec && key + 3 < p.Nk) {
-                                f32x4 v4 = *(const f32x4*)(bias_row + key);
-                                bv[0] = v4[0]; bv[1] = v4[1]; bv[2] = v4[2]; bv[3] = v4[3];
-                            } else {
-#pragma unroll
-                                for (int t = 0; t < 4; ++t)
-                                    if (key + t < p.Nk) bv[t] = bias_row[key + t];
-                            }
-                        }
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) s_acc[k2][g * 4 + t] = fmaf(bv[t], LOG2E, s_acc[k2][g * 4 + t]);
-                    }
-            }
-            if (ragged) {
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int key = key0 + k2 * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-                        if (key >= p.Nk) s_acc[k2][e] = -INFINITY;
-                    }
-            }
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) bmax = fmaxf(bmax, s_acc[k2][e]);
-        } else {
-            // c1 >= 0 on this path: the maximum commutes with the scaling
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) bmax = fmaxf(bmax, s_acc[k2][e]);
-            bmax *= c1;
+        for (int e = 0; e < 16; ++e) {
+            if (e < e0 || e >= e1) continue;
+            float v = sv[e];
+            if (PRE) v *= c1;
+            if (HAS_BIAS) v = fmaf(bias[e], LOG2E, v);
+            if (RAGGED && kbase + (e >> 2) * 8 + h * 4 + (e & 3) >= p.Nk) v = -INFINITY;
+            sv[e] = v;
         }
-        bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
-        // The reference point m_run only has to stay within 2^ATT_SLACK of the true running
-        // maximum for nothing to overflow: it is moved (and the accumulated sum and output
-        // corrected) only when a block exceeds it by more than that.  Weights and sum use the
-        // same reference, so the quotient is unchanged.
+    };
+    auto load_bias = [&](int kbase, float (&bias)[16]) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int key = kbase + g * 8 + h * 4;
+            float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (q_ok) {
+                if (bias_vec && key + 3 < p.Nk) {
+                    f32x4 v4 = *(const f32x4*)(bias_row + key);
+                    bv[0] = v4[0]; bv[1] = v4[1]; bv[2] = v4[2]; bv[3] = v4[3];
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (key + t < p.Nk) bv[t] = bias_row[key + t];
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) bias[g * 4 + t] = bv[t];
+        }
+    };
+    auto block_max = [&](const f32x16& sv) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) m = fmaxf(m, sv[e]);
+        return PRE ? m : m * c1;          // c1 > 0 without PRE: the maximum commutes with the scaling
+    };
+    // The reference point m_run only has to stay within 2^ATT_SLACK of the true running
+    // maximum for nothing to overflow: it is moved (and the accumulated sum and output
+    // corrected) only when a block exceeds it by more than that.  Weights and sum use the
+    // same reference, so the quotient is unchanged.  bmax: block maximum of the row (both halves).
+    auto move_reference = [&](float bmax) {
         const bool move = bmax > m_run + ATT_SLACK;                 // same in lane and lane^32
         if (__builtin_amdgcn_ballot_w64(move) != 0) {
             const float m_new = move ? bmax : m_run;
@@ -266,46 +268,125 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o_acc[j][e] *= corr;
         }
-        const float m_use = m_run == -INFINITY ? 0.0f : m_run;
-        float psum = 0.0f;
-        if (general) {
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    s_acc[k2][e] = fast_exp2(s_acc[k2][e] - m_use);
-                    psum += s_acc[k2][e];
-                }
-        } else {
-            const float neg_m = -m_use;
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    s_acc[k2][e] = fast_exp2(fmaf(s_acc[k2][e], c1, neg_m));
-                    psum += s_acc[k2][e];
-                }
-        }
-        l_run += psum;
+    };
 
-        // ---- O^T += V^T P^T, four 16-key steps; step s uses registers 8 (s%2) .. +8 of block s/2,
-        // i.e. keys 16 s + 8 (e/4) + 4 h + e%4 for element e: V is read in the same order
+    // ---- prologue: scores of block 0 (keys 0..31, upper half of K slot 1), its reference point
+    f32x16 s_blk[2];              // scores / weights of the block being consumed and of the next one
+    wait_vmcnt<0>();
+    __syncthreads();
+    {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s_blk[0][e] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            read_k(TILE + 32 * D * 2, ks);
+            s_blk[0] = MfmaOp<T>::run(kfr[ks & 3], qf[ks], s_blk[0]);
+        }
+        float bias0[16];
+        if (HAS_BIAS) load_bias(0, bias0);
+        if (32 > p.Nk) scale_scores(s_blk[0], 0, bias0, TailYes{}, 0, 16);
+        else scale_scores(s_blk[0], 0, bias0, TailNo{}, 0, 16);
+        float bmax = block_max(s_blk[0]);
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+        move_reference(bmax);
+    }
+
+    // ---- main loop over 64-key tiles, two 32-key blocks each.  For block j (scores already in
+    // registers): phase 1 turns them into weights while the MFMAs of the NEXT block's scores
+    // run; phase 2 multiplies the weights into O while the next block's scores are prepared and
+    // its row maximum is found.  PAR: parity of the tile = LDS slot, compile-time so that
+    // every LDS address is a per-lane register plus an immediate.
+    auto tile = [&](int t, auto par_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        wait_vmcnt<0>();              // this wave's pieces of V(t), K(t) have landed
+        __syncthreads();              // everyone's have; everyone is done with V(t-1), K(t-1)
+        // the first fragment reads of the tile go out before the (scalar-heavy) issue of the
+        // next tile's loads, which hides their LDS latency
+#pragma unroll
+        for (int ks = 0; ks < KPF; ++ks) read_k(PAR * TILE, ks);
+        read_v((2 + PAR) * TILE);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < NT) { issue_v(t + 1); issue_k(t + 1); }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            if (st + VPF < 4) read_v(st + VPF);
-            Frag<1> pf;
-            int4v pw;
+        for (int hb = 0; hb < 2; ++hb) {
+            f32x16& s_cur = s_blk[hb];
+            f32x16& s_nxt = s_blk[hb ^ 1];
+            const int kcb = PAR * TILE + 32 * hb * (D * 2);           // K rows of the next block
+            const int vcb = (2 + PAR) * TILE + 32 * hb * (D * 2);     // V rows of this block
+            const int knext = t * ATT_BKV + 32 * hb + 32;             // first key of the next block
+            const float m_use = m_run == -INFINITY ? 0.0f : m_run;
+            const float neg_m = -m_use;
+
+            // ---- phase 1
+            if (hb != 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                pw[i] = (int)pack2<T>(s_acc[st >> 1][(st & 1) * 8 + 2 * i], s_acc[st >> 1][(st & 1) * 8 + 2 * i + 1]);
-            pf.c[0] = __builtin_bit_cast(short8v, pw);
+                for (int ks = 0; ks < KPF; ++ks) read_k(kcb, ks);
+                read_v(vcb);
+            }
             __builtin_amdgcn_sched_barrier(0);
+            int pw[8];                 // the block's 16 weights, rounded and packed in pairs
+            float psum = 0.0f;
 #pragma unroll
-            for (int j = 0; j < JD; ++j) o_acc[j] = MfmaOp<T>::run(vfr[st % VRING][j], pf, o_acc[j]);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + KPF < KS) read_k(kcb, ks + KPF);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ks == 0) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) s_nxt[e] = 0.0f;
+                }
+                s_nxt = MfmaOp<T>::run(kfr[ks & 3], qf[ks], s_nxt);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (i < ks * 8 / KS || i >= (ks + 1) * 8 / KS) continue;
+                    const float p0 = fast_exp2(PRE ? s_cur[2 * i] - m_use : fmaf(s_cur[2 * i], c1, neg_m));
+                    const float p1 = fast_exp2(PRE ? s_cur[2 * i + 1] - m_use : fmaf(s_cur[2 * i + 1], c1, neg_m));
+                    psum += p0 + p1;
+                    pw[i] = (int)pack2<T>(p0, p1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            l_run += psum;
+
+            // ---- phase 2
+            float biasn[16];
+            if (HAS_BIAS) load_bias(knext, biasn);
+            const bool ragged = knext + 32 > p.Nk;           // wave-uniform
+            float bmax = -INFINITY;
+            int mfma_idx = 0;
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                Frag<1> pf;
+                int4v pv = {pw[4 * st], pw[4 * st + 1], pw[4 * st + 2], pw[4 * st + 3]};
+                pf.c[0] = __builtin_bit_cast(short8v, pv);
+#pragma unroll
+                for (int j = 0; j < JD; ++j, ++mfma_idx) {
+                    o_acc[j] = MfmaOp<T>::run(vfr[st][j], pf, o_acc[j]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // the next block's scores: prepared in slices under the first half of the MFMAs,
+                    // maximum and the exchange with lane^32 under the second half
+                    constexpr int HALF = NPV / 2;
+                    if (mfma_idx < HALF) {
+                        if (ragged) scale_scores(s_nxt, knext, biasn, TailYes{}, mfma_idx * 16 / HALF, (mfma_idx + 1) * 16 / HALF);
+                        else scale_scores(s_nxt, knext, biasn, TailNo{}, mfma_idx * 16 / HALF, (mfma_idx + 1) * 16 / HALF);
+                    }
+                    if (mfma_idx == HALF - 1) {
+                        bmax = block_max(s_nxt);
+                        bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            move_reference(bmax);
         }
+    };
+    int t = 0;
+    for (; t + 1 < NT; t += 2) {
+        tile(t, IntTag<0>{});
+        tile(t + 1, IntTag<1>{});
     }
+    if (t < NT) tile(t, IntTag<0>{});
 
     // ---- normalise and store: the lane holds, for query q0 + lane%32, d = 32 j + 8 g + 4 h + 0..3
     const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -327,7 +408,9 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
 template <typename T, int D>
 hipError_t launch_d(const AttnProblem& p, hipStream_t stream) {
     constexpr int LDS_BYTES = 2 * 2 * ATT_BKV * D * 2;
-    const void* kern = p.bias ? (const void*)attention_mfma_kernel<T, D, true> : (const void*)attention_mfma_kernel<T, D, false>;
+    const void* kern = p.bias ? (const void*)attention_mfma_kernel<T, D, true, true>
+                       : p.alpha > 0.0f ? (const void*)attention_mfma_kernel<T, D, false, false>
+                                        : (const void*)attention_mfma_kernel<T, D, false, true>;
     int q_tiles = (p.Nq + ATT_BQ - 1) / ATT_BQ;
     long long total = (long long)q_tiles * p.batch;
     if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
@@ -356,7 +439,6 @@ bool al(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a
 bool attention_mfma_supported(const AttnProblem& p) {
     if (p.dtype != DT_BF16 && p.dtype != DT_F16) return false;
     if (p.D != 32 && p.D != 64 && p.D != 128) return false;
-    if (!(p.alpha >= 0.0f)) return false;          // the kernel takes the row maximum before scaling
     if (!al(p.Q, 16) || !al(p.K, 16) || !al(p.V, 16) || !al(p.O, 8)) return false;
     if (p.ldq % 8 || p.ldk % 8 || p.ldv % 8 || p.ldo % 4) return false;
     if (p.stride_q % 8 || p.stride_k % 8 || p.stride_v % 8 || p.stride_o % 4) return false;

@@ -83,6 +83,13 @@ def test_attention_generic(dtype, shape, bias):
     check_attention(w, force="generic", expect_kernel="attn_generic")
 
 
+@pytest.mark.parametrize("alpha", [0.0, -0.3])
+def test_attention_mfma_nonpositive_scale(alpha):
+    """alpha <= 0 takes the kernel variant that scales the scores before the row maximum."""
+    w = wl.AttentionWorkload("att_alpha", BF16, 2, 150, 200, 64, alpha=alpha)
+    check_attention(w, expect_kernel="attn_mfma")
+
+
 def test_attention_odd_head_size_falls_back():
     w = wl.AttentionWorkload("att_d40", BF16, 2, 100, 90, 40, alpha=scale(40))
     check_attention(w, expect_kernel="attn_generic")
