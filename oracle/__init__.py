@@ -50,6 +50,12 @@ def lib() -> ctypes.CDLL:
                                                + [i32, i32, f32, i32, i64, vp, vp, vp])
         L.oracle_conv2d_nhwc_at.argtypes = ([vp, vp, vp, vp, vp] + [i64] * 13
                                             + [i32, f32, i32, i64, vp, vp, vp, vp])
+        L.oracle_conv2d_nhwc_pad4.argtypes = [vp, vp, vp, vp, vp] + [i64] * 15 + [i32, f32, i32]
+        L.oracle_conv2d_transpose_nhwc.argtypes = [vp, vp, vp, vp, vp] + [i64] * 15 + [i32, f32, i32]
+        L.oracle_conv2d_transpose_nhwc_at.argtypes = ([vp, vp, vp, vp, vp] + [i64] * 15
+                                                      + [i32, f32, i32, i64, vp, vp, vp, vp])
+        L.oracle_conv_transpose_out_dim.argtypes = [i64] * 6
+        L.oracle_conv_transpose_out_dim.restype = i64
         L.oracle_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32]
         L.oracle_attention_rows.argtypes = [vp, vp, vp, vp, vp] + [i64] * 12 + [i32, f32, i64, vp, vp]
         L.oracle_conv_out_dim.argtypes = [i64] * 5
@@ -209,6 +215,78 @@ def conv2d_nhwc_at(x, w, bias, sn, soh, sow, sco, *, dtype, stride=(1, 1), pad=(
                                      pad[0], pad[1], dil[0], dil[1], dtype, float(alpha), epi,
                                      len(out), *[_ptr(v) for v in idx])
     _rc(rc, "conv2d_nhwc_at")
+    return out, pre
+
+
+def conv2d_nhwc_pad4(x, w, bias=None, *, dtype, stride=(1, 1), pad=(0, 0, 0, 0), dil=(1, 1),
+                     alpha=1.0, epi=EPI_NONE, want_preact=False):
+    """Convolution with pad = (top, bottom, left, right); float64 [N][OH][OW][Cout]."""
+    x = _check_in(np.ascontiguousarray(x), dtype)
+    w = _check_in(np.ascontiguousarray(w), dtype)
+    bias = _check_bias(bias)
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    OH = (H + pad[0] + pad[1] - dil[0] * (KH - 1) - 1) // stride[0] + 1
+    OW = (W + pad[2] + pad[3] - dil[1] * (KW - 1) - 1) // stride[1] + 1
+    if OH < 1 or OW < 1:
+        raise ValueError("empty output")
+    out = np.empty((N, OH, OW, Cout), dtype=np.float64)
+    pre = np.empty_like(out) if want_preact else None
+    rc = lib().oracle_conv2d_nhwc_pad4(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), _ptr(pre),
+                                       N, H, W, Cin, Cout, KH, KW, stride[0], stride[1],
+                                       pad[0], pad[1], pad[2], pad[3], dil[0], dil[1],
+                                       dtype, float(alpha), epi)
+    _rc(rc, "conv2d_nhwc_pad4")
+    return (out, pre) if want_preact else out
+
+
+def conv_transpose_out_dim(size, k, stride, pad, out_pad, dil) -> int:
+    return int(lib().oracle_conv_transpose_out_dim(size, k, stride, pad, out_pad, dil))
+
+
+def conv2d_transpose_nhwc(x, w, bias=None, *, dtype, stride=(1, 1), pad=(0, 0), out_pad=(0, 0),
+                          dil=(1, 1), alpha=1.0, epi=EPI_NONE, want_preact=False):
+    """Transposed convolution; x [N][H][W][Cin], w [KH][KW][Cin][Cout]; float64 [N][OH][OW][Cout]."""
+    x = _check_in(np.ascontiguousarray(x), dtype)
+    w = _check_in(np.ascontiguousarray(w), dtype)
+    bias = _check_bias(bias)
+    N, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    OH = conv_transpose_out_dim(H, KH, stride[0], pad[0], out_pad[0], dil[0])
+    OW = conv_transpose_out_dim(W, KW, stride[1], pad[1], out_pad[1], dil[1])
+    if OH < 1 or OW < 1:
+        raise ValueError("empty or invalid output")
+    out = np.empty((N, OH, OW, Cout), dtype=np.float64)
+    pre = np.empty_like(out) if want_preact else None
+    rc = lib().oracle_conv2d_transpose_nhwc(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), _ptr(pre),
+                                            N, H, W, Cin, Cout, KH, KW, stride[0], stride[1],
+                                            pad[0], pad[1], out_pad[0], out_pad[1], dil[0], dil[1],
+                                            dtype, float(alpha), epi)
+    _rc(rc, "conv2d_transpose_nhwc")
+    return (out, pre) if want_preact else out
+
+
+def conv2d_transpose_nhwc_at(x, w, bias, sn, soh, sow, sco, *, dtype, stride=(1, 1), pad=(0, 0),
+                             out_pad=(0, 0), dil=(1, 1), alpha=1.0, epi=EPI_NONE):
+    """(out, preact) of the transposed convolution at listed output coordinates."""
+    x = _check_in(np.ascontiguousarray(x), dtype)
+    w = _check_in(np.ascontiguousarray(w), dtype)
+    bias = _check_bias(bias)
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    idx = [np.ascontiguousarray(a, dtype=np.int64) for a in (sn, soh, sow, sco)]
+    out = np.empty(idx[0].size, dtype=np.float64)
+    pre = np.empty_like(out)
+    rc = lib().oracle_conv2d_transpose_nhwc_at(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), _ptr(pre),
+                                               N, H, W, Cin, Cout, KH, KW, stride[0], stride[1],
+                                               pad[0], pad[1], out_pad[0], out_pad[1], dil[0], dil[1],
+                                               dtype, float(alpha), epi, idx[0].size,
+                                               *[_ptr(a) for a in idx])
+    _rc(rc, "conv2d_transpose_nhwc_at")
     return out, pre
 
 

@@ -363,6 +363,159 @@ int oracle_conv2d_nhwc_at(const void* x, const void* w, const float* bias,
     return 0;
 }
 
+/* ---- convolution with four-sided padding -------------------------------- */
+
+static int64_t conv_out_dim2(int64_t in, int64_t k, int64_t stride, int64_t pad_lo, int64_t pad_hi, int64_t dil)
+{
+    if (in < 1 || k < 1 || stride < 1 || pad_lo < 0 || pad_hi < 0 || dil < 1) return -1;
+    int64_t span = in + pad_lo + pad_hi - dil * (k - 1) - 1;
+    if (span < 0) return -1;
+    return span / stride + 1;
+}
+
+int oracle_conv2d_nhwc_pad4(const void* x, const void* w, const float* bias,
+                            double* out, double* preact,
+                            int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                            int64_t pad_top, int64_t pad_bottom, int64_t pad_left, int64_t pad_right,
+                            int64_t dil_h, int64_t dil_w,
+                            int dtype, float alpha, int epi)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (N < 0 || Cin < 1 || Cout < 1) return -4;
+    int64_t OH = conv_out_dim2(H, KH, stride_h, pad_top, pad_bottom, dil_h);
+    int64_t OW = conv_out_dim2(W, KW, stride_w, pad_left, pad_right, dil_w);
+    if (OH < 0 || OW < 0) return -5;
+    if (!x || !w || !out) return -6;
+    /* the far-side padding only decides how many outputs exist; the near side shifts the taps */
+    for (int64_t n = 0; n < N; ++n) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t oh = 0; oh < OH; ++oh) {
+            for (int64_t ow = 0; ow < OW; ++ow) {
+                for (int64_t co = 0; co < Cout; ++co) {
+                    double s = conv_point(x, w, dtype, H, W, Cin, Cout, KH, KW,
+                                          stride_h, stride_w, pad_top, pad_left, dil_h, dil_w,
+                                          n, oh, ow, co);
+                    double t = preactivation(s, epi_has_bias(epi) ? (double)bias[co] : 0.0,
+                                             alpha, epi);
+                    int64_t o = ((n * OH + oh) * OW + ow) * Cout + co;
+                    if (preact) preact[o] = t;
+                    out[o] = activation(t, epi);
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---- transposed convolution ---------------------------------------------- */
+
+int64_t oracle_conv_transpose_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad,
+                                      int64_t out_pad, int64_t dil)
+{
+    if (in < 1 || k < 1 || stride < 1 || pad < 0 || dil < 1 || out_pad < 0) return -1;
+    if (out_pad >= stride && out_pad >= dil) return -1;
+    int64_t o = (in - 1) * stride - 2 * pad + dil * (k - 1) + out_pad + 1;
+    return o >= 1 ? o : -1;
+}
+
+/* The definition: every input pixel scatters its value times the filter into
+ * the output, s[n][ih*stride - pad + kh*dil][iw*stride - pad + kw*dil][co] +=
+ * x[n][ih][iw][c] * w[kh][kw][c][co]; contributions that land outside the
+ * output are dropped.  This is the transpose (adjoint) of the convolution
+ * with the same filter, stride, padding and dilation. */
+int oracle_conv2d_transpose_nhwc(const void* x, const void* w, const float* bias,
+                                 double* out, double* preact,
+                                 int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                 int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                 int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
+                                 int64_t dil_h, int64_t dil_w,
+                                 int dtype, float alpha, int epi)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (N < 0 || Cin < 1 || Cout < 1) return -4;
+    int64_t OH = oracle_conv_transpose_out_dim(H, KH, stride_h, pad_h, out_pad_h, dil_h);
+    int64_t OW = oracle_conv_transpose_out_dim(W, KW, stride_w, pad_w, out_pad_w, dil_w);
+    if (OH < 0 || OW < 0) return -5;
+    if (!x || !w || !out) return -6;
+    int64_t per_image = OH * OW * Cout;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t n = 0; n < N; ++n) {
+        double* acc = out + n * per_image;
+        for (int64_t o = 0; o < per_image; ++o) acc[o] = 0.0;
+        for (int64_t ih = 0; ih < H; ++ih)
+            for (int64_t iw = 0; iw < W; ++iw)
+                for (int64_t kh = 0; kh < KH; ++kh) {
+                    int64_t oh = ih * stride_h - pad_h + kh * dil_h;
+                    if (oh < 0 || oh >= OH) continue;
+                    for (int64_t kw = 0; kw < KW; ++kw) {
+                        int64_t ow = iw * stride_w - pad_w + kw * dil_w;
+                        if (ow < 0 || ow >= OW) continue;
+                        for (int64_t c = 0; c < Cin; ++c) {
+                            double xv = load(x, dtype, ((n * H + ih) * W + iw) * Cin + c);
+                            for (int64_t co = 0; co < Cout; ++co)
+                                acc[(oh * OW + ow) * Cout + co] +=
+                                    xv * load(w, dtype, ((kh * KW + kw) * Cin + c) * Cout + co);
+                        }
+                    }
+                }
+        for (int64_t o = 0; o < per_image; ++o) {
+            double t = preactivation(acc[o], epi_has_bias(epi) ? (double)bias[o % Cout] : 0.0,
+                                     alpha, epi);
+            if (preact) preact[n * per_image + o] = t;
+            acc[o] = activation(t, epi);
+        }
+    }
+    return 0;
+}
+
+/* The same sums collected per output element (for sampled checks at sizes the
+ * scatter loops would take too long for): output row oh receives tap kh from
+ * input row ih exactly when ih*stride - pad + kh*dil == oh. */
+int oracle_conv2d_transpose_nhwc_at(const void* x, const void* w, const float* bias,
+                                    double* out, double* preact,
+                                    int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                    int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                    int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
+                                    int64_t dil_h, int64_t dil_w,
+                                    int dtype, float alpha, int epi,
+                                    int64_t nsamp, const int64_t* sn, const int64_t* soh,
+                                    const int64_t* sow, const int64_t* sco)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (N < 1 || Cin < 1 || Cout < 1 || nsamp < 0) return -4;
+    int64_t OH = oracle_conv_transpose_out_dim(H, KH, stride_h, pad_h, out_pad_h, dil_h);
+    int64_t OW = oracle_conv_transpose_out_dim(W, KW, stride_w, pad_w, out_pad_w, dil_w);
+    if (OH < 0 || OW < 0) return -5;
+    if (!x || !w || !out || !sn || !soh || !sow || !sco) return -6;
+    for (int64_t s = 0; s < nsamp; ++s)
+        if (sn[s] < 0 || sn[s] >= N || soh[s] < 0 || soh[s] >= OH ||
+            sow[s] < 0 || sow[s] >= OW || sco[s] < 0 || sco[s] >= Cout)
+            return -7;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t s = 0; s < nsamp; ++s) {
+        double acc = 0.0;
+        for (int64_t ih = 0; ih < H; ++ih)
+            for (int64_t kh = 0; kh < KH; ++kh) {
+                if (ih * stride_h - pad_h + kh * dil_h != soh[s]) continue;
+                for (int64_t iw = 0; iw < W; ++iw)
+                    for (int64_t kw = 0; kw < KW; ++kw) {
+                        if (iw * stride_w - pad_w + kw * dil_w != sow[s]) continue;
+                        for (int64_t c = 0; c < Cin; ++c)
+                            acc += load(x, dtype, ((sn[s] * H + ih) * W + iw) * Cin + c) *
+                                   load(w, dtype, ((kh * KW + kw) * Cin + c) * Cout + sco[s]);
+                    }
+            }
+        double t = preactivation(acc, epi_has_bias(epi) ? (double)bias[sco[s]] : 0.0, alpha, epi);
+        if (preact) preact[s] = t;
+        out[s] = activation(t, epi);
+    }
+    return 0;
+}
+
 /* ---- attention ---------------------------------------------------------- */
 
 /* One output row (b, i) of  softmax(alpha * Q K^T + bias) V,  by the definition:

@@ -92,6 +92,44 @@ int oracle_conv2d_nhwc_at(const void* x, const void* w, const float* bias,
                           int64_t nsamp, const int64_t* sn, const int64_t* soh,
                           const int64_t* sow, const int64_t* sco);
 
+/* Convolution with separate padding on the four sides (the "same"-style
+ * padding kinds of the frameworks; paper Sec. 4.5 lists padding kinds among the
+ * supported configurations).  Output rows: (H + pad_top + pad_bottom -
+ * dil_h*(KH-1) - 1)/stride_h + 1, columns likewise; row oh reads input rows
+ * oh*stride_h - pad_top + kh*dil_h. */
+int oracle_conv2d_nhwc_pad4(const void* x, const void* w, const float* bias,
+                            double* out, double* preact,
+                            int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                            int64_t pad_top, int64_t pad_bottom, int64_t pad_left, int64_t pad_right,
+                            int64_t dil_h, int64_t dil_w,
+                            int dtype, float alpha, int epi);
+
+/* Transposed convolution (paper Sec. 4.5: transpose convolutions are covered
+ * by the same lowering).  x [N][H][W][Cin], w [KH][KW][Cin][Cout],
+ * out [N][OH][OW][Cout] with OH = (H-1)*stride_h - 2*pad_h + dil_h*(KH-1) +
+ * out_pad_h + 1: each input pixel scatters x*w to output rows
+ * ih*stride_h - pad_h + kh*dil_h (the adjoint of the convolution with the same
+ * filter and geometry).  out_pad must be smaller than the stride or the dilation. */
+int oracle_conv2d_transpose_nhwc(const void* x, const void* w, const float* bias,
+                                 double* out, double* preact,
+                                 int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                 int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                 int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
+                                 int64_t dil_h, int64_t dil_w,
+                                 int dtype, float alpha, int epi);
+int oracle_conv2d_transpose_nhwc_at(const void* x, const void* w, const float* bias,
+                                    double* out, double* preact,
+                                    int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                    int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                    int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
+                                    int64_t dil_h, int64_t dil_w,
+                                    int dtype, float alpha, int epi,
+                                    int64_t nsamp, const int64_t* sn, const int64_t* soh,
+                                    const int64_t* sow, const int64_t* sco);
+int64_t oracle_conv_transpose_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad,
+                                      int64_t out_pad, int64_t dil);
+
 /* Attention layer (paper Sec. 4.4; the operator of its attention example):
  *   out[b][i][d] = sum_j P[b][i][j] * V[b][j][d],
  *   P[b][i][:]   = softmax_j( alpha * sum_c Q[b][i][c]*K[b][j][c] + bias[b][i][j] ).
