@@ -117,6 +117,40 @@ pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* b
                            float alpha, pbk_epilogue epi, void* stream);
 
 /*
+ * The same convolution with separate padding on the four sides (the "same"-style
+ * padding kinds; paper Sec. 4.5 lists padding kinds among the covered
+ * configurations).  Row oh reads input rows oh*stride_h - pad_top + kh*dil_h;
+ * OH = (H + pad_top + pad_bottom - dil_h*(KH-1) - 1) / stride_h + 1, OW likewise
+ * with pad_left / pad_right.  pbk_conv2d_nhwc is this call with equal paddings.
+ */
+pbk_status pbk_conv2d_nhwc_pad4(const void* x, const void* w, void* y, const float* bias,
+                                int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                int64_t pad_top, int64_t pad_bottom, int64_t pad_left, int64_t pad_right,
+                                int64_t dil_h, int64_t dil_w,
+                                pbk_dtype in_dtype, pbk_dtype out_dtype,
+                                float alpha, pbk_epilogue epi, void* stream);
+
+/*
+ * Transposed convolution (paper Sec. 4.5: covered by the same lowering).
+ * x: [N][H][W][Cin], w: [KH][KW][Cin][Cout], y: [N][OH][OW][Cout] with
+ *   OH = (H-1)*stride_h - 2*pad_h + dil_h*(KH-1) + out_pad_h + 1   (OW likewise),
+ *   y[n][oh][ow][co] = sum over (ih, kh) with ih*stride_h - pad_h + kh*dil_h == oh,
+ *                      (iw, kw) likewise, and c, of x[n][ih][iw][c] * w[kh][kw][c][co]:
+ * the adjoint of the convolution with the same filter and geometry.  out_pad must
+ * be smaller than the stride or the dilation, OH and OW must be >= 1.  It runs as
+ * the implicit GEMM with rows (n, oh, ow) and K = KH*KW*Cin in which the taps
+ * that do not divide by the stride are zero; the epilogue is the usual one.
+ */
+pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, const float* bias,
+                                     int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                     int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                     int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
+                                     int64_t dil_h, int64_t dil_w,
+                                     pbk_dtype in_dtype, pbk_dtype out_dtype,
+                                     float alpha, pbk_epilogue epi, void* stream);
+
+/*
  * Attention layer, every operator fused into one kernel          (paper Sec. 4.4)
  *   O[b][i][:] = sum_j P[b][i][j] * V[b][j][:],
  *   P[b][i][:] = softmax over j of ( alpha * sum_c Q[b][i][c] * K[b][j][c] + bias[b][i][j] ).

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     PBK_OK, PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2,
     PBK_EPI_NONE, PBK_EPI_BIAS, PBK_EPI_RELU, PBK_EPI_BIAS_RELU,
     PBK_EPI_BIAS_GELU_TANH, PBK_EPI_GELU_TANH,
-    PbkError, lib, lib_path, pbk_matmul, pbk_batched_matmul, pbk_conv2d_nhwc, pbk_attention,
+    PbkError, lib, lib_path, pbk_matmul, pbk_batched_matmul, pbk_conv2d_nhwc, pbk_conv2d_nhwc_pad4,
+    pbk_conv2d_transpose_nhwc, pbk_attention,
     pbk_status_string, pbk_version, pbk_last_kernel, check, EXPORTED_SYMBOLS,
 )

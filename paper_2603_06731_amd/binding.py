@@ -14,7 +14,8 @@ PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2 = 0, 1, 2, 3, 4
 (PBK_EPI_NONE, PBK_EPI_BIAS, PBK_EPI_RELU, PBK_EPI_BIAS_RELU,
  PBK_EPI_BIAS_GELU_TANH, PBK_EPI_GELU_TANH) = range(6)
 
-EXPORTED_SYMBOLS = ("pbk_matmul", "pbk_batched_matmul", "pbk_conv2d_nhwc", "pbk_attention",
+EXPORTED_SYMBOLS = ("pbk_matmul", "pbk_batched_matmul", "pbk_conv2d_nhwc", "pbk_conv2d_nhwc_pad4",
+                    "pbk_conv2d_transpose_nhwc", "pbk_attention",
                     "pbk_status_string", "pbk_version", "pbk_last_kernel")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -55,6 +56,10 @@ def lib() -> ctypes.CDLL:
         L.pbk_batched_matmul.restype = i32
         L.pbk_conv2d_nhwc.argtypes = [vp, vp, vp, vp] + [i64] * 13 + [i32, i32, f32, i32, vp]
         L.pbk_conv2d_nhwc.restype = i32
+        L.pbk_conv2d_nhwc_pad4.argtypes = [vp, vp, vp, vp] + [i64] * 15 + [i32, i32, f32, i32, vp]
+        L.pbk_conv2d_nhwc_pad4.restype = i32
+        L.pbk_conv2d_transpose_nhwc.argtypes = [vp, vp, vp, vp] + [i64] * 15 + [i32, i32, f32, i32, vp]
+        L.pbk_conv2d_transpose_nhwc.restype = i32
         L.pbk_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32, vp]
         L.pbk_attention.restype = i32
         L.pbk_status_string.argtypes = [i32]
@@ -102,6 +107,22 @@ def pbk_conv2d_nhwc(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_
     return lib().pbk_conv2d_nhwc(_ptr(x), _ptr(w), _ptr(y), _ptr(bias), N, H, W, Cin, Cout,
                                  KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
                                  in_dtype, out_dtype, float(alpha), epi, _stream(stream))
+
+
+def pbk_conv2d_nhwc_pad4(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
+                         pad_top, pad_bottom, pad_left, pad_right, dil_h, dil_w,
+                         in_dtype, out_dtype, alpha, epi, stream=None) -> int:
+    return lib().pbk_conv2d_nhwc_pad4(_ptr(x), _ptr(w), _ptr(y), _ptr(bias), N, H, W, Cin, Cout,
+                                      KH, KW, stride_h, stride_w, pad_top, pad_bottom, pad_left, pad_right,
+                                      dil_h, dil_w, in_dtype, out_dtype, float(alpha), epi, _stream(stream))
+
+
+def pbk_conv2d_transpose_nhwc(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
+                              pad_h, pad_w, out_pad_h, out_pad_w, dil_h, dil_w,
+                              in_dtype, out_dtype, alpha, epi, stream=None) -> int:
+    return lib().pbk_conv2d_transpose_nhwc(_ptr(x), _ptr(w), _ptr(y), _ptr(bias), N, H, W, Cin, Cout,
+                                           KH, KW, stride_h, stride_w, pad_h, pad_w, out_pad_h, out_pad_w,
+                                           dil_h, dil_w, in_dtype, out_dtype, float(alpha), epi, _stream(stream))
 
 
 def pbk_attention(Q, K, V, bias, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo,

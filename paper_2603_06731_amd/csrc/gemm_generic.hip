@@ -31,8 +31,16 @@ __device__ __forceinline__ float conv_a(const T* x, const ConvGeom& g, int i, in
     int c = k - tap * g.Cin;
     int kh = tap / g.KW;
     int kw = tap - kh * g.KW;
-    int ih = oh * g.stride_h - g.pad_h + kh * g.dil_h;
-    int iw = ow * g.stride_w - g.pad_w + kw * g.dil_w;
+    int ih, iw;
+    if (g.transposed) {
+        int th = oh + g.pad_h - kh * g.dil_h, tw = ow + g.pad_w - kw * g.dil_w;
+        if (th < 0 || tw < 0) return 0.0f;
+        ih = th / g.stride_h; iw = tw / g.stride_w;
+        if (ih * g.stride_h != th || iw * g.stride_w != tw) return 0.0f;
+    } else {
+        ih = oh * g.stride_h - g.pad_h + kh * g.dil_h;
+        iw = ow * g.stride_w - g.pad_w + kw * g.dil_w;
+    }
     if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0.0f;
     return widen<T>(x[(((int64_t)n * g.H + ih) * g.W + iw) * g.Cin + c]);
 }

@@ -46,6 +46,7 @@ static int choose_config(const Problem& p) {
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name) {
     const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2;
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
+    if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1) cfg = choose_config(p);   // only 0 and 1 are built
     if (fp8) {
         // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
         // only the 64-deep configurations are built for it

@@ -48,7 +48,7 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
 #define PBK_LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-enum : int { MODE_DENSE = 0, MODE_TRANS_B = 1, MODE_CONV = 2 };
+enum : int { MODE_DENSE = 0, MODE_TRANS_B = 1, MODE_CONV = 2, MODE_CONVT = 3 };
 
 // buffer offsets at or above this are out of range for every descriptor we
 // build (num_records = 2^31): the load returns zeros
@@ -354,7 +354,8 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // types the host halves them (two FP8 values per unit), the staging code only moves bytes.
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
 __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mfma_kernel(Problem p, TileMap tmap) {
-    constexpr bool CONV = MODE == MODE_CONV;
+    constexpr bool CONVT = MODE == MODE_CONVT;               // transposed convolution: gather form
+    constexpr bool CONV = MODE == MODE_CONV || CONVT;        // A is an image, rows are output pixels
     constexpr bool TRANS_B = MODE == MODE_TRANS_B;
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -417,10 +418,17 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             int rem = gmc - n * pix;
             int oh = rem / p.conv.OW;
             int ow = rem - oh * p.conv.OW;
-            a_ih0[r] = oh * p.conv.stride_h - p.conv.pad_h;
-            a_iw0[r] = ow * p.conv.stride_w - p.conv.pad_w;
-            // byte offset of pixel (n, ih0, iw0), channel 0; may be "negative" (wraps), fixed up per tap
-            a_voff[r] = (unsigned)(((n * p.conv.H + a_ih0[r]) * p.conv.W + a_iw0[r]) * p.conv.Cin * 2);
+            if (CONVT) {
+                // output row oh receives tap kh from input row (oh + pad - kh*dil) / stride, if that divides
+                a_ih0[r] = oh + p.conv.pad_h;
+                a_iw0[r] = ow + p.conv.pad_w;
+                a_voff[r] = (unsigned)(n * p.conv.H * p.conv.W * p.conv.Cin * 2);    // image base
+            } else {
+                a_ih0[r] = oh * p.conv.stride_h - p.conv.pad_h;
+                a_iw0[r] = ow * p.conv.stride_w - p.conv.pad_w;
+                // byte offset of pixel (n, ih0, iw0), channel 0; may be "negative" (wraps), fixed up per tap
+                a_voff[r] = (unsigned)(((n * p.conv.H + a_ih0[r]) * p.conv.W + a_iw0[r]) * p.conv.Cin * 2);
+            }
         } else {
             a_voff[r] = a_ok[r] ? (unsigned)(row * (int)p.lda * 2 + chunk * 16) : kOob;
         }
@@ -461,6 +469,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     int4v ld_ra = make_rsrc(a_tile), ld_rb = make_rsrc(b_tile);
     int ld_dh = 0, ld_dw = 0;
     unsigned ld_delta = 0;
+    int ld_c = 0;              // transposed convolution, one tap per k-tile: first channel of the tile
 
     // Start issuing the k-tile at k0 into `stage`: descriptors rebased to k0.
     auto begin_tile = [&](int k0, int stage) {
@@ -470,6 +479,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         if (CONV) {
             ld_dh = tap_kh * p.conv.dil_h; ld_dw = tap_kw * p.conv.dil_w;
             ld_delta = (unsigned)(((ld_dh * p.conv.W + ld_dw) * p.conv.Cin + tap_c) * 2);
+            ld_c = tap_c;
             if (one_tap) {              // advance the uniform tap state to the next k-tile
                 tap_c += BK;
                 if (tap_c >= p.conv.Cin) {
@@ -490,7 +500,25 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         constexpr bool TAIL = decltype(tail_tag)::value;
         if (r < CA) {
             unsigned off;
-            if (CONV) {
+            if (CONVT) {
+                int dh, dw, c;
+                if (one_tap) {
+                    dh = ld_dh; dw = ld_dw; c = ld_c + a_kofs[r];
+                } else {
+                    int k = ld_k0 + a_kofs[r];
+                    int tap = k / p.conv.Cin;
+                    c = k - tap * p.conv.Cin;
+                    int kh = tap / p.conv.KW;
+                    int kw = tap - kh * p.conv.KW;
+                    dh = kh * p.conv.dil_h; dw = kw * p.conv.dil_w;
+                }
+                const int th = a_ih0[r] - dh, tw = a_iw0[r] - dw;
+                const int ih = th / p.conv.stride_h, iw = tw / p.conv.stride_w;
+                bool ok = a_ok[r] && th >= 0 && tw >= 0 && ih * p.conv.stride_h == th && iw * p.conv.stride_w == tw &&
+                          ih < p.conv.H && iw < p.conv.W;
+                if (TAIL) ok = ok && (ld_k0 + a_kofs[r] < p.K);
+                off = ok ? a_voff[r] + (unsigned)(((ih * p.conv.W + iw) * p.conv.Cin + c) * 2) : kOob;
+            } else if (CONV) {
                 int dh, dw;
                 if (one_tap) {
                     dh = ld_dh; dw = ld_dw;

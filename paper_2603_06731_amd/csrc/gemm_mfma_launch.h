@@ -56,6 +56,13 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
 
 template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
+    if (p.is_conv && p.conv.transposed) {
+        // the transposed form is built for the two configurations the dispatcher picks
+        if constexpr ((BM == 128 && BN == 256 && BK == 32) || (BM == 128 && BN == 128 && BK == 64))
+            return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONVT, NSTAGE, OCC>(p, stream, group_m);
+        else
+            return hipErrorInvalidValue;
+    }
     if (p.is_conv) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC>(p, stream, group_m);
     if (p.trans_b) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC>(p, stream, group_m);
     return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC>(p, stream, group_m);

@@ -62,6 +62,51 @@ pbk_status dispatch(const pbk::Problem& p, void* stream) {
     return PBK_OK;
 }
 
+// Shared tail of the convolution entry points.  pad_h / pad_w are the near-side (top, left)
+// paddings; OH / OW the output size the caller derived (negative = empty or invalid).
+pbk_status conv_common(const void* x, const void* w, void* y, const float* bias,
+                       int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                       int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                       int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                       int64_t OH, int64_t OW, int transposed,
+                       int in_dtype, int out_dtype, float alpha, int epi, void* stream) {
+    pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
+    if (s != PBK_OK) return s;
+    if (N < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 1 || KH < 1 || KW < 1) return PBK_ERR_SHAPE;
+    if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
+        return PBK_ERR_SHAPE;
+    const int64_t lim = 1 << 24;   // keeps every 32-bit index computation in range
+    if (H > lim || W > lim || Cin > lim || Cout > lim || KH > 4096 || KW > 4096 ||
+        stride_h > 4096 || stride_w > 4096 || pad_h > lim || pad_w > lim || dil_h > 4096 || dil_w > 4096)
+        return PBK_ERR_SHAPE;
+    if (OH < 1 || OW < 1 || OH > (lim << 4) || OW > (lim << 4)) return PBK_ERR_SHAPE;
+    if (N == 0) return PBK_OK;
+    if (!x || !w || !y) return PBK_ERR_NULL;
+    int64_t gm = N * OH * OW, gk = KH * KW * Cin;
+    if (gm > INT_MAX || gk > INT_MAX || N * H * W > INT_MAX) return PBK_ERR_SHAPE;
+    if (!aligned(x, elem_size(in_dtype)) || !aligned(w, elem_size(in_dtype)) ||
+        !aligned(y, elem_size(out_dtype)))
+        return PBK_ERR_ALIGN;
+
+    pbk::Problem p{};
+    p.A = x; p.B = w; p.C = y; p.bias = bias;
+    p.M = (int)gm; p.N = (int)Cout; p.K = (int)gk; p.batch = 1;
+    p.lda = gk;            // of the virtual im2col matrix; never dereferenced as such
+    p.ldb = Cout; p.ldc = Cout;
+    p.in_dtype = in_dtype; p.out_dtype = out_dtype;
+    p.trans_b = 0;
+    p.is_conv = 1;
+    p.epi = epi; p.alpha = alpha;
+    p.conv.H = (int)H; p.conv.W = (int)W; p.conv.Cin = (int)Cin;
+    p.conv.OH = (int)OH; p.conv.OW = (int)OW;
+    p.conv.KH = (int)KH; p.conv.KW = (int)KW;
+    p.conv.stride_h = (int)stride_h; p.conv.stride_w = (int)stride_w;
+    p.conv.pad_h = (int)pad_h; p.conv.pad_w = (int)pad_w;
+    p.conv.dil_h = (int)dil_h; p.conv.dil_w = (int)dil_w;
+    p.conv.transposed = transposed;
+    return dispatch(p, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -106,49 +151,59 @@ pbk_status pbk_matmul(const void* A, const void* B, void* C, const float* bias,
                               in_dtype, out_dtype, trans_b, alpha, epi, stream);
 }
 
+pbk_status pbk_conv2d_nhwc_pad4(const void* x, const void* w, void* y, const float* bias,
+                                int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                int64_t pad_top, int64_t pad_bottom, int64_t pad_left, int64_t pad_right,
+                                int64_t dil_h, int64_t dil_w,
+                                pbk_dtype in_dtype, pbk_dtype out_dtype,
+                                float alpha, pbk_epilogue epi, void* stream) {
+    int64_t OH = -1, OW = -1;
+    const int64_t lim = 1 << 24;
+    const bool sane = pad_top >= 0 && pad_bottom >= 0 && pad_left >= 0 && pad_right >= 0 &&
+                      pad_top <= lim && pad_bottom <= lim && pad_left <= lim && pad_right <= lim &&
+                      H >= 1 && W >= 1 && H <= lim && W <= lim && KH >= 1 && KW >= 1 && KH <= 4096 && KW <= 4096 &&
+                      stride_h >= 1 && stride_w >= 1 && dil_h >= 1 && dil_w >= 1 && dil_h <= 4096 && dil_w <= 4096;
+    if (sane) {
+        const int64_t span_h = H + pad_top + pad_bottom - dil_h * (KH - 1) - 1;
+        const int64_t span_w = W + pad_left + pad_right - dil_w * (KW - 1) - 1;
+        if (span_h >= 0 && span_w >= 0) { OH = span_h / stride_h + 1; OW = span_w / stride_w + 1; }
+    }
+    return conv_common(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, sane ? pad_top : -1,
+                       sane ? pad_left : -1, dil_h, dil_w, OH, OW, 0, in_dtype, out_dtype, alpha, epi, stream);
+}
+
 pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* bias,
                            int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                            pbk_dtype in_dtype, pbk_dtype out_dtype,
                            float alpha, pbk_epilogue epi, void* stream) {
-    pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
-    if (s != PBK_OK) return s;
-    if (N < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 1 || KH < 1 || KW < 1) return PBK_ERR_SHAPE;
-    if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
-        return PBK_ERR_SHAPE;
-    const int64_t lim = 1 << 24;   // keeps every 32-bit index computation in range
-    if (H > lim || W > lim || Cin > lim || Cout > lim || KH > 4096 || KW > 4096 ||
-        stride_h > 4096 || stride_w > 4096 || pad_h > lim || pad_w > lim || dil_h > 4096 || dil_w > 4096)
-        return PBK_ERR_SHAPE;
-    int64_t span_h = H + 2 * pad_h - dil_h * (KH - 1) - 1;
-    int64_t span_w = W + 2 * pad_w - dil_w * (KW - 1) - 1;
-    if (span_h < 0 || span_w < 0) return PBK_ERR_SHAPE;
-    int64_t OH = span_h / stride_h + 1, OW = span_w / stride_w + 1;
-    if (N == 0) return PBK_OK;
-    if (!x || !w || !y) return PBK_ERR_NULL;
-    int64_t gm = N * OH * OW, gk = KH * KW * Cin;
-    if (gm > INT_MAX || gk > INT_MAX || N * H * W > INT_MAX) return PBK_ERR_SHAPE;
-    if (!aligned(x, elem_size(in_dtype)) || !aligned(w, elem_size(in_dtype)) ||
-        !aligned(y, elem_size(out_dtype)))
-        return PBK_ERR_ALIGN;
+    return pbk_conv2d_nhwc_pad4(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
+                                pad_h, pad_h, pad_w, pad_w, dil_h, dil_w, in_dtype, out_dtype, alpha, epi, stream);
+}
 
-    pbk::Problem p{};
-    p.A = x; p.B = w; p.C = y; p.bias = bias;
-    p.M = (int)gm; p.N = (int)Cout; p.K = (int)gk; p.batch = 1;
-    p.lda = gk;            // of the virtual im2col matrix; never dereferenced as such
-    p.ldb = Cout; p.ldc = Cout;
-    p.in_dtype = in_dtype; p.out_dtype = out_dtype;
-    p.trans_b = 0;
-    p.is_conv = 1;
-    p.epi = epi; p.alpha = alpha;
-    p.conv.H = (int)H; p.conv.W = (int)W; p.conv.Cin = (int)Cin;
-    p.conv.OH = (int)OH; p.conv.OW = (int)OW;
-    p.conv.KH = (int)KH; p.conv.KW = (int)KW;
-    p.conv.stride_h = (int)stride_h; p.conv.stride_w = (int)stride_w;
-    p.conv.pad_h = (int)pad_h; p.conv.pad_w = (int)pad_w;
-    p.conv.dil_h = (int)dil_h; p.conv.dil_w = (int)dil_w;
-    return dispatch(p, stream);
+pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, const float* bias,
+                                     int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                     int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                     int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
+                                     int64_t dil_h, int64_t dil_w,
+                                     pbk_dtype in_dtype, pbk_dtype out_dtype,
+                                     float alpha, pbk_epilogue epi, void* stream) {
+    int64_t OH = -1, OW = -1;
+    const int64_t lim = 1 << 24;
+    const bool sane = H >= 1 && W >= 1 && H <= lim && W <= lim && KH >= 1 && KW >= 1 && KH <= 4096 && KW <= 4096 &&
+                      stride_h >= 1 && stride_w >= 1 && stride_h <= 4096 && stride_w <= 4096 &&
+                      dil_h >= 1 && dil_w >= 1 && dil_h <= 4096 && dil_w <= 4096 &&
+                      pad_h >= 0 && pad_w >= 0 && pad_h <= lim && pad_w <= lim && out_pad_h >= 0 && out_pad_w >= 0 &&
+                      (out_pad_h < stride_h || out_pad_h < dil_h) && (out_pad_w < stride_w || out_pad_w < dil_w);
+    if (sane) {
+        OH = (H - 1) * stride_h - 2 * pad_h + dil_h * (KH - 1) + out_pad_h + 1;
+        OW = (W - 1) * stride_w - 2 * pad_w + dil_w * (KW - 1) + out_pad_w + 1;
+        if (OH < 1 || OW < 1) OH = OW = -1;
+    }
+    return conv_common(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w,
+                       dil_h, dil_w, OH, OW, 1, in_dtype, out_dtype, alpha, epi, stream);
 }
 
 pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,

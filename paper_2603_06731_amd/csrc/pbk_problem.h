@@ -15,7 +15,11 @@ struct ConvGeom {
     int H, W, Cin;
     int OH, OW;
     int KH, KW;
-    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;   // pad: near side (top, left)
+    // 0: row (n, oh, ow) reads input rows oh*stride - pad + kh*dil.
+    // 1: transposed convolution in gather form: it reads input row (oh + pad - kh*dil)/stride
+    //    for the taps where the division is exact.
+    int transposed;
 };
 
 struct Problem {

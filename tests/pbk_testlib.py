@@ -87,7 +87,16 @@ def run_workload(w: wl.Workload, dev: dict, out=None, stream=None):
     m, n, k = w.gemm_mnk
     if out is None:
         out = device_empty(w.batch * m * n, w.out_dtype)
-    if w.kind == "conv":
+    if w.kind == "conv" and w.transposed:
+        st = pbk.pbk_conv2d_transpose_nhwc(dev["a"], dev["b"], out, dev["bias"], w.n, w.H, w.W, w.Cin, w.Cout,
+                                           w.KH, w.KW, w.stride[0], w.stride[1], w.pad[0], w.pad[1],
+                                           w.out_pad[0], w.out_pad[1], w.dil[0], w.dil[1],
+                                           w.in_dtype, w.out_dtype, w.alpha, w.epi, stream)
+    elif w.kind == "conv" and w.pad4:
+        st = pbk.pbk_conv2d_nhwc_pad4(dev["a"], dev["b"], out, dev["bias"], w.n, w.H, w.W, w.Cin, w.Cout,
+                                      w.KH, w.KW, w.stride[0], w.stride[1], *w.pad4, w.dil[0], w.dil[1],
+                                      w.in_dtype, w.out_dtype, w.alpha, w.epi, stream)
+    elif w.kind == "conv":
         st = pbk.pbk_conv2d_nhwc(dev["a"], dev["b"], out, dev["bias"], w.n, w.H, w.W, w.Cin, w.Cout,
                                  w.KH, w.KW, w.stride[0], w.stride[1], w.pad[0], w.pad[1],
                                  w.dil[0], w.dil[1], w.in_dtype, w.out_dtype, w.alpha, w.epi, stream)
@@ -110,6 +119,14 @@ def upload(host: dict) -> dict:
 def oracle_full(w: wl.Workload, host: dict):
     """(out, preact) float64 from the CPU oracle, full tensor."""
     import oracle
+    if w.kind == "conv" and w.transposed:
+        return oracle.conv2d_transpose_nhwc(host["a"], host["b"], host["bias"], dtype=w.in_dtype,
+                                            stride=w.stride, pad=w.pad, out_pad=w.out_pad, dil=w.dil,
+                                            alpha=w.alpha, epi=w.epi, want_preact=True)
+    if w.kind == "conv" and w.pad4:
+        return oracle.conv2d_nhwc_pad4(host["a"], host["b"], host["bias"], dtype=w.in_dtype,
+                                       stride=w.stride, pad=w.pad4, dil=w.dil, alpha=w.alpha,
+                                       epi=w.epi, want_preact=True)
     if w.kind == "conv":
         return oracle.conv2d_nhwc(host["a"], host["b"], host["bias"], dtype=w.in_dtype,
                                   stride=w.stride, pad=w.pad, dil=w.dil, alpha=w.alpha,
@@ -146,6 +163,10 @@ def oracle_sampled(w: wl.Workload, host: dict, b, i, j):
     if w.kind == "conv":
         pix = w.OH * w.OW
         sn, rem = i // pix, i % pix
+        if w.transposed:
+            return oracle.conv2d_transpose_nhwc_at(host["a"], host["b"], host["bias"], sn, rem // w.OW, rem % w.OW, j,
+                                                   dtype=w.in_dtype, stride=w.stride, pad=w.pad, out_pad=w.out_pad,
+                                                   dil=w.dil, alpha=w.alpha, epi=w.epi)
         return oracle.conv2d_nhwc_at(host["a"], host["b"], host["bias"], sn, rem // w.OW, rem % w.OW, j,
                                      dtype=w.in_dtype, stride=w.stride, pad=w.pad, dil=w.dil,
                                      alpha=w.alpha, epi=w.epi)

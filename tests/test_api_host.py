@@ -107,3 +107,24 @@ def test_attention_argument_errors(pbk):
     assert call(Q=P + 1) == 4 and call(O=P + 1) == 4 and call(bias=P + 2, ldb=8) == 4
     assert call(Q=P + 2, dtype=F32) == 4
     assert call(D=600, ldq=600, ldk=600, ldv=600, ldo=600, sq=4800, sk=4800, sv=4800, so=4800, dtype=F32) == 7
+
+
+def test_conv_variant_argument_errors(pbk):
+    F32 = 0
+    P = 0x1000
+    pad4 = pbk.pbk_conv2d_nhwc_pad4
+    tr = pbk.pbk_conv2d_transpose_nhwc
+
+    def p4(N=1, H=8, W=8, Cin=4, Cout=4, KH=3, KW=3, sh=1, sw=1, pt=0, pb=0, pl=0, pr=0, dh=1, dw=1, x=P):
+        return pad4(x, P, P, None, N, H, W, Cin, Cout, KH, KW, sh, sw, pt, pb, pl, pr, dh, dw, F32, F32, 1.0, 0)
+    assert p4(pt=-1) == 2 and p4(pr=-2) == 2 and p4(sh=0) == 2 and p4(dw=0) == 2
+    assert p4(H=2, pt=0, pb=0) == 2                 # empty output
+    assert p4(N=0) == 0
+    assert p4(x=None) == 1
+
+    def t(N=1, H=4, W=4, Cin=4, Cout=4, KH=3, KW=3, sh=2, sw=2, ph=0, pw=0, oh=0, ow=0, dh=1, dw=1, x=P):
+        return tr(x, P, P, None, N, H, W, Cin, Cout, KH, KW, sh, sw, ph, pw, oh, ow, dh, dw, F32, F32, 1.0, 0)
+    assert t(oh=2) == 2                             # out_pad must stay below stride or dilation
+    assert t(oh=-1) == 2 and t(ph=-1) == 2 and t(sh=0) == 2
+    assert t(H=1, W=1, KH=1, KW=1, sh=1, sw=1, ph=1, pw=1) == 2      # empty output
+    assert t(N=0) == 0 and t(x=None) == 1

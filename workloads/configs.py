@@ -49,6 +49,9 @@ class Workload:
     stride: tuple = (1, 1)
     pad: tuple = (0, 0)
     dil: tuple = (1, 1)
+    pad4: tuple = None           # (top, bottom, left, right) instead of `pad`
+    transposed: int = 0          # transposed convolution (uses pad, out_pad)
+    out_pad: tuple = (0, 0)
     # distributions: (dist, scale) per tensor
     dist_a: tuple = ("normal", 1.0)
     dist_b: tuple = ("normal", 1.0)
@@ -59,11 +62,17 @@ class Workload:
     # ---- derived sizes -------------------------------------------------
     @property
     def OH(self) -> int:
-        return (self.H + 2 * self.pad[0] - self.dil[0] * (self.KH - 1) - 1) // self.stride[0] + 1
+        if self.transposed:
+            return (self.H - 1) * self.stride[0] - 2 * self.pad[0] + self.dil[0] * (self.KH - 1) + self.out_pad[0] + 1
+        both = self.pad4[0] + self.pad4[1] if self.pad4 else 2 * self.pad[0]
+        return (self.H + both - self.dil[0] * (self.KH - 1) - 1) // self.stride[0] + 1
 
     @property
     def OW(self) -> int:
-        return (self.W + 2 * self.pad[1] - self.dil[1] * (self.KW - 1) - 1) // self.stride[1] + 1
+        if self.transposed:
+            return (self.W - 1) * self.stride[1] - 2 * self.pad[1] + self.dil[1] * (self.KW - 1) + self.out_pad[1] + 1
+        both = self.pad4[2] + self.pad4[3] if self.pad4 else 2 * self.pad[1]
+        return (self.W + both - self.dil[1] * (self.KW - 1) - 1) // self.stride[1] + 1
 
     @property
     def gemm_mnk(self):
