@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
              or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
     if force or stale:
         tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
                                "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
                                                       + [i32, f32, i32, i64, vp, vp, vp, vp])
         L.oracle_conv_transpose_out_dim.argtypes = [i64] * 6
         L.oracle_conv_transpose_out_dim.restype = i64
+        L.oracle_matmul_int8.argtypes = ([vp, vp, vp, vp] + [i64] * 6 + [i32, vp, vp, f32, vp, vp, i32, f32, i32])
+        L.oracle_conv2d_nhwc_int8.argtypes = ([vp, vp, vp, vp] + [i64] * 13 + [vp, vp, f32, vp, vp, i32, f32, i32])
         L.oracle_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32]
         L.oracle_attention_rows.argtypes = [vp, vp, vp, vp, vp] + [i64] * 12 + [i32, f32, i64, vp, vp]
         L.oracle_conv_out_dim.argtypes = [i64] * 5
@@ -288,6 +290,52 @@ def conv2d_transpose_nhwc_at(x, w, bias, sn, soh, sow, sco, *, dtype, stride=(1,
                                                *[_ptr(a) for a in idx])
     _rc(rc, "conv2d_transpose_nhwc_at")
     return out, pre
+
+
+def _f32vec(v, n, name):
+    if v is None:
+        return None
+    v = np.ascontiguousarray(v)
+    if v.dtype != np.float32 or v.shape != (n,):
+        raise TypeError(f"{name} must be float32 [{n}]")
+    return v
+
+
+def matmul_int8(A, B, *, scale, bias=None, mid_scale=0.0, mul=None, add=None, relu=False, out_scale=1.0,
+                out_int8=True, trans_b=0, want_acc=False):
+    """int8 matmul with the quantised epilogue; returns int8 (or float32) [M][N], and the int32 sums if asked."""
+    A = np.ascontiguousarray(A); B = np.ascontiguousarray(B)
+    if A.dtype != np.int8 or B.dtype != np.int8:
+        raise TypeError("int8 operands expected")
+    M, K = A.shape
+    N = B.shape[0] if trans_b else B.shape[1]
+    scale, bias, mul, add = (_f32vec(v, N, n) for v, n in ((scale, "scale"), (bias, "bias"), (mul, "mul"), (add, "add")))
+    out = np.empty((M, N), dtype=np.int8 if out_int8 else np.float32)
+    acc = np.empty((M, N), dtype=np.int32) if want_acc else None
+    rc = lib().oracle_matmul_int8(_ptr(A), _ptr(B), _ptr(out), _ptr(acc), M, N, K, K, B.shape[1], N, int(trans_b),
+                                  _ptr(scale), _ptr(bias), float(mid_scale), _ptr(mul), _ptr(add), int(relu),
+                                  float(out_scale), int(out_int8))
+    _rc(rc, "matmul_int8")
+    return (out, acc) if want_acc else out
+
+
+def conv2d_nhwc_int8(x, w, *, scale, bias=None, mid_scale=0.0, mul=None, add=None, relu=False, out_scale=1.0,
+                     out_int8=True, stride=(1, 1), pad=(0, 0), dil=(1, 1), want_acc=False):
+    x = np.ascontiguousarray(x); w = np.ascontiguousarray(w)
+    if x.dtype != np.int8 or w.dtype != np.int8:
+        raise TypeError("int8 operands expected")
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    OH = conv_out_dim(H, KH, stride[0], pad[0], dil[0]); OW = conv_out_dim(W, KW, stride[1], pad[1], dil[1])
+    scale, bias, mul, add = (_f32vec(v, Cout, n) for v, n in ((scale, "scale"), (bias, "bias"), (mul, "mul"), (add, "add")))
+    out = np.empty((N, OH, OW, Cout), dtype=np.int8 if out_int8 else np.float32)
+    acc = np.empty((N, OH, OW, Cout), dtype=np.int32) if want_acc else None
+    rc = lib().oracle_conv2d_nhwc_int8(_ptr(x), _ptr(w), _ptr(out), _ptr(acc), N, H, W, Cin, Cout, KH, KW,
+                                       stride[0], stride[1], pad[0], pad[1], dil[0], dil[1],
+                                       _ptr(scale), _ptr(bias), float(mid_scale), _ptr(mul), _ptr(add), int(relu),
+                                       float(out_scale), int(out_int8))
+    _rc(rc, "conv2d_nhwc_int8")
+    return (out, acc) if want_acc else out
 
 
 def _attention_args(Q, K, V, bias, dtype):

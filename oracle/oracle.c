@@ -516,6 +516,133 @@ int oracle_conv2d_transpose_nhwc_at(const void* x, const void* w, const float* b
     return 0;
 }
 
+/* ---- int8 contraction with the quantised epilogue ------------------------ */
+
+/* The epilogue of the paper's fused quantised convolution (appendix on
+ * quantisation, figure of the fused de-quantisation / quantisation nest), in
+ * the paper's precision: every step is one IEEE binary32 operation, in this
+ * order, with no contraction into fused multiply-adds:
+ *   t = float(acc) * scale[j]            de-quantise (per output channel)
+ *   t = t + bias[j]                      (if bias)
+ *   if mid_scale > 0:                    the quantise / de-quantise pair that the
+ *       q = clamp(roundeven(t / mid_scale), -128, 127);  t = float(q) * mid_scale
+ *   t = t * mul[j]   (if mul);  t = t + add[j]   (if add)      folded batch-norm
+ *   t = t > 0 ? t : 0                    (if relu)
+ *   int8 output:  clamp(roundeven(t / out_scale), -128, 127);  float output: t
+ * The accumulator is the exact integer sum. */
+typedef struct {
+    const float* scale;
+    const float* bias;
+    float mid_scale;
+    const float* mul;
+    const float* add;
+    int relu;
+    float out_scale;
+} quant_epi;
+
+static float quantise_step(float t, float step)
+{
+    volatile float q = t / step;            /* volatile: one rounding per operation, whatever the optimiser does */
+    q = rintf(q);                           /* default rounding mode: nearest, ties to even */
+    if (q < -128.0f) q = -128.0f;
+    if (q > 127.0f) q = 127.0f;
+    return q;
+}
+
+static float quant_epilogue(int64_t acc, int64_t j, const quant_epi* e)
+{
+    volatile float t = (float)(int32_t)acc;
+    t = t * e->scale[j];
+    if (e->bias) t = t + e->bias[j];
+    if (e->mid_scale > 0.0f) {
+        volatile float q = quantise_step(t, e->mid_scale);
+        t = q * e->mid_scale;
+    }
+    if (e->mul) t = t * e->mul[j];
+    if (e->add) t = t + e->add[j];
+    if (e->relu) t = t > 0.0f ? t : 0.0f;
+    return t;
+}
+
+static int check_quant(const quant_epi* e, int out_int8)
+{
+    if (!e->scale) return -3;
+    if (e->mid_scale < 0.0f || (out_int8 && !(e->out_scale > 0.0f))) return -2;
+    return 0;
+}
+
+static void store_quant(void* out, int64_t o, float t, const quant_epi* e, int out_int8)
+{
+    if (out_int8) ((int8_t*)out)[o] = (int8_t)quantise_step(t, e->out_scale);
+    else ((float*)out)[o] = t;
+}
+
+int oracle_matmul_int8(const int8_t* A, const int8_t* B, void* out, int32_t* acc_out,
+                       int64_t M, int64_t N, int64_t K,
+                       int64_t lda, int64_t ldb, int64_t ldo, int trans_b,
+                       const float* scale, const float* bias, float mid_scale,
+                       const float* mul, const float* add, int relu, float out_scale,
+                       int out_int8)
+{
+    quant_epi e = {scale, bias, mid_scale, mul, add, relu, out_scale};
+    int rc = check_quant(&e, out_int8);
+    if (rc) return rc;
+    if (M < 0 || N < 0 || K < 0 || K > 131071) return -4;
+    if (lda < K || ldo < N || ldb < (trans_b ? K : N)) return -5;
+    if ((M && N) && (!out || (K && (!A || !B)))) return -6;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int64_t)A[i * lda + k] * (int64_t)(trans_b ? B[j * ldb + k] : B[k * ldb + j]);
+            if (acc_out) acc_out[i * N + j] = (int32_t)acc;
+            store_quant(out, i * ldo + j, quant_epilogue(acc, j, &e), &e, out_int8);
+        }
+    return 0;
+}
+
+int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t* acc_out,
+                            int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                            const float* scale, const float* bias, float mid_scale,
+                            const float* mul, const float* add, int relu, float out_scale,
+                            int out_int8)
+{
+    quant_epi e = {scale, bias, mid_scale, mul, add, relu, out_scale};
+    int rc = check_quant(&e, out_int8);
+    if (rc) return rc;
+    if (N < 0 || Cin < 1 || Cout < 1 || KH * KW * Cin > 131071) return -4;
+    int64_t OH = oracle_conv_out_dim(H, KH, stride_h, pad_h, dil_h);
+    int64_t OW = oracle_conv_out_dim(W, KW, stride_w, pad_w, dil_w);
+    if (OH < 0 || OW < 0) return -5;
+    if (!x || !w || !out) return -6;
+    for (int64_t n = 0; n < N; ++n) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t oh = 0; oh < OH; ++oh)
+            for (int64_t ow = 0; ow < OW; ++ow)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    int64_t acc = 0;
+                    for (int64_t kh = 0; kh < KH; ++kh) {
+                        int64_t ih = oh * stride_h - pad_h + kh * dil_h;
+                        if (ih < 0 || ih >= H) continue;
+                        for (int64_t kw = 0; kw < KW; ++kw) {
+                            int64_t iw = ow * stride_w - pad_w + kw * dil_w;
+                            if (iw < 0 || iw >= W) continue;
+                            for (int64_t c = 0; c < Cin; ++c)
+                                acc += (int64_t)x[((n * H + ih) * W + iw) * Cin + c] *
+                                       (int64_t)w[((kh * KW + kw) * Cin + c) * Cout + co];
+                        }
+                    }
+                    int64_t o = ((n * OH + oh) * OW + ow) * Cout + co;
+                    if (acc_out) acc_out[o] = (int32_t)acc;
+                    store_quant(out, o, quant_epilogue(acc, co, &e), &e, out_int8);
+                }
+    }
+    return 0;
+}
+
 /* ---- attention ---------------------------------------------------------- */
 
 /* One output row (b, i) of  softmax(alpha * Q K^T + bias) V,  by the definition:

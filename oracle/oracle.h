@@ -130,6 +130,33 @@ int oracle_conv2d_transpose_nhwc_at(const void* x, const void* w, const float* b
 int64_t oracle_conv_transpose_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad,
                                       int64_t out_pad, int64_t dil);
 
+/* int8 x int8 contraction, exact integer accumulation, and the quantised
+ * epilogue of the paper's appendix on quantisation (figure of the fused
+ * de-quantisation / quantisation nest).  The epilogue runs in binary32, one
+ * rounding per operation, in this order:
+ *   t = float(acc) * scale[j];  t += bias[j] (if bias);
+ *   if mid_scale > 0: t = float(clamp(roundeven(t / mid_scale), -128, 127)) * mid_scale;
+ *   t *= mul[j] (if mul);  t += add[j] (if add);  t = max(t, 0) (if relu);
+ *   out_int8 ? int8(clamp(roundeven(t / out_scale), -128, 127)) : t.
+ * out is int8_t or float accordingly; acc_out (may be NULL) receives the
+ * integer sums.  B is K x N (ldb) or, if trans_b, N x K.  K <= 131071 keeps the
+ * sum inside int32. */
+int oracle_matmul_int8(const int8_t* A, const int8_t* B, void* out, int32_t* acc_out,
+                       int64_t M, int64_t N, int64_t K,
+                       int64_t lda, int64_t ldb, int64_t ldo, int trans_b,
+                       const float* scale, const float* bias, float mid_scale,
+                       const float* mul, const float* add, int relu, float out_scale,
+                       int out_int8);
+
+/* Same epilogue on the direct convolution (x NHWC, w HWIO, symmetric padding). */
+int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t* acc_out,
+                            int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                            const float* scale, const float* bias, float mid_scale,
+                            const float* mul, const float* add, int relu, float out_scale,
+                            int out_int8);
+
 /* Attention layer (paper Sec. 4.4; the operator of its attention example):
  *   out[b][i][d] = sum_j P[b][i][j] * V[b][j][d],
  *   P[b][i][:]   = softmax_j( alpha * sum_c Q[b][i][c]*K[b][j][c] + bias[b][i][j] ).
