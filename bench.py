@@ -27,7 +27,7 @@ HEADLINE = "cfg2_bf16_8192"
 PEAK_MFMA_16BIT_TFLOPS = 2516.6     # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16/fp16)
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-DTYPE_NAMES = {0: "f32", 1: "bf16", 2: "f16", 3: "fp8_e4m3", 4: "fp8_e5m2"}
+DTYPE_NAMES = {0: "f32", 1: "bf16", 2: "f16", 3: "fp8_e4m3", 4: "fp8_e5m2", 5: "int8"}
 PEAK_MFMA_FP8_TFLOPS = 5033.2       # twice the 16-bit rate
 
 
@@ -35,13 +35,19 @@ def is_attention(w):
     return hasattr(w, "Nq")
 
 
+def is_int8(w):
+    return type(w).__name__ == "Int8Workload"
+
+
 def in_dtype_of(w):
-    return w.dtype if is_attention(w) else w.in_dtype
+    return 5 if is_int8(w) else w.dtype if is_attention(w) else w.in_dtype
 
 
 def bound_of(w):
     """Which roofline bounds the workload: arithmetic intensity against the ridge."""
     import workloads as wl
+    if is_int8(w):
+        return ("mfma", PEAK_MFMA_FP8_TFLOPS)       # int8 dense MFMA: 5.0 POP/s, same rate as FP8
     if is_attention(w):
         peak = PEAK_FP32_TFLOPS if w.dtype == wl.DTYPE_F32 else PEAK_MFMA_16BIT_TFLOPS
         ridge = peak * 1e12 / (PEAK_HBM_GBS * 1e9)
@@ -60,7 +66,16 @@ def time_workload(w, steps, warmup):
     import pbk_testlib as T
     import paper_2603_06731_amd as pbk
 
-    if is_attention(w):
+    if is_int8(w):
+        host = wl.make_int8_inputs(w)
+        out = torch.empty(w.M * w.N, dtype=torch.int8, device="cuda")
+
+        def run(w, dev, out=None, stream=None):
+            return pbk.pbk_matmul_int8(dev["a"], dev["b"], out, w.M, w.N, w.K, w.K, w.K, w.N, 1, dev["scale"], dev["bias"],
+                                       host["mid_scale"], dev["mul"], dev["add"], host["relu"], host["out_scale"],
+                                       5, stream), out
+        dev = {k: torch.from_numpy(v).cuda() for k, v in host.items() if hasattr(v, "dtype")}
+    elif is_attention(w):
         host = wl.make_attention_inputs(w)
         out = T.device_empty(w.batch * w.Nq * w.D, w.dtype)
         run = T.run_attention
@@ -69,7 +84,8 @@ def time_workload(w, steps, warmup):
         m, n, _ = w.gemm_mnk
         out = T.device_empty(w.batch * m * n, w.out_dtype)
         run = T.run_workload
-    dev = T.upload(host)
+    if not is_int8(w):
+        dev = T.upload(host)
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         st, _o = run(w, dev, out=out, stream=stream)
@@ -120,6 +136,16 @@ def cpu_baseline(w, host, budget_s=15.0):
     import workloads as wl
     if is_attention(w):
         return cpu_baseline_attention(w, host, budget_s)
+    if is_int8(w):
+        q = {k: host[k] for k in ("scale", "bias", "mid_scale", "mul", "add", "relu", "out_scale")}
+        rows = 8
+        t0 = time.perf_counter(); oracle.matmul_int8(host["a"][:rows], host["b"], trans_b=1, **q); dt = time.perf_counter() - t0
+        rows2 = int(min(w.M, max(rows, rows * budget_s / max(dt, 1e-6))))
+        if rows2 > 2 * rows:
+            rows = rows2
+            t0 = time.perf_counter(); oracle.matmul_int8(host["a"][:rows], host["b"], trans_b=1, **q); dt = time.perf_counter() - t0
+        return {"value": 2.0 * rows * w.N * w.K / dt / 1e12, "unit": "TOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": f"{rows} rows x {w.N} columns of the output (K={w.K}), {dt:.1f} s", "seconds": dt}
     threads = oracle.num_threads()
     m, n, k = w.gemm_mnk
 
@@ -185,7 +211,10 @@ def report(w, r, steps, warmup, with_cpu=True):
         "ms_per_step": r["wall_ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAMES[in_dtype_of(w)], "data": "synthetic",
-        "config": ({"workload": w.name, "kind": "attention", "batch_x_heads": w.batch, "Nq": w.Nq, "Nk": w.Nk,
+        "config": ({"workload": w.name, "kind": "matmul_int8", "gemm_mnk": [w.M, w.N, w.K], "trans_b": 1,
+                    "epilogue": "dequant+bias+requant pair+affine+relu+quantise", "out_dtype": "int8",
+                    "kernel": r["kernel"]} if is_int8(w) else
+                   {"workload": w.name, "kind": "attention", "batch_x_heads": w.batch, "Nq": w.Nq, "Nk": w.Nk,
                     "D": w.D, "bias": w.bias, "kernel": r["kernel"]} if is_attention(w) else
                    {"workload": w.name, "kind": w.kind, "gemm_mnk": list(w.gemm_mnk), "batch": w.batch,
                     "epilogue": w.epi, "out_dtype": DTYPE_NAMES[w.out_dtype], "kernel": r["kernel"]}),
@@ -235,7 +264,7 @@ def main():
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": args.steps}))
         return
 
-    w = {**wl.CONFIGS, **wl.EXTRA_CONFIGS, **wl.ATTENTION_CONFIGS}[args.workload]
+    w = {**wl.CONFIGS, **wl.EXTRA_CONFIGS, **wl.ATTENTION_CONFIGS, **wl.INT8_CONFIGS}[args.workload]
     r = time_workload(w, args.steps, args.warmup)
     line = report(w, r, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline)
     del r

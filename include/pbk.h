@@ -62,7 +62,8 @@ typedef enum {
     PBK_BF16 = 1,
     PBK_F16 = 2,
     PBK_FP8_E4M3 = 3,   /* OCP FP8 E4M3 (bias 7, no infinities, max 448); input type only */
-    PBK_FP8_E5M2 = 4    /* OCP FP8 E5M2 (bias 15, max 57344); input type only */
+    PBK_FP8_E5M2 = 4,   /* OCP FP8 E5M2 (bias 15, max 57344); input type only */
+    PBK_INT8 = 5        /* signed 8-bit integers; only through the *_int8 entry points */
 } pbk_dtype;
 
 typedef enum {
@@ -149,6 +150,42 @@ pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, cons
                                      int64_t dil_h, int64_t dil_w,
                                      pbk_dtype in_dtype, pbk_dtype out_dtype,
                                      float alpha, pbk_epilogue epi, void* stream);
+
+/*
+ * int8 x int8 contraction with exact 32-bit integer accumulation and the quantised
+ * epilogue of the paper's appendix on quantisation (the fused de-quantisation /
+ * quantisation nest at the output of a quantised convolution), computed in
+ * binary32, one rounding per operation, in this order, for output column j:
+ *   t = float(acc) * scale[j];           de-quantise (scale is required)
+ *   t = t + bias[j]                      if bias != NULL
+ *   if mid_scale > 0:                    a quantise / de-quantise pair
+ *       t = float(clamp(roundeven(t / mid_scale), -128, 127)) * mid_scale
+ *   t = t * mul[j]                       if mul != NULL   (folded batch-norm scale)
+ *   t = t + add[j]                       if add != NULL   (folded batch-norm shift)
+ *   t = t > 0 ? t : 0                    if relu != 0
+ *   out_dtype PBK_INT8: C = int8(clamp(roundeven(t / out_scale), -128, 127)), out_scale > 0
+ *   out_dtype PBK_F32:  C = t
+ * Results are bit-exact for a given input whatever kernel runs.  scale, bias, mul,
+ * add are device float arrays of N entries.  K (KH*KW*Cin) must not exceed 131071
+ * (PBK_ERR_UNSUPPORTED), which keeps every sum inside 32 bits.  A: M x K (lda);
+ * B: K x N (ldb) or, if trans_b, N x K.  The matrix-unit kernel takes trans_b with
+ * 16-byte aligned A, B and K, lda, ldb multiples of 16; other calls, and the
+ * convolution (x NHWC, w HWIO, symmetric padding, OH/OW as pbk_conv2d_nhwc), run on
+ * the generic kernel with integer accumulation.
+ */
+pbk_status pbk_matmul_int8(const int8_t* A, const int8_t* B, void* C,
+                           int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int trans_b,
+                           const float* scale, const float* bias, float mid_scale,
+                           const float* mul, const float* add, int relu, float out_scale,
+                           pbk_dtype out_dtype, void* stream);
+
+pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
+                                int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                const float* scale, const float* bias, float mid_scale,
+                                const float* mul, const float* add, int relu, float out_scale,
+                                pbk_dtype out_dtype, void* stream);
 
 /*
  * Attention layer, every operator fused into one kernel          (paper Sec. 4.4)

@@ -10,12 +10,12 @@ import ctypes
 import os
 
 PBK_OK = 0
-PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2 = 0, 1, 2, 3, 4
+PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2, PBK_INT8 = 0, 1, 2, 3, 4, 5
 (PBK_EPI_NONE, PBK_EPI_BIAS, PBK_EPI_RELU, PBK_EPI_BIAS_RELU,
  PBK_EPI_BIAS_GELU_TANH, PBK_EPI_GELU_TANH) = range(6)
 
 EXPORTED_SYMBOLS = ("pbk_matmul", "pbk_batched_matmul", "pbk_conv2d_nhwc", "pbk_conv2d_nhwc_pad4",
-                    "pbk_conv2d_transpose_nhwc", "pbk_attention",
+                    "pbk_conv2d_transpose_nhwc", "pbk_attention", "pbk_matmul_int8", "pbk_conv2d_nhwc_int8",
                     "pbk_status_string", "pbk_version", "pbk_last_kernel")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -60,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.pbk_conv2d_nhwc_pad4.restype = i32
         L.pbk_conv2d_transpose_nhwc.argtypes = [vp, vp, vp, vp] + [i64] * 15 + [i32, i32, f32, i32, vp]
         L.pbk_conv2d_transpose_nhwc.restype = i32
+        L.pbk_matmul_int8.argtypes = [vp, vp, vp] + [i64] * 6 + [i32, vp, vp, f32, vp, vp, i32, f32, i32, vp]
+        L.pbk_matmul_int8.restype = i32
+        L.pbk_conv2d_nhwc_int8.argtypes = [vp, vp, vp] + [i64] * 13 + [vp, vp, f32, vp, vp, i32, f32, i32, vp]
+        L.pbk_conv2d_nhwc_int8.restype = i32
         L.pbk_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32, vp]
         L.pbk_attention.restype = i32
         L.pbk_status_string.argtypes = [i32]
@@ -123,6 +127,20 @@ def pbk_conv2d_transpose_nhwc(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_
     return lib().pbk_conv2d_transpose_nhwc(_ptr(x), _ptr(w), _ptr(y), _ptr(bias), N, H, W, Cin, Cout,
                                            KH, KW, stride_h, stride_w, pad_h, pad_w, out_pad_h, out_pad_w,
                                            dil_h, dil_w, in_dtype, out_dtype, float(alpha), epi, _stream(stream))
+
+
+def pbk_matmul_int8(A, B, C, M, N, K, lda, ldb, ldc, trans_b, scale, bias, mid_scale, mul, add, relu,
+                    out_scale, out_dtype, stream=None) -> int:
+    return lib().pbk_matmul_int8(_ptr(A), _ptr(B), _ptr(C), M, N, K, lda, ldb, ldc, int(trans_b), _ptr(scale),
+                                 _ptr(bias), float(mid_scale), _ptr(mul), _ptr(add), int(relu), float(out_scale),
+                                 out_dtype, _stream(stream))
+
+
+def pbk_conv2d_nhwc_int8(x, w, y, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                         scale, bias, mid_scale, mul, add, relu, out_scale, out_dtype, stream=None) -> int:
+    return lib().pbk_conv2d_nhwc_int8(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
+                                      pad_h, pad_w, dil_h, dil_w, _ptr(scale), _ptr(bias), float(mid_scale),
+                                      _ptr(mul), _ptr(add), int(relu), float(out_scale), out_dtype, _stream(stream))
 
 
 def pbk_attention(Q, K, V, bias, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo,

@@ -7,6 +7,7 @@
 // buffers, Sec. 4.5 on-the-fly packing of the im2col tile, partial tiles
 // zero-filled) at a tile size picked for VALU rather than matrix units.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include "pbk_problem.h"
 #include "pbk_epilogue.h"
 
@@ -18,6 +19,12 @@ constexpr int GK = 16;     // tile depth
 constexpr int GPAD = 4;
 
 template <typename T> __device__ __forceinline__ float ld_elem(const T* p, int64_t i) { return widen<T>(p[i]); }
+
+// accumulator type: exact 32-bit integers for int8 operands, fp32 otherwise
+template <typename T> struct AccOf { typedef float type; };
+template <> struct AccOf<int8_t> { typedef int type; };
+__device__ __forceinline__ float mad(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ __forceinline__ int mad(int a, int b, int c) { return a * b + c; }
 
 // A(i, k) of the implicit GEMM: im2col element, zero outside the image.
 template <typename T>
@@ -47,8 +54,9 @@ __device__ __forceinline__ float conv_a(const T* x, const ConvGeom& g, int i, in
 
 template <typename T, bool CONV>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_m, int tiles_n) {
-    __shared__ float As[GK][GT + GPAD];
-    __shared__ float Bs[GK][GT + GPAD];
+    typedef typename AccOf<T>::type acc_t;
+    __shared__ acc_t As[GK][GT + GPAD];
+    __shared__ acc_t Bs[GK][GT + GPAD];
 
     int bid = blockIdx.x;
     int tn = bid % tiles_n;
@@ -62,11 +70,11 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
 
     int t = threadIdx.x;
     int tx = t % 16, ty = t / 16;
-    float acc[4][4];
+    acc_t acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0;
 
     for (int k0 = 0; k0 < p.K; k0 += GK) {
         // A tile: 64 rows x 16 k; lanes run along k (contiguous in memory)
@@ -80,7 +88,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
                 if (CONV) v = conv_a<T>(A, p.conv, gm, gk);
                 else v = ld_elem<T>(A, (int64_t)gm * p.lda + gk);
             }
-            As[kk][mm] = v;
+            As[kk][mm] = (acc_t)v;
         }
         // B tile: 16 k x 64 n
 #pragma unroll
@@ -94,12 +102,12 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
             if (gk < p.K && gn < p.N)
                 v = p.trans_b ? ld_elem<T>(B, (int64_t)gn * p.ldb + gk)
                               : ld_elem<T>(B, (int64_t)gk * p.ldb + gn);
-            Bs[kk][nn] = v;
+            Bs[kk][nn] = (acc_t)v;
         }
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < GK; ++kk) {
-            float a[4], bv[4];
+            acc_t a[4], bv[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
 #pragma unroll
@@ -107,7 +115,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], bv[j], acc[i][j]);
+                for (int j = 0; j < 4; ++j) acc[i][j] = mad(a[i], bv[j], acc[i][j]);
         }
         __syncthreads();
     }
@@ -121,9 +129,18 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
         for (int j = 0; j < 4; ++j) {
             int gn = n0 + tx * 4 + j;
             if (gn >= p.N) continue;
-            float bias = has_bias ? p.bias[gn] : 0.0f;
-            float v = apply_epilogue(acc[i][j], p.alpha, bias, p.epi);
             int64_t o = (int64_t)b * p.stride_c + (int64_t)gm * p.ldc + gn;
+            if constexpr (std::is_same<T, int8_t>::value) {
+                QuantParams c = {p.q_scale[gn], p.bias ? p.bias[gn] : 0.0f, p.q_mul ? p.q_mul[gn] : 1.0f,
+                                 p.q_add ? p.q_add[gn] : 0.0f};
+                float t = quant_value(acc[i][j], c, p.bias != nullptr, p.q_mul != nullptr, p.q_add != nullptr,
+                                      p.q_mid, p.q_relu);
+                if (p.out_dtype == DT_INT8) ((int8_t*)p.C)[o] = quant_code(t, p.q_out);
+                else ((float*)p.C)[o] = t;
+                continue;
+            }
+            float bias = has_bias ? p.bias[gn] : 0.0f;
+            float v = apply_epilogue((float)acc[i][j], p.alpha, bias, p.epi);
             if (p.out_dtype == DT_F32) ((float*)p.C)[o] = v;
             else if (p.out_dtype == DT_BF16) ((uint16_t*)p.C)[o] = to_bits16<bf16_t>(v);
             else ((uint16_t*)p.C)[o] = to_bits16<f16_t>(v);
@@ -153,6 +170,7 @@ hipError_t launch_generic(const Problem& p, hipStream_t stream, const char** nam
     case DT_F16: return launch_t<f16_t>(p, stream);
     case DT_FP8_E4M3: return launch_t<fp8_e4m3_t>(p, stream);
     case DT_FP8_E5M2: return launch_t<fp8_e5m2_t>(p, stream);
+    case DT_INT8: return launch_t<int8_t>(p, stream);
     default: return hipErrorInvalidValue;
     }
 }

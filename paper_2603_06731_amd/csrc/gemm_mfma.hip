@@ -11,7 +11,8 @@ static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 // entirely inside or outside the matrix; likewise N for row-major B and Cin
 // for the convolution (a piece must not straddle two filter taps).
 bool mfma_supported(const Problem& p) {
-    const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2;
+    // 8-bit operand types (FP8, int8) share the rules: 16 values per 16-byte piece, k-major operands
+    const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2 || p.in_dtype == DT_INT8;
     if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16 && !fp8) return false;
     const int per16 = fp8 ? 16 : 8;                  // elements per 16-byte piece
     const int esz = fp8 ? 1 : 2;
@@ -45,6 +46,16 @@ static int choose_config(const Problem& p) {
 
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name) {
     const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2;
+    if (p.in_dtype == DT_INT8) {
+        // measured: the 256x256 tile with the deep k-tile is the fastest of the three built for int8
+        long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
+        int c = (force_cfg == 0 || force_cfg == 1 || force_cfg == 4) ? force_cfg
+                : (p.M >= 256 && p.N >= 256 && t256 >= 128) ? 4 : 1;
+        *name = kMfmaConfigs[c].name;
+        int gm = 8;
+        if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) gm = g; }
+        return launch_mfma_int8(p, stream, c, gm);
+    }
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
     if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1) cfg = choose_config(p);   // only 0 and 1 are built
     if (fp8) {

@@ -95,6 +95,18 @@ template <> struct MfmaOp<fp8_e5m2_t> {
     }
 };
 
+// int8: v_mfma_i32_32x32x32_i8, 16 bytes (16 values) per lane and operand; the 32-bit integer
+// accumulators travel in the same registers, typed as floats only in name
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+template <> struct MfmaOp<int8_t> {
+    static constexpr int kChunks = 1;
+    static __device__ __forceinline__ f32x16 run(const Frag<1>& a, const Frag<1>& b, f32x16 c) {
+        i32x16 r = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(int4v, a.c[0]), __builtin_bit_cast(int4v, b.c[0]),
+                                                         __builtin_bit_cast(i32x16, c), 0, 0, 0);
+        return __builtin_bit_cast(f32x16, r);
+    }
+};
+
 // How linear workgroup ids are turned into (batch, tile_m, tile_n).
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; ids
 // are first regrouped so that every XCD owns a contiguous run, then runs are
@@ -314,6 +326,64 @@ struct EpiCtx {
         }
     }
 
+    // ---- int8 path: the accumulators are 32-bit integers; quantised epilogue, stores straight
+    // from registers (4 consecutive columns per lane: one dword of int8 codes, or 16 bytes of fp32)
+    __device__ __forceinline__ void run_quant() {
+        const bool out_i8 = p.out_dtype == DT_INT8;
+        const bool has_bias = p.bias != nullptr, has_mul = p.q_mul != nullptr, has_add = p.q_add != nullptr;
+        const int esz = out_i8 ? 1 : 4;
+        const bool vec = (p.N % 4 == 0) && (p.ldc % 4 == 0) &&
+                         (((uintptr_t)p.C + (uintptr_t)c_batch * esz) % (4 * esz) == 0);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int gn = col0 + j * 32 + g * 8 + ((lane >> 5) << 2);
+                QuantParams c[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool in = gn + e < p.N;
+                    c[e].scale = in ? p.q_scale[gn + e] : 0.0f;
+                    c[e].bias = (in && has_bias) ? p.bias[gn + e] : 0.0f;
+                    c[e].mul = (in && has_mul) ? p.q_mul[gn + e] : 1.0f;
+                    c[e].add = (in && has_add) ? p.q_add[gn + e] : 0.0f;
+                }
+#pragma unroll
+                for (int i = 0; i < FM; ++i) {
+                    const int gm = row0 + i * 32 + (lane & 31);
+                    if (gm >= p.M || gn >= p.N) continue;
+                    const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
+                    float t[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        t[e] = quant_value(__float_as_int(acc[i][j][g * 4 + e]), c[e], has_bias, has_mul, has_add,
+                                           p.q_mid, p.q_relu);
+                    if (out_i8) {
+                        int8_t q[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) q[e] = quant_code(t[e], p.q_out);
+                        if (vec) {
+                            const unsigned w = (unsigned)(uint8_t)q[0] | ((unsigned)(uint8_t)q[1] << 8) |
+                                               ((unsigned)(uint8_t)q[2] << 16) | ((unsigned)(uint8_t)q[3] << 24);
+                            *(unsigned*)((int8_t*)p.C + o) = w;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (gn + e < p.N) ((int8_t*)p.C)[o + e] = q[e];
+                        }
+                    } else if (vec) {
+                        f32x4 w = {t[0], t[1], t[2], t[3]};
+                        *(f32x4*)((float*)p.C + o) = w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gn + e < p.N) ((float*)p.C)[o + e] = t[e];
+                    }
+                }
+            }
+        }
+    }
+
     // ---- general path (ragged N, unaligned C): stores straight from registers
     template <bool OUT_F32> __device__ __forceinline__ void run_direct(bool bias_vec, int act) {
 #pragma unroll
@@ -362,7 +432,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     constexpr int FM = WTM / 32, FN = WTN / 32;
     constexpr int CH = MfmaOp<T>::kChunks;         // 16-byte pieces per lane per MFMA operand
     constexpr int KSUB = BK / (16 * CH);           // MFMA k-steps per k-tile
-    static_assert(CH == 1 || MODE == MODE_TRANS_B, "FP8 operands need both tiles k-major (trans_b)");
+    static_assert(sizeof(T) == 2 || MODE == MODE_TRANS_B, "8-bit operands need both tiles k-major (trans_b)");
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE = A_BYTES + B_BYTES;
     constexpr int A_BLKS = A_BYTES / 1024, B_BLKS = B_BYTES / 1024;     // 1 KiB per wave-load
@@ -734,7 +804,9 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     char* wlds = lds + wave * ((NSTAGE * STAGE) / NW);
     EpiCtx<TO, FM, FN, WTM, WTN, (NSTAGE * STAGE) / NW> ctx{p, acc, wlds, m0 + wm * WTM, n0 + wn * WTN, lane,
                                                          (int64_t)b * p.stride_c};
-    if (out_f32) {
+    if constexpr (sizeof(T) == 1 && MfmaOp<T>::kChunks == 1) {      // int8 operands
+        ctx.run_quant();
+    } else if (out_f32) {
         if (act == 0) ctx.template run<0, true>(); else if (act == 1) ctx.template run<1, true>();
         else ctx.template run<2, true>();
     } else {

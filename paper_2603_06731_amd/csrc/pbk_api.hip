@@ -13,11 +13,11 @@ namespace {
 thread_local const char* g_last_kernel = "";
 
 int64_t elem_size(int dt) {
-    return dt == pbk::DT_F32 ? 4 : (dt == pbk::DT_BF16 || dt == pbk::DT_F16) ? 2 : 1;
+    return dt == pbk::DT_F32 ? 4 : (dt == pbk::DT_BF16 || dt == pbk::DT_F16) ? 2 : 1;   // FP8 and int8: 1
 }
 
 bool is_fp8(int dt) { return dt == PBK_FP8_E4M3 || dt == PBK_FP8_E5M2; }
-bool valid_in_dtype(int dt) { return dt >= PBK_F32 && dt <= PBK_FP8_E5M2; }
+bool valid_in_dtype(int dt) { return dt >= PBK_F32 && dt <= PBK_FP8_E5M2; }   // int8 has its own entry points
 bool valid_out_dtype(int dt) { return dt == PBK_F32 || dt == PBK_BF16 || dt == PBK_F16; }
 
 bool aligned(const void* p, int64_t a) { return (reinterpret_cast<uintptr_t>(p) % (uintptr_t)a) == 0; }
@@ -62,6 +62,26 @@ pbk_status dispatch(const pbk::Problem& p, void* stream) {
     return PBK_OK;
 }
 
+// Quantised epilogue parameters of the int8 entry points.
+pbk_status check_quant(const float* scale, const float* bias, float mid_scale, const float* mul,
+                       const float* add, float out_scale, int out_dtype) {
+    if (out_dtype != PBK_INT8 && out_dtype != PBK_F32) return PBK_ERR_DTYPE;
+    if (!scale) return PBK_ERR_EPILOGUE;
+    if (!(mid_scale >= 0.0f) || (out_dtype == PBK_INT8 && !(out_scale > 0.0f))) return PBK_ERR_EPILOGUE;
+    if (!aligned(scale, 4) || (bias && !aligned(bias, 4)) || (mul && !aligned(mul, 4)) || (add && !aligned(add, 4)))
+        return PBK_ERR_ALIGN;
+    return PBK_OK;
+}
+
+void set_quant(pbk::Problem& p, const float* scale, const float* bias, float mid_scale, const float* mul,
+               const float* add, int relu, float out_scale) {
+    p.in_dtype = pbk::DT_INT8;
+    p.bias = bias;
+    p.q_scale = scale; p.q_mul = mul; p.q_add = add;
+    p.q_mid = mid_scale; p.q_out = out_scale; p.q_relu = relu ? 1 : 0;
+    p.epi = pbk::EPI_NONE; p.alpha = 1.0f;
+}
+
 // Shared tail of the convolution entry points.  pad_h / pad_w are the near-side (top, left)
 // paddings; OH / OW the output size the caller derived (negative = empty or invalid).
 pbk_status conv_common(const void* x, const void* w, void* y, const float* bias,
@@ -69,9 +89,13 @@ pbk_status conv_common(const void* x, const void* w, void* y, const float* bias,
                        int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                        int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                        int64_t OH, int64_t OW, int transposed,
-                       int in_dtype, int out_dtype, float alpha, int epi, void* stream) {
-    pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
-    if (s != PBK_OK) return s;
+                       int in_dtype, int out_dtype, float alpha, int epi, void* stream,
+                       const float* q_scale = nullptr, const float* q_mul = nullptr, const float* q_add = nullptr,
+                       float q_mid = 0.0f, float q_out = 0.0f, int q_relu = 0) {
+    if (in_dtype != PBK_INT8) {          // the int8 entry point has validated its own parameters
+        pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
+        if (s != PBK_OK) return s;
+    }
     if (N < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 1 || KH < 1 || KW < 1) return PBK_ERR_SHAPE;
     if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
         return PBK_ERR_SHAPE;
@@ -104,6 +128,7 @@ pbk_status conv_common(const void* x, const void* w, void* y, const float* bias,
     p.conv.pad_h = (int)pad_h; p.conv.pad_w = (int)pad_w;
     p.conv.dil_h = (int)dil_h; p.conv.dil_w = (int)dil_w;
     p.conv.transposed = transposed;
+    if (in_dtype == PBK_INT8) set_quant(p, q_scale, bias, q_mid, q_mul, q_add, q_relu, q_out);
     return dispatch(p, stream);
 }
 
@@ -204,6 +229,52 @@ pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, cons
     }
     return conv_common(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w,
                        dil_h, dil_w, OH, OW, 1, in_dtype, out_dtype, alpha, epi, stream);
+}
+
+pbk_status pbk_matmul_int8(const int8_t* A, const int8_t* B, void* C,
+                           int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int trans_b,
+                           const float* scale, const float* bias, float mid_scale,
+                           const float* mul, const float* add, int relu, float out_scale,
+                           pbk_dtype out_dtype, void* stream) {
+    pbk_status s = check_quant(scale, bias, mid_scale, mul, add, out_scale, out_dtype);
+    if (s != PBK_OK) return s;
+    if (M < 0 || N < 0 || K < 0 || M > INT_MAX || N > INT_MAX) return PBK_ERR_SHAPE;
+    if (K > 131071) return PBK_ERR_UNSUPPORTED;       // the sum of K products must fit 32 bits
+    if (M == 0 || N == 0) return PBK_OK;
+    if (!C || (K > 0 && (!A || !B))) return PBK_ERR_NULL;
+    if (lda < K || ldc < N || ldb < (trans_b ? K : N)) return PBK_ERR_STRIDE;
+    if (!aligned(C, elem_size(out_dtype))) return PBK_ERR_ALIGN;
+    pbk::Problem p{};
+    p.A = A; p.B = B; p.C = C;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K; p.batch = 1;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.out_dtype = out_dtype;
+    p.trans_b = trans_b ? 1 : 0;
+    set_quant(p, scale, bias, mid_scale, mul, add, relu, out_scale);
+    return dispatch(p, stream);
+}
+
+pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
+                                int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                const float* scale, const float* bias, float mid_scale,
+                                const float* mul, const float* add, int relu, float out_scale,
+                                pbk_dtype out_dtype, void* stream) {
+    pbk_status s = check_quant(scale, bias, mid_scale, mul, add, out_scale, out_dtype);
+    if (s != PBK_OK) return s;
+    if (KH >= 1 && KW >= 1 && Cin >= 1 && KH <= 4096 && KW <= 4096 && Cin <= (1 << 24) && KH * KW * Cin > 131071)
+        return PBK_ERR_UNSUPPORTED;
+    int64_t OH = -1, OW = -1;
+    if (H >= 1 && W >= 1 && KH >= 1 && KW >= 1 && stride_h >= 1 && stride_w >= 1 && pad_h >= 0 && pad_w >= 0 &&
+        dil_h >= 1 && dil_w >= 1 && H <= (1 << 24) && W <= (1 << 24) && pad_h <= (1 << 24) && pad_w <= (1 << 24) &&
+        KH <= 4096 && KW <= 4096 && dil_h <= 4096 && dil_w <= 4096) {
+        const int64_t span_h = H + 2 * pad_h - dil_h * (KH - 1) - 1, span_w = W + 2 * pad_w - dil_w * (KW - 1) - 1;
+        if (span_h >= 0 && span_w >= 0) { OH = span_h / stride_h + 1; OW = span_w / stride_w + 1; }
+    }
+    return conv_common(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                       OH, OW, 0, PBK_INT8, out_dtype, 1.0f, PBK_EPI_NONE, stream, scale, mul, add, mid_scale,
+                       out_scale, relu);
 }
 
 pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,

@@ -62,4 +62,42 @@ template <> __device__ __forceinline__ float widen<fp8_e4m3_t>(fp8_e4m3_t x) {
     return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, mag) | sign);
 }
 
+// ---- quantised epilogue of the int8 path (paper appendix on quantisation: de-quantise, bias,
+// optional quantise/de-quantise pair, folded batch-norm affine, ReLU, output quantisation).
+// Every step is a single binary32 operation in this order; contraction into fused
+// multiply-adds is switched off so that the integer codes come out bit-exact.
+__device__ __forceinline__ float quantise_step(float t, float step) {
+#pragma clang fp contract(off)
+    float q = __builtin_rintf(t / step);             // v_rndne_f32: nearest, ties to even
+    q = q < -128.0f ? -128.0f : q;
+    q = q > 127.0f ? 127.0f : q;
+    return q;
+}
+
+struct QuantParams {       // per-column values of one output element, plus the uniform ones
+    float scale, bias, mul, add;
+};
+
+__device__ __forceinline__ float quant_value(int acc, const QuantParams& c, bool has_bias, bool has_mul,
+                                             bool has_add, float mid, int relu) {
+#pragma clang fp contract(off)
+    float t = (float)acc;                             // v_cvt_f32_i32: round to nearest even
+    t = t * c.scale;
+    if (has_bias) t = t + c.bias;
+    if (mid > 0.0f) {
+        float q = quantise_step(t, mid);
+        t = q * mid;
+    }
+    if (has_mul) t = t * c.mul;
+    if (has_add) t = t + c.add;
+    if (relu) t = t > 0.0f ? t : 0.0f;
+    return t;
+}
+
+__device__ __forceinline__ int8_t quant_code(float t, float out_scale) {
+    return (int8_t)(int)quantise_step(t, out_scale);
+}
+
+template <> __device__ __forceinline__ float widen<int8_t>(int8_t v) { return (float)v; }
+
 }  // namespace pbk

@@ -5,7 +5,7 @@
 
 namespace pbk {
 
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_FP8_E4M3 = 3, DT_FP8_E5M2 = 4 };
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_FP8_E4M3 = 3, DT_FP8_E5M2 = 4, DT_INT8 = 5 };
 enum : int { EPI_NONE = 0, EPI_BIAS = 1, EPI_RELU = 2, EPI_BIAS_RELU = 3,
              EPI_BIAS_GELU_TANH = 4, EPI_GELU_TANH = 5 };
 
@@ -36,6 +36,15 @@ struct Problem {
     int epi;
     float alpha;
     ConvGeom conv;
+    // int8 operands (in_dtype DT_INT8): integer accumulation and the quantised epilogue
+    //   t = float(acc)*q_scale[n] (+ bias[n]); optional requantise/dequantise with q_mid;
+    //   t = t*q_mul[n] + q_add[n] (each if given); ReLU if q_relu;
+    //   out = int8(clamp(roundeven(t/q_out))) for out_dtype DT_INT8, else t as fp32.
+    const float* q_scale;
+    const float* q_mul;
+    const float* q_add;
+    float q_mid, q_out;
+    int q_relu;
 };
 
 // One attention layer call (paper Sec. 4.4): O = softmax(alpha Q K^T + bias) V

@@ -128,3 +128,19 @@ def test_conv_variant_argument_errors(pbk):
     assert t(oh=-1) == 2 and t(ph=-1) == 2 and t(sh=0) == 2
     assert t(H=1, W=1, KH=1, KW=1, sh=1, sw=1, ph=1, pw=1) == 2      # empty output
     assert t(N=0) == 0 and t(x=None) == 1
+
+
+def test_int8_argument_errors(pbk):
+    P = 0x1000
+    mm = pbk.pbk_matmul_int8
+
+    def call(A=P, B=P, C=P, M=4, N=4, K=16, lda=16, ldb=16, ldc=4, tb=1, scale=P, bias=None, mid=0.0, mul=None,
+             add=None, relu=0, out_scale=1.0, out=5):
+        return mm(A, B, C, M, N, K, lda, ldb, ldc, tb, scale, bias, mid, mul, add, relu, out_scale, out)
+    assert call(out=1) == 5 and call(out=2) == 5              # outputs are int8 or fp32
+    assert call(scale=None) == 6 and call(out_scale=0.0) == 6 and call(mid=-1.0) == 6
+    assert call(M=-1) == 2 and call(K=131072, lda=131072, ldb=131072) == 7
+    assert call(A=None) == 1 and call(C=None) == 1
+    assert call(lda=8) == 3 and call(ldc=3) == 3 and call(tb=0, ldb=3) == 3
+    assert call(scale=P + 2) == 4 and call(out=0, C=P + 2) == 4
+    assert call(M=0) == 0

@@ -1,0 +1,156 @@
+"""Parity of the int8 path (through the C ABI) with the CPU oracle: integer
+codes and fp32 outputs must be bit-exact."""
+import numpy as np
+import pytest
+
+import workloads as wl
+import pbk_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+INT8, F32 = 5, 0
+
+
+def params(n, variant, seed=0):
+    """Epilogue parameter sets: 0 scale only; 1 +bias, ReLU; 2 +mul; 3 everything incl. the
+    middle quantise/de-quantise pair (the paper's fused nest); 4 pair, no affine; 5 add only."""
+    r = np.random.default_rng(1000 + seed + variant)
+    scale = (r.uniform(0.5, 2.0, n) * 2e-4).astype(np.float32)
+    bias = r.normal(0, 0.5, n).astype(np.float32) if variant in (1, 3) else None
+    mid = {0: 0.0, 1: 0.0, 2: 0.0, 3: 0.031, 4: 0.07, 5: 0.0}[variant]
+    mul = r.uniform(0.5, 1.5, n).astype(np.float32) if variant in (2, 3) else None
+    add = r.normal(0, 0.3, n).astype(np.float32) if variant in (3, 5) else None
+    relu = variant in (1, 3)
+    return dict(scale=scale, bias=bias, mid_scale=mid, mul=mul, add=add, relu=relu, out_scale=0.043)
+
+
+def dev_or_none(a):
+    return None if a is None else T.to_device(a)
+
+
+def run_matmul(A, B, q, trans_b, out_int8, force=None, lda=None, ldb=None):
+    import torch
+    import paper_2603_06731_amd as pbk
+    m, k = A.shape
+    n = B.shape[0] if trans_b else B.shape[1]
+    dA = torch.from_numpy(A).cuda(); dB = torch.from_numpy(B).cuda()
+    out = torch.empty(m * n, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+    d = {k2: dev_or_none(v) if isinstance(v, np.ndarray) else v for k2, v in q.items()}
+    with T.forced_kernel(force):
+        st = pbk.pbk_matmul_int8(dA, dB, out, m, n, k, lda or k, ldb or B.shape[1], n, trans_b, d["scale"], d["bias"],
+                                 q["mid_scale"], d["mul"], d["add"], q["relu"], q["out_scale"],
+                                 INT8 if out_int8 else F32, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    return out.cpu().numpy().reshape(m, n), pbk.pbk_last_kernel()
+
+
+SHAPES = [(300, 264, 208), (256, 256, 64), (520, 136, 80), (33, 520, 144), (64, 8, 16), (130, 260, 4096)]
+
+
+@pytest.mark.parametrize("cfg", [None, 0, 1, 4, "generic"])
+@pytest.mark.parametrize("mnk", SHAPES)
+def test_matmul_int8_kmajor(cfg, mnk):
+    import oracle
+    m, n, k = mnk
+    A = wl.int8_tensor((m, k), 1); B = wl.int8_tensor((n, k), 2)
+    q = params(n, 3)
+    force = None if cfg is None else ("generic" if cfg == "generic" else f"mfma:{cfg}")
+    got, kern = run_matmul(A, B, q, 1, True, force)
+    want = oracle.matmul_int8(A, B, trans_b=1, **q)
+    print(f"int8 {mnk} force={force} kernel={kern} codes={len(np.unique(want))}", flush=True)
+    assert ("generic" in kern) == (cfg == "generic")
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("variant", range(6))
+@pytest.mark.parametrize("out_int8", [True, False])
+@pytest.mark.parametrize("force", [None, "generic"])
+def test_matmul_int8_epilogue_variants(variant, out_int8, force):
+    import oracle
+    m, n, k = 200, 264, 304
+    A = wl.int8_tensor((m, k), 1, "normal", 40.0); B = wl.int8_tensor((n, k), 2, "normal", 30.0)
+    q = params(n, variant)
+    got, kern = run_matmul(A, B, q, 1, out_int8, force)
+    want = oracle.matmul_int8(A, B, trans_b=1, out_int8=out_int8, **q)
+    assert got.dtype == want.dtype
+    assert np.array_equal(got.view(np.uint8 if out_int8 else np.uint32), want.view(np.uint8 if out_int8 else np.uint32)), kern
+
+
+def test_matmul_int8_row_major_b_runs_generic():
+    import oracle
+    m, n, k = 70, 50, 90
+    A = wl.int8_tensor((m, k), 1); B = wl.int8_tensor((k, n), 2)
+    q = params(n, 1)
+    got, kern = run_matmul(A, B, q, 0, True)
+    assert "generic" in kern
+    assert np.array_equal(got, oracle.matmul_int8(A, B, trans_b=0, **q))
+
+
+def test_matmul_int8_extreme_values_and_saturation():
+    import oracle
+    m, n, k = 128, 256, 8192
+    A = np.full((m, k), -128, np.int8); B = np.full((n, k), -128, np.int8)
+    B[::2] = 127
+    q = dict(scale=np.full(n, 1e-6, np.float32), bias=None, mid_scale=0.0, mul=None, add=None, relu=False, out_scale=0.5)
+    got, kern = run_matmul(A, B, q, 1, True)
+    want, acc = oracle.matmul_int8(A, B, trans_b=1, want_acc=True, **q)
+    assert acc.max() == k * 16384 and "mfma" in kern
+    assert np.array_equal(got, want) and got.max() == 127 and got.min() == -128
+    gotf, _ = run_matmul(A, B, q, 1, False)
+    assert np.array_equal(gotf, oracle.matmul_int8(A, B, trans_b=1, out_int8=False, **q))
+
+
+def test_matmul_int8_views():
+    """Leading dimensions larger than K: bytes outside the views must not matter."""
+    import oracle
+    m, n, k, ld = 140, 136, 96, 128
+    r = np.random.default_rng(3)
+    Ap = r.integers(-128, 128, size=(m, ld), dtype=np.int8); Bp = r.integers(-128, 128, size=(n, ld), dtype=np.int8)
+    q = params(n, 3)
+    import torch
+    import paper_2603_06731_amd as pbk
+    dA = torch.from_numpy(Ap).cuda(); dB = torch.from_numpy(Bp).cuda()
+    out = torch.empty(m * n, dtype=torch.int8, device="cuda")
+    d = {k2: dev_or_none(v) if isinstance(v, np.ndarray) else v for k2, v in q.items()}
+    st = pbk.pbk_matmul_int8(dA, dB, out, m, n, k, ld, ld, n, 1, d["scale"], d["bias"], q["mid_scale"], d["mul"],
+                             d["add"], q["relu"], q["out_scale"], INT8, None)
+    assert st == 0 and "mfma" in pbk.pbk_last_kernel()
+    want = oracle.matmul_int8(np.ascontiguousarray(Ap[:, :k]), np.ascontiguousarray(Bp[:, :k]), trans_b=1, **q)
+    assert np.array_equal(out.cpu().numpy().reshape(m, n), want)
+
+
+@pytest.mark.parametrize("geom", [((1, 1), (1, 1), (1, 1)), ((2, 2), (1, 1), (1, 1)), ((1, 2), (2, 0), (2, 1))])
+@pytest.mark.parametrize("out_int8", [True, False])
+def test_conv_int8(geom, out_int8):
+    import torch
+    import oracle
+    import paper_2603_06731_amd as pbk
+    stride, pad, dil = geom
+    n, H, W, Cin, Cout, KH, KW = 2, 14, 13, 16, 24, 3, 3
+    x = wl.int8_tensor((n, H, W, Cin), 1, "normal", 40.0); w = wl.int8_tensor((KH, KW, Cin, Cout), 2, "normal", 30.0)
+    q = params(Cout, 3)
+    want = oracle.conv2d_nhwc_int8(x, w, stride=stride, pad=pad, dil=dil, out_int8=out_int8, **q)
+    out = torch.empty(want.size, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+    d = {k2: dev_or_none(v) if isinstance(v, np.ndarray) else v for k2, v in q.items()}
+    st = pbk.pbk_conv2d_nhwc_int8(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), out, n, H, W, Cin, Cout,
+                                  KH, KW, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], d["scale"], d["bias"],
+                                  q["mid_scale"], d["mul"], d["add"], q["relu"], q["out_scale"],
+                                  INT8 if out_int8 else F32, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    got = out.cpu().numpy().reshape(want.shape)
+    assert np.array_equal(got, want)
+
+
+def test_matmul_int8_full_size_sampled_rows():
+    """8192^3 in the bench's configuration; whole rows of the output against the oracle."""
+    import oracle
+    m = n = k = 8192
+    A = wl.int8_tensor((m, k), 1, "normal", 40.0); B = wl.int8_tensor((n, k), 2, "normal", 30.0)
+    q = params(n, 3)
+    q["scale"] = (q["scale"] * 0.05).astype(np.float32)
+    got, kern = run_matmul(A, B, q, 1, True)
+    rows = np.array([0, 1, 127, 128, 4095, 4096, 8191, 777, 2301, 6000])
+    want = oracle.matmul_int8(np.ascontiguousarray(A[rows]), B, trans_b=1, **q)
+    print(f"int8 8192^3 kernel={kern} codes={len(np.unique(want))}", flush=True)
+    assert "mfma_256x256x64" in kern
+    assert np.array_equal(got[rows], want) and len(np.unique(want)) > 50

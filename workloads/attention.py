@@ -77,3 +77,39 @@ def make_attention_inputs(w: AttentionWorkload) -> dict:
     elif w.bias == "per_batch":
         bias = gen.tensor((w.batch, w.Nq, w.Nk), gen.DTYPE_F32, 3, w.dist_bias[0], w.dist_bias[1], w.seed)
     return {"q": q, "k": k, "v": v, "bias": bias}
+
+
+@dataclass(frozen=True)
+class Int8Workload:
+    """int8 matmul C = quant_epilogue(A . B^T), both operands k-major, int8 codes out."""
+    name: str
+    M: int
+    N: int
+    K: int
+    seed: int = gen.MASTER_SEED
+
+    @property
+    def flops(self) -> int:
+        return 2 * self.M * self.N * self.K
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        return self.M * self.K + self.N * self.K + self.M * self.N + 4 * 4 * self.N
+
+
+INT8_CONFIGS = {"int8_8192_nt": Int8Workload("int8_8192_nt", 8192, 8192, 8192)}
+
+
+def make_int8_inputs(w: Int8Workload) -> dict:
+    """Quantised activations / weights (rounded normals) and the per-channel epilogue
+    parameters of the paper's fused nest: de-quantisation scale, bias, the middle
+    quantise/de-quantise pair, folded batch-norm affine, ReLU, output step."""
+    a = gen.int8_tensor((w.M, w.K), 1, "normal", 40.0, w.seed)
+    b = gen.int8_tensor((w.N, w.K), 2, "normal", 30.0, w.seed)
+    u = gen.uniform_f64(w.seed, 5, 0, w.N, 0.5, 2.0)
+    scale = (u * (3.0 / (40.0 * 30.0 * math.sqrt(w.K)))).astype(np.float32)
+    bias = gen.tensor((w.N,), gen.DTYPE_F32, 3, "normal", 0.5, w.seed)
+    mul = gen.uniform_f64(w.seed, 6, 0, w.N, 0.5, 1.5).astype(np.float32)
+    add = gen.tensor((w.N,), gen.DTYPE_F32, 7, "normal", 0.3, w.seed)
+    return {"a": a, "b": b, "scale": scale, "bias": bias, "mid_scale": 0.05, "mul": mul, "add": add,
+            "relu": True, "out_scale": 0.06}

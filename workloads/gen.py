@@ -146,3 +146,22 @@ def tensor(shape, dtype: int, tensor_id: int, dist: str, scale: float = 1.0,
             raise ValueError(dist)
         out[s:s + c] = to_storage(v, dtype)
     return out.reshape(shape)
+
+
+def int8_tensor(shape, tensor_id: int, dist: str = "uniform", scale: float = 127.0,
+                seed: int = MASTER_SEED) -> np.ndarray:
+    """int8 codes: "uniform" draws every code in [-128, 127] equally often;
+    "normal" rounds N(0, scale^2) to the nearest integer and saturates (the
+    bell shape of quantised activations and weights)."""
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.int8)
+    for s in range(0, n, _CHUNK):
+        c = min(_CHUNK, n - s)
+        if dist == "uniform":
+            v = np.floor(uniform_f64(seed, tensor_id, s, c, -128.0, 128.0))
+        elif dist == "normal":
+            v = np.rint(normal_f64(seed, tensor_id, s, c, scale))
+        else:
+            raise ValueError(dist)
+        out[s:s + c] = np.clip(v, -128, 127).astype(np.int8)
+    return out.reshape(shape)
