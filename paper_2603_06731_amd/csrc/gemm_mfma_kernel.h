@@ -334,11 +334,20 @@ struct EpiCtx {
         const int esz = out_i8 ? 1 : 4;
         const bool vec = (p.N % 4 == 0) && (p.ldc % 4 == 0) &&
                          (((uintptr_t)p.C + (uintptr_t)c_batch * esz) % (4 * esz) == 0);
+        // int8 codes of the whole wave tile pass through the wave's LDS slice once, so that the
+        // global stores are 16 bytes per lane along rows (needs whole aligned 16-byte chunks of C)
+        constexpr int ROW_BYTES = WTN;
+        constexpr int CPR = ROW_BYTES / 16;
+        constexpr int RP = ROW_BYTES >= 256 ? 1 : 256 / ROW_BYTES;
+        constexpr bool CAN_STAGE = WTM * WTN <= LDS_PER_WAVE && 64 % CPR == 0;
+        const bool staged = CAN_STAGE && out_i8 && (p.N % 16 == 0) && (p.ldc % 16 == 0) &&
+                            (((uintptr_t)p.C + (uintptr_t)c_batch) % 16 == 0);
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int gn = col0 + j * 32 + g * 8 + ((lane >> 5) << 2);
+                const int lcol = j * 32 + g * 8 + ((lane >> 5) << 2);
+                const int gn = col0 + lcol;
                 QuantParams c[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -350,8 +359,9 @@ struct EpiCtx {
                 }
 #pragma unroll
                 for (int i = 0; i < FM; ++i) {
-                    const int gm = row0 + i * 32 + (lane & 31);
-                    if (gm >= p.M || gn >= p.N) continue;
+                    const int lrow = i * 32 + (lane & 31);
+                    const int gm = row0 + lrow;
+                    if (!staged && (gm >= p.M || gn >= p.N)) continue;
                     const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
                     float t[4];
 #pragma unroll
@@ -362,9 +372,12 @@ struct EpiCtx {
                         int8_t q[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) q[e] = quant_code(t[e], p.q_out);
-                        if (vec) {
-                            const unsigned w = (unsigned)(uint8_t)q[0] | ((unsigned)(uint8_t)q[1] << 8) |
-                                               ((unsigned)(uint8_t)q[2] << 16) | ((unsigned)(uint8_t)q[3] << 24);
+                        const unsigned w = (unsigned)(uint8_t)q[0] | ((unsigned)(uint8_t)q[1] << 8) |
+                                           ((unsigned)(uint8_t)q[2] << 16) | ((unsigned)(uint8_t)q[3] << 24);
+                        if (staged) {
+                            const int sw = (lrow / RP) % CPR;
+                            *(unsigned*)(wlds + lrow * ROW_BYTES + ((((lcol >> 4) ^ sw)) << 4) + (lcol & 15)) = w;
+                        } else if (vec) {
                             *(unsigned*)((int8_t*)p.C + o) = w;
                         } else {
 #pragma unroll
@@ -379,6 +392,23 @@ struct EpiCtx {
                         for (int e = 0; e < 4; ++e)
                             if (gn + e < p.N) ((float*)p.C)[o + e] = t[e];
                     }
+                }
+            }
+        }
+        if constexpr (CAN_STAGE) {
+            if (staged) {
+                constexpr int ROWS_PER_LD = 64 / CPR;
+                constexpr int NLD = WTM / ROWS_PER_LD;
+                const int ld_row = lane / CPR, ld_chunk = lane % CPR;
+                const int gn = col0 + ld_chunk * 16;
+                const int rows_left = (p.M - row0 < WTM ? p.M - row0 : WTM);
+#pragma unroll
+                for (int q = 0; q < NLD; ++q) {
+                    const int lrow = q * ROWS_PER_LD + ld_row;
+                    const int sw = (lrow / RP) % CPR;
+                    const int4v w = *(const int4v*)(wlds + lrow * ROW_BYTES + ((ld_chunk ^ sw) << 4));
+                    if (lrow < rows_left && gn < p.N)
+                        *(int4v*)((int8_t*)p.C + c_batch + (int64_t)(row0 + lrow) * p.ldc + gn) = w;
                 }
             }
         }
