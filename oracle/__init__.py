@@ -58,6 +58,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_conv_transpose_out_dim.restype = i64
         L.oracle_matmul_int8.argtypes = ([vp, vp, vp, vp] + [i64] * 6 + [i32, vp, vp, f32, vp, vp, i32, f32, i32])
         L.oracle_conv2d_nhwc_int8.argtypes = ([vp, vp, vp, vp] + [i64] * 13 + [vp, vp, f32, vp, vp, i32, f32, i32])
+        L.oracle_matmul_residual.argtypes = [vp, vp, vp, vp, vp, vp] + [i64] * 7 + [i32, i32, i32, f32, f32, i32]
+        L.oracle_conv2d_nhwc_residual.argtypes = [vp, vp, vp, vp, vp, vp] + [i64] * 13 + [i32, i32, f32, f32, i32]
         L.oracle_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32]
         L.oracle_attention_rows.argtypes = [vp, vp, vp, vp, vp] + [i64] * 12 + [i32, f32, i64, vp, vp]
         L.oracle_conv_out_dim.argtypes = [i64] * 5
@@ -290,6 +292,41 @@ def conv2d_transpose_nhwc_at(x, w, bias, sn, soh, sow, sco, *, dtype, stride=(1,
                                                *[_ptr(a) for a in idx])
     _rc(rc, "conv2d_transpose_nhwc_at")
     return out, pre
+
+
+def matmul_residual(A, B, bias, R, *, dtype, r_dtype, trans_b=0, alpha=1.0, beta=1.0, epi=EPI_NONE,
+                    want_preact=False):
+    """act(alpha*A.B + bias + beta*R) as float64 [M][N]."""
+    A = _check_in(np.ascontiguousarray(A), dtype); B = _check_in(np.ascontiguousarray(B), dtype)
+    R = _check_in(np.ascontiguousarray(R), r_dtype); bias = _check_bias(bias)
+    M, K = A.shape
+    N = B.shape[0] if trans_b else B.shape[1]
+    if R.shape != (M, N):
+        raise ValueError("R must have the output's shape")
+    out = np.empty((M, N), dtype=np.float64)
+    pre = np.empty_like(out) if want_preact else None
+    rc = lib().oracle_matmul_residual(_ptr(A), _ptr(B), _ptr(bias), _ptr(R), _ptr(out), _ptr(pre), M, N, K,
+                                      K, B.shape[1], N, N, dtype, r_dtype, int(trans_b), float(alpha), float(beta), epi)
+    _rc(rc, "matmul_residual")
+    return (out, pre) if want_preact else out
+
+
+def conv2d_nhwc_residual(x, w, bias, r, *, dtype, r_dtype, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0,
+                         beta=1.0, epi=EPI_NONE, want_preact=False):
+    x = _check_in(np.ascontiguousarray(x), dtype); w = _check_in(np.ascontiguousarray(w), dtype)
+    r = _check_in(np.ascontiguousarray(r), r_dtype); bias = _check_bias(bias)
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    OH = conv_out_dim(H, KH, stride[0], pad[0], dil[0]); OW = conv_out_dim(W, KW, stride[1], pad[1], dil[1])
+    if r.shape != (N, OH, OW, Cout):
+        raise ValueError("r must have the output's shape")
+    out = np.empty((N, OH, OW, Cout), dtype=np.float64)
+    pre = np.empty_like(out) if want_preact else None
+    rc = lib().oracle_conv2d_nhwc_residual(_ptr(x), _ptr(w), _ptr(bias), _ptr(r), _ptr(out), _ptr(pre), N, H, W, Cin,
+                                           Cout, KH, KW, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1],
+                                           dtype, r_dtype, float(alpha), float(beta), epi)
+    _rc(rc, "conv2d_nhwc_residual")
+    return (out, pre) if want_preact else out
 
 
 def _f32vec(v, n, name):

@@ -643,6 +643,70 @@ int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t
     return 0;
 }
 
+/* ---- residual-add epilogue ------------------------------------------------ */
+
+/* out = act(alpha * (A . B) + bias + beta * R): the shortcut branch of a
+ * residual block summed into the contraction's output tile (paper Sec. 4.3:
+ * pointwise consumers of the tile, here a binary one, fused into it).
+ * R has the output's shape (row stride ldr) and element type r_dtype. */
+int oracle_matmul_residual(const void* A, const void* B, const float* bias,
+                           const void* R, double* out, double* preact,
+                           int64_t M, int64_t N, int64_t K,
+                           int64_t lda, int64_t ldb, int64_t ldo, int64_t ldr,
+                           int dtype, int r_dtype, int trans_b, float alpha, float beta, int epi)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (r_dtype != ORACLE_F32 && r_dtype != ORACLE_BF16 && r_dtype != ORACLE_F16) return -1;
+    if (M < 0 || N < 0 || K < 0) return -4;
+    if (lda < K || ldo < N || ldr < N || ldb < (trans_b ? K : N)) return -5;
+    if (!out || !R || ((!A || !B) && K > 0 && M > 0 && N > 0)) return -6;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double s = dot_ik_kj(A, B, dtype, trans_b, 0, 0, lda, ldb, i, j, K);
+            double t = preactivation(s, epi_has_bias(epi) ? (double)bias[j] : 0.0, alpha, epi)
+                       + (double)beta * load(R, r_dtype, i * ldr + j);
+            if (preact) preact[i * ldo + j] = t;
+            out[i * ldo + j] = activation(t, epi);
+        }
+    }
+    return 0;
+}
+
+/* Same for the convolution; r is [N][OH][OW][Cout] like the output. */
+int oracle_conv2d_nhwc_residual(const void* x, const void* w, const float* bias,
+                                const void* r, double* out, double* preact,
+                                int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                int dtype, int r_dtype, float alpha, float beta, int epi)
+{
+    int rc = check_common(dtype, epi, bias);
+    if (rc) return rc;
+    if (r_dtype != ORACLE_F32 && r_dtype != ORACLE_BF16 && r_dtype != ORACLE_F16) return -1;
+    if (N < 0 || Cin < 1 || Cout < 1) return -4;
+    int64_t OH = oracle_conv_out_dim(H, KH, stride_h, pad_h, dil_h);
+    int64_t OW = oracle_conv_out_dim(W, KW, stride_w, pad_w, dil_w);
+    if (OH < 0 || OW < 0) return -5;
+    if (!x || !w || !out || !r) return -6;
+    for (int64_t n = 0; n < N; ++n) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int64_t oh = 0; oh < OH; ++oh)
+            for (int64_t ow = 0; ow < OW; ++ow)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    double s = conv_point(x, w, dtype, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
+                                          pad_h, pad_w, dil_h, dil_w, n, oh, ow, co);
+                    int64_t o = ((n * OH + oh) * OW + ow) * Cout + co;
+                    double t = preactivation(s, epi_has_bias(epi) ? (double)bias[co] : 0.0, alpha, epi)
+                               + (double)beta * load(r, r_dtype, o);
+                    if (preact) preact[o] = t;
+                    out[o] = activation(t, epi);
+                }
+    }
+    return 0;
+}
+
 /* ---- attention ---------------------------------------------------------- */
 
 /* One output row (b, i) of  softmax(alpha * Q K^T + bias) V,  by the definition:

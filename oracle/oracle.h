@@ -157,6 +157,21 @@ int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t
                             const float* mul, const float* add, int relu, float out_scale,
                             int out_int8);
 
+/* Residual-add epilogue: out = act(alpha * (A . B) + bias + beta * R), R of the
+ * output's shape (row stride ldr), element type r_dtype (F32, BF16, F16),
+ * widened exactly.  The convolution variant takes r [N][OH][OW][Cout]. */
+int oracle_matmul_residual(const void* A, const void* B, const float* bias,
+                           const void* R, double* out, double* preact,
+                           int64_t M, int64_t N, int64_t K,
+                           int64_t lda, int64_t ldb, int64_t ldo, int64_t ldr,
+                           int dtype, int r_dtype, int trans_b, float alpha, float beta, int epi);
+int oracle_conv2d_nhwc_residual(const void* x, const void* w, const float* bias,
+                                const void* r, double* out, double* preact,
+                                int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                int dtype, int r_dtype, float alpha, float beta, int epi);
+
 /* Attention layer (paper Sec. 4.4; the operator of its attention example):
  *   out[b][i][d] = sum_j P[b][i][j] * V[b][j][d],
  *   P[b][i][:]   = softmax_j( alpha * sum_c Q[b][i][c]*K[b][j][c] + bias[b][i][j] ).
