@@ -152,6 +152,26 @@ pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, cons
                                      float alpha, pbk_epilogue epi, void* stream);
 
 /*
+ * Residual-add epilogue: C = act(alpha * A . B + bias + beta * R), the shortcut
+ * branch of a residual block summed into the output tile before the activation
+ * (paper Sec. 4.3: pointwise consumers fused into the tile).  R is M x N (row
+ * stride ldr >= N) resp. [N][OH][OW][Cout], of type out_dtype, may alias nothing
+ * that is written.  Everything else as pbk_matmul / pbk_conv2d_nhwc.
+ */
+pbk_status pbk_matmul_residual(const void* A, const void* B, void* C, const float* bias, const void* R,
+                               int64_t M, int64_t N, int64_t K,
+                               int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr,
+                               pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
+                               float alpha, float beta, pbk_epilogue epi, void* stream);
+
+pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const float* bias, const void* r,
+                                    int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                    int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                    int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                    pbk_dtype in_dtype, pbk_dtype out_dtype,
+                                    float alpha, float beta, pbk_epilogue epi, void* stream);
+
+/*
  * int8 x int8 contraction with exact 32-bit integer accumulation and the quantised
  * epilogue of the paper's appendix on quantisation (the fused de-quantisation /
  * quantisation nest at the output of a quantised convolution), computed in

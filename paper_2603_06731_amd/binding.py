@@ -16,6 +16,7 @@ PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2, PBK_INT8 = 0, 1, 2, 3, 4
 
 EXPORTED_SYMBOLS = ("pbk_matmul", "pbk_batched_matmul", "pbk_conv2d_nhwc", "pbk_conv2d_nhwc_pad4",
                     "pbk_conv2d_transpose_nhwc", "pbk_attention", "pbk_matmul_int8", "pbk_conv2d_nhwc_int8",
+                    "pbk_matmul_residual", "pbk_conv2d_nhwc_residual",
                     "pbk_status_string", "pbk_version", "pbk_last_kernel")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -64,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.pbk_matmul_int8.restype = i32
         L.pbk_conv2d_nhwc_int8.argtypes = [vp, vp, vp] + [i64] * 13 + [vp, vp, f32, vp, vp, i32, f32, i32, vp]
         L.pbk_conv2d_nhwc_int8.restype = i32
+        L.pbk_matmul_residual.argtypes = [vp, vp, vp, vp, vp] + [i64] * 7 + [i32, i32, i32, f32, f32, i32, vp]
+        L.pbk_matmul_residual.restype = i32
+        L.pbk_conv2d_nhwc_residual.argtypes = [vp, vp, vp, vp, vp] + [i64] * 13 + [i32, i32, f32, f32, i32, vp]
+        L.pbk_conv2d_nhwc_residual.restype = i32
         L.pbk_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32, vp]
         L.pbk_attention.restype = i32
         L.pbk_status_string.argtypes = [i32]
@@ -141,6 +146,19 @@ def pbk_conv2d_nhwc_int8(x, w, y, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w
     return lib().pbk_conv2d_nhwc_int8(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
                                       pad_h, pad_w, dil_h, dil_w, _ptr(scale), _ptr(bias), float(mid_scale),
                                       _ptr(mul), _ptr(add), int(relu), float(out_scale), out_dtype, _stream(stream))
+
+
+def pbk_matmul_residual(A, B, C, bias, R, M, N, K, lda, ldb, ldc, ldr, in_dtype, out_dtype, trans_b,
+                        alpha, beta, epi, stream=None) -> int:
+    return lib().pbk_matmul_residual(_ptr(A), _ptr(B), _ptr(C), _ptr(bias), _ptr(R), M, N, K, lda, ldb, ldc, ldr,
+                                     in_dtype, out_dtype, int(trans_b), float(alpha), float(beta), epi, _stream(stream))
+
+
+def pbk_conv2d_nhwc_residual(x, w, y, bias, r, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
+                             pad_h, pad_w, dil_h, dil_w, in_dtype, out_dtype, alpha, beta, epi, stream=None) -> int:
+    return lib().pbk_conv2d_nhwc_residual(_ptr(x), _ptr(w), _ptr(y), _ptr(bias), _ptr(r), N, H, W, Cin, Cout,
+                                          KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                                          in_dtype, out_dtype, float(alpha), float(beta), epi, _stream(stream))
 
 
 def pbk_attention(Q, K, V, bias, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo,

@@ -140,7 +140,13 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
                 continue;
             }
             float bias = has_bias ? p.bias[gn] : 0.0f;
-            float v = apply_epilogue((float)acc[i][j], p.alpha, bias, p.epi);
+            float res = 0.0f;
+            if (p.R) {
+                const int64_t ro = (int64_t)b * p.stride_c + (int64_t)gm * p.ldr + gn;
+                res = p.out_dtype == DT_F32 ? ((const float*)p.R)[ro]
+                    : p.out_dtype == DT_BF16 ? (float)((const bf16_t*)p.R)[ro] : (float)((const f16_t*)p.R)[ro];
+            }
+            float v = apply_epilogue((float)acc[i][j], p.alpha, bias, p.epi, p.beta, res);
             if (p.out_dtype == DT_F32) ((float*)p.C)[o] = v;
             else if (p.out_dtype == DT_BF16) ((uint16_t*)p.C)[o] = to_bits16<bf16_t>(v);
             else ((uint16_t*)p.C)[o] = to_bits16<f16_t>(v);

@@ -213,11 +213,36 @@ struct EpiCtx {
     int lane;
     int64_t c_batch;
 
-    template <int ACT> __device__ __forceinline__ float act_of(float acc_v, float bias_v) const {
+    template <int ACT> __device__ __forceinline__ float act_of(float acc_v, float bias_v, float res_v = 0.0f) const {
         float t = fmaf(p.alpha, acc_v, bias_v);
+        t = fmaf(p.beta, res_v, t);            // beta is 0 when there is no residual operand
         if (ACT == 1) t = fmaxf(t, 0.0f);
         if (ACT == 2) t = gelu_tanh_f32(t);
         return t;
+    }
+
+    // residual values R[gm][gn..gn+3] widened to float (zero where there is no residual operand);
+    // vec: whole aligned 4-element pieces may be loaded at once
+    template <bool OUT_F32> __device__ __forceinline__ void res4(int gm, int gn, bool vec, float (&rv)[4]) const {
+        rv[0] = rv[1] = rv[2] = rv[3] = 0.0f;
+        if (!p.R || gm >= p.M || gn >= p.N) return;
+        const int64_t o = c_batch + (int64_t)gm * p.ldr + gn;
+        if (OUT_F32) {
+            if (vec) { f32x4 q = *(const f32x4*)((const float*)p.R + o); rv[0] = q[0]; rv[1] = q[1]; rv[2] = q[2]; rv[3] = q[3]; }
+            else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) if (gn + e < p.N) rv[e] = ((const float*)p.R)[o + e];
+            }
+        } else {
+            T h[4] = {(T)0.0f, (T)0.0f, (T)0.0f, (T)0.0f};
+            if (vec) { int2v q = *(const int2v*)((const uint16_t*)p.R + o); __builtin_memcpy(h, &q, 8); }
+            else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) if (gn + e < p.N) h[e] = ((const T*)p.R)[o + e];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) rv[e] = (float)h[e];
+        }
     }
 
     // bias for columns gn..gn+3 (zero where there is none)
@@ -258,6 +283,8 @@ struct EpiCtx {
         constexpr int ROWS_PER_LD = 64 / CPR;               // rows covered by one wave-wide 16-byte read
         static_assert((32 % ROWS_PER_LD) == 0, "reads must tile a 32-row block");
         const int ld_row = lane / CPR, ld_chunk = lane % CPR;
+        const bool res_vec = p.R && (p.ldr % 4 == 0) &&
+                             (((uintptr_t)p.R + (uintptr_t)c_batch * ESZ) % (4 * ESZ) == 0);
 
         // every bias value this lane needs, loaded once and together
         float bias_r[FN][4][4];
@@ -281,9 +308,10 @@ struct EpiCtx {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int lcol = j * 32 + g * 8 + ((lane >> 5) << 2);
-                        float v[4];
+                        float v[4], rv[4];
+                        res4<OUT_F32>(row0 + i * 32 + (lane & 31), col0 + lcol, res_vec, rv);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(acc[i][j][g * 4 + e], bias_r[j][g][e]);
+                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(acc[i][j][g * 4 + e], bias_r[j][g][e], rv[e]);
                         const int cbyte = lcol * ESZ;
                         char* dst = wlds + lrow * ROW_BYTES + ((((cbyte >> 4) ^ sw)) << 4) + (cbyte & 15);
                         if (OUT_F32) {
@@ -428,10 +456,13 @@ struct EpiCtx {
                     const int gm = row0 + i * 32 + (lane & 31);
                     if (gm >= p.M || gn >= p.N) continue;
                     const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
+                    float rv[4];
+                    res4<OUT_F32>(gm, gn, false, rv);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         if (gn + e >= p.N) break;
                         float v = fmaf(p.alpha, acc[i][j][g * 4 + e], bv[e]);
+                        v = fmaf(p.beta, rv[e], v);
                         if (act == 1) v = fmaxf(v, 0.0f);
                         else if (act == 2) v = gelu_tanh_f32(v);
                         if (OUT_F32) ((float*)p.C)[o + e] = v;

@@ -11,6 +11,10 @@
 namespace {
 
 thread_local const char* g_last_kernel = "";
+// residual operand of the call being assembled on this thread (set by the *_residual entry points)
+thread_local const void* g_residual = nullptr;
+thread_local int64_t g_ldr = 0;
+thread_local float g_beta = 0.0f;
 
 int64_t elem_size(int dt) {
     return dt == pbk::DT_F32 ? 4 : (dt == pbk::DT_BF16 || dt == pbk::DT_F16) ? 2 : 1;   // FP8 and int8: 1
@@ -43,7 +47,9 @@ pbk_status check_common(int in_dtype, int out_dtype, int epi, const float* bias)
     return PBK_OK;
 }
 
-pbk_status dispatch(const pbk::Problem& p, void* stream) {
+pbk_status dispatch(const pbk::Problem& p_in, void* stream) {
+    pbk::Problem p = p_in;
+    if (g_residual) { p.R = g_residual; p.ldr = g_ldr; p.beta = g_beta; }
     int cfg = -1;
     int force = forced_choice(&cfg);
     const char* name = "";
@@ -167,6 +173,21 @@ pbk_status pbk_batched_matmul(const void* A, const void* B, void* C, const float
     return dispatch(p, stream);
 }
 
+pbk_status pbk_matmul_residual(const void* A, const void* B, void* C, const float* bias, const void* R,
+                               int64_t M, int64_t N, int64_t K,
+                               int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr,
+                               pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
+                               float alpha, float beta, pbk_epilogue epi, void* stream) {
+    if (!R && M > 0 && N > 0) return PBK_ERR_NULL;
+    if (ldr < N) return PBK_ERR_STRIDE;
+    if (valid_out_dtype(out_dtype) && !aligned(R, elem_size(out_dtype))) return PBK_ERR_ALIGN;
+    g_residual = R; g_ldr = ldr; g_beta = beta;
+    pbk_status s = pbk_batched_matmul(A, B, C, bias, 1, M, N, K, lda, ldb, ldc, 0, 0, 0,
+                                      in_dtype, out_dtype, trans_b, alpha, epi, stream);
+    g_residual = nullptr;
+    return s;
+}
+
 pbk_status pbk_matmul(const void* A, const void* B, void* C, const float* bias,
                       int64_t M, int64_t N, int64_t K,
                       int64_t lda, int64_t ldb, int64_t ldc,
@@ -206,6 +227,21 @@ pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* b
                            float alpha, pbk_epilogue epi, void* stream) {
     return pbk_conv2d_nhwc_pad4(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
                                 pad_h, pad_h, pad_w, pad_w, dil_h, dil_w, in_dtype, out_dtype, alpha, epi, stream);
+}
+
+pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const float* bias, const void* r,
+                                    int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                    int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                    int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                    pbk_dtype in_dtype, pbk_dtype out_dtype,
+                                    float alpha, float beta, pbk_epilogue epi, void* stream) {
+    if (!r && N > 0) return PBK_ERR_NULL;
+    if (valid_out_dtype(out_dtype) && !aligned(r, elem_size(out_dtype))) return PBK_ERR_ALIGN;
+    g_residual = r; g_ldr = Cout; g_beta = beta;
+    pbk_status s = pbk_conv2d_nhwc(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w,
+                                   dil_h, dil_w, in_dtype, out_dtype, alpha, epi, stream);
+    g_residual = nullptr;
+    return s;
 }
 
 pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, const float* bias,

@@ -23,9 +23,11 @@ __device__ __forceinline__ float gelu_tanh_f32(float t) {
     return 0.5f * t * (1.0f + th);
 }
 
-// t = alpha*acc + bias ; act(t).  `bias` must be 0 when the epilogue has none.
-__device__ __forceinline__ float apply_epilogue(float acc, float alpha, float bias, int epi) {
+// t = alpha*acc + bias + beta*res ; act(t).  `bias` must be 0 when the epilogue has none.
+__device__ __forceinline__ float apply_epilogue(float acc, float alpha, float bias, int epi,
+                                                float beta = 0.0f, float res = 0.0f) {
     float t = fmaf(alpha, acc, bias);
+    t = fmaf(beta, res, t);             // residual operand; beta is 0 when there is none
     switch (epi) {
     case EPI_RELU:
     case EPI_BIAS_RELU:

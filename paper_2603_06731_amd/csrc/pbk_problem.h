@@ -36,6 +36,10 @@ struct Problem {
     int epi;
     float alpha;
     ConvGeom conv;
+    // residual-add epilogue: out = act(alpha*acc + bias + beta*R), R of out_dtype, M x N (ldr); nullptr = none
+    const void* R;
+    int64_t ldr;
+    float beta;
     // int8 operands (in_dtype DT_INT8): integer accumulation and the quantised epilogue
     //   t = float(acc)*q_scale[n] (+ bias[n]); optional requantise/dequantise with q_mid;
     //   t = t*q_mul[n] + q_add[n] (each if given); ReLU if q_relu;

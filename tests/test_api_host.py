@@ -144,3 +144,17 @@ def test_int8_argument_errors(pbk):
     assert call(lda=8) == 3 and call(ldc=3) == 3 and call(tb=0, ldb=3) == 3
     assert call(scale=P + 2) == 4 and call(out=0, C=P + 2) == 4
     assert call(M=0) == 0
+
+
+def test_residual_argument_errors(pbk):
+    F32 = 0
+    P = 0x1000
+    mr = pbk.pbk_matmul_residual
+    assert mr(P, P, P, None, None, 2, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 1.0, 0) == 1       # R missing
+    assert mr(P, P, P, None, P, 2, 2, 2, 2, 2, 2, 1, F32, F32, 0, 1.0, 1.0, 0) == 3          # ldr < N
+    assert mr(P, P, P, None, P + 2, 2, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 1.0, 0) == 4      # R misaligned
+    assert mr(P, P, P, None, P, 2, 2, 2, 1, 2, 2, 2, F32, F32, 0, 1.0, 1.0, 0) == 3          # lda < K (plain checks still run)
+    assert mr(P, P, P, None, P, 0, 2, 2, 2, 2, 2, 2, F32, F32, 0, 1.0, 1.0, 0) == 0
+    cr = pbk.pbk_conv2d_nhwc_residual
+    assert cr(P, P, P, None, None, 1, 4, 4, 2, 2, 3, 3, 1, 1, 1, 1, 1, 1, F32, F32, 1.0, 1.0, 0) == 1
+    assert cr(P, P, P, None, P, 1, 4, 4, 2, 2, 3, 3, 0, 1, 1, 1, 1, 1, F32, F32, 1.0, 1.0, 0) == 2
