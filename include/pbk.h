@@ -188,10 +188,11 @@ pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const
  * Results are bit-exact for a given input whatever kernel runs.  scale, bias, mul,
  * add are device float arrays of N entries.  K (KH*KW*Cin) must not exceed 131071
  * (PBK_ERR_UNSUPPORTED), which keeps every sum inside 32 bits.  A: M x K (lda);
- * B: K x N (ldb) or, if trans_b, N x K.  The matrix-unit kernel takes trans_b with
- * 16-byte aligned A, B and K, lda, ldb multiples of 16; other calls, and the
- * convolution (x NHWC, w HWIO, symmetric padding, OH/OW as pbk_conv2d_nhwc), run on
- * the generic kernel with integer accumulation.
+ * B: K x N (ldb) or, if trans_b, N x K.  Convolution: x NHWC, w HWIO, symmetric
+ * padding, OH/OW as pbk_conv2d_nhwc.  The matrix-unit kernel takes 16-byte aligned
+ * operands with K, lda, ldb (and N for row-major B; Cin and Cout for the
+ * convolution) multiples of 16; other calls run on the generic kernel with
+ * integer accumulation.
  */
 pbk_status pbk_matmul_int8(const int8_t* A, const int8_t* B, void* C,
                            int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int trans_b,

@@ -11,25 +11,25 @@ static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 // entirely inside or outside the matrix; likewise N for row-major B and Cin
 // for the convolution (a piece must not straddle two filter taps).
 bool mfma_supported(const Problem& p) {
-    // 8-bit operand types (FP8, int8) share the rules: 16 values per 16-byte piece, k-major operands
-    const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2 || p.in_dtype == DT_INT8;
-    if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16 && !fp8) return false;
-    const int per16 = fp8 ? 16 : 8;                  // elements per 16-byte piece
-    const int esz = fp8 ? 1 : 2;
-    if (fp8 && (p.is_conv || !p.trans_b)) return false;   // FP8 path: both operands k-major
+    // 8-bit operand types (FP8, int8): 16 values per 16-byte piece
+    const bool e8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2 || p.in_dtype == DT_INT8;
+    if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16 && !e8) return false;
+    const int per16 = e8 ? 16 : 8;                   // elements per 16-byte piece
+    const int esz = e8 ? 1 : 2;
     if (p.K < per16 || p.K % per16) return false;
     if (!al16(p.A) || !al16(p.B)) return false;
     if (p.stride_a % per16 || p.stride_b % per16) return false;
     // per-lane buffer offsets are 32-bit and must stay below 2^31
     const int64_t lim = (int64_t)1 << 31;
     if (p.is_conv) {
-        if (p.conv.Cin % 8 || p.N % 8) return false;
-        int64_t img = (int64_t)(p.M / (p.conv.OH * p.conv.OW)) * p.conv.H * p.conv.W * p.conv.Cin * 2;
-        int64_t halo = ((int64_t)p.conv.pad_h * p.conv.W + p.conv.pad_w + p.conv.W) * p.conv.Cin * 2;
+        if (e8 && p.conv.transposed) return false;   // the transposed form is built for 16-bit types
+        if (p.conv.Cin % per16 || p.N % per16) return false;
+        int64_t img = (int64_t)(p.M / (p.conv.OH * p.conv.OW)) * p.conv.H * p.conv.W * p.conv.Cin * esz;
+        int64_t halo = ((int64_t)p.conv.pad_h * p.conv.W + p.conv.pad_w + p.conv.W) * p.conv.Cin * esz;
         if (img + halo >= lim) return false;
     } else {
         if (p.lda % per16 || p.ldb % per16) return false;
-        if (!p.trans_b && p.N % 8) return false;
+        if (!p.trans_b && p.N % per16) return false;
         if (256 * p.lda * esz + 256 >= lim) return false;
     }
     if (256 * p.ldb * esz + 1024 >= lim) return false;

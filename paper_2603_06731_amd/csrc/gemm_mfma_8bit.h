@@ -1,0 +1,49 @@
+// Launch of the MFMA kernel for 8-bit operand types (FP8, int8).  The kernel takes every size
+// along k in 2-byte units (two values per unit): k-major tiles are then plain byte copies, and
+// the n-major B tile (row-major B, convolution weights) is read with the 8-bit transposing
+// LDS read.  Row strides of n-major operands stay byte counts (ldb * 2 units' worth).
+#pragma once
+#include "gemm_mfma_launch.h"
+
+namespace pbk {
+
+inline Problem to_k_units(const Problem& p) {
+    Problem q = p;
+    q.K = p.K / 2;
+    q.lda = p.lda / 2;
+    q.ldb = p.ldb / 2;          // k-major: units; n-major: the kernel multiplies by 2 again to get bytes
+    q.stride_a = p.stride_a / 2;
+    q.stride_b = p.stride_b / 2;
+    if (p.is_conv) q.conv.Cin = p.conv.Cin / 2;
+    return q;
+}
+
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC>
+hipError_t launch_8bit_modes(const Problem& q, hipStream_t stream, int group_m) {
+    if (q.is_conv) return launch_one<T, TO, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC>(q, stream, group_m);
+    if (q.trans_b) return launch_one<T, TO, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC>(q, stream, group_m);
+    return launch_one<T, TO, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC>(q, stream, group_m);
+}
+
+// The two tile configurations built for the FP8 types (a 64-unit k-tile = 128 values deep).
+template <typename T, typename TO>
+hipError_t launch_fp8_cfg(const Problem& q, hipStream_t stream, int cfg, int group_m) {
+    switch (cfg) {
+    case 1: return launch_8bit_modes<T, TO, 128, 128, 64, 2, 2, 2, 1>(q, stream, group_m);
+    case 4: return launch_8bit_modes<T, TO, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename T>
+hipError_t launch_fp8_type(const Problem& p, hipStream_t stream, int cfg, int group_m) {
+    const Problem q = to_k_units(p);
+    // an F32 output does not use the 16-bit output type at all
+    if (q.out_dtype == DT_F16) return launch_fp8_cfg<T, f16_t>(q, stream, cfg, group_m);
+    return launch_fp8_cfg<T, bf16_t>(q, stream, cfg, group_m);
+}
+
+hipError_t launch_mfma_fp8_e4m3(const Problem& p, hipStream_t stream, int cfg, int group_m);
+hipError_t launch_mfma_fp8_e5m2(const Problem& p, hipStream_t stream, int cfg, int group_m);
+
+}  // namespace pbk

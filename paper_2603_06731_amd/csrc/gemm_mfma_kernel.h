@@ -493,7 +493,10 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     constexpr int FM = WTM / 32, FN = WTN / 32;
     constexpr int CH = MfmaOp<T>::kChunks;         // 16-byte pieces per lane per MFMA operand
     constexpr int KSUB = BK / (16 * CH);           // MFMA k-steps per k-tile
-    static_assert(sizeof(T) == 2 || MODE == MODE_TRANS_B, "8-bit operands need both tiles k-major (trans_b)");
+    // 8-bit element types: sizes along k are in 2-byte units, a k-row of the n-major B tile is one
+    // k VALUE (so the tile has 2*BK rows of BN bytes) and is read with the 8-bit transposing LDS read
+    constexpr bool E8 = sizeof(T) == 1;
+    static_assert(!E8 || MODE != MODE_CONVT, "transposed convolution is built for 16-bit types only");
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE = A_BYTES + B_BYTES;
     constexpr int A_BLKS = A_BYTES / 1024, B_BLKS = B_BYTES / 1024;     // 1 KiB per wave-load
@@ -526,6 +529,9 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     constexpr int NM_CPR = BN / 8;
     constexpr int NM_ROWS = 64 / NM_CPR;
     const int nm_row = lane / NM_CPR, nm_slot = lane % NM_CPR;
+    // 8-bit n-major tile ([2 BK][BN] bytes): 1 KiB block = NM8_ROWS k-rows of BN/16 slots
+    constexpr int NM8_CPR = BN / 16;
+    constexpr int NM8_ROWS = 64 / NM8_CPR;
 
     const char* Abase = (const char*)p.A + (int64_t)b * p.stride_a * 2;
     const char* Bbase = (const char*)p.B + (int64_t)b * p.stride_b * 2;
@@ -575,6 +581,15 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             b_kofs[r] = chunk * 8;
             b_voff[r] = (n0 + row < p.N) ? (unsigned)(row * (int)p.ldb * 2 + chunk * 16) : kOob;
         } else {
+            if (E8) {
+                // 16-byte chunk index XOR-swizzled by the k-row (8 rows of one transposing read
+                // land in 8 different bank groups); b_kofs in 2-byte units like every k size
+                const int krow = blk * NM8_ROWS + lane / NM8_CPR;
+                const int chunk = (lane % NM8_CPR) ^ (krow & 7);
+                b_kofs[r] = krow >> 1;
+                b_voff[r] = (n0 + chunk * 16 < p.N) ? (unsigned)(krow * (int)p.ldb * 2 + chunk * 16) : kOob;
+                continue;
+            }
             int krow = blk * NM_ROWS + nm_row;
             int c64 = (nm_slot >> 2) ^ (krow & 3);
             int nbyte = (c64 << 6) | ((nm_slot & 3) << 4);
@@ -585,7 +600,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 
     // Descriptor bases: A at (m0, 0), B at (0, n0) resp. (n0, 0); advanced by k0 per k-tile.
     const char* a_tile = CONV ? Abase : Abase + (int64_t)m0 * p.lda * 2;
-    const char* b_tile = TRANS_B ? Bbase + (int64_t)n0 * p.ldb * 2 : Bbase + (int64_t)n0 * 2;
+    const char* b_tile = TRANS_B ? Bbase + (int64_t)n0 * p.ldb * 2 : Bbase + (int64_t)n0 * (E8 ? 1 : 2);
 
     const unsigned lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr_of(lds));
 
@@ -621,7 +636,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         } else {
             ld_ra = make_rsrc(a_tile + (int64_t)k0 * 2);
         }
-        ld_rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2 : b_tile + (int64_t)k0 * p.ldb * 2);
+        ld_rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2 : b_tile + (int64_t)k0 * p.ldb * (E8 ? 4 : 2));
     };
 
     // Issue load number r (0 .. LOADS-1) of the current tile: first this wave's
@@ -691,6 +706,11 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     // B via transposing read: 16-lane block -> 16 n; lane -> k row (lane%16)/4, n piece lane%4
     const int tr_k = ((lane & 15) >> 2) + ((lane >> 5) << 3);
     const int tr_nbyte = ((((lane >> 4) & 1) << 4) + ((lane & 3) << 2)) * 2;
+    // 8-bit transposing read (ds_read_b64_tr_b8): within a 16-lane block, lane i addresses 8 bytes of
+    // k-row i/2 at n-piece i%2 and receives, for n = i, the 8 consecutive k of the block's 8 rows
+    const int tr8_row = (lane & 15) >> 1;                                   // k-row within the 8 (= swizzle term)
+    const int tr8_n = (((lane >> 4) & 1) << 4) + ((lane & 1) << 3);         // n offset within the 32 of a fragment
+    const int tr8_half = lane >> 5;
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -717,6 +737,18 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 #pragma unroll
                 for (int c = 0; c < CH; ++c)
                     bf[j].c[c] = *(const short8v*)(sb + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
+            } else if (E8) {
+                // a lane's fragment: 16*CH consecutive k of column n = lane%32, half lane/32 of the step
+                const int nb = wn * WTN + j * 32 + tr8_n;
+                const int kbase = (ks * 2 + tr8_half) * (16 * CH) + tr8_row;
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const char* r0 = sb + (kbase + c * 16) * BN + ((((nb >> 4) ^ tr8_row)) << 4) + (nb & 15);
+                    int2v lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0));
+                    int2v hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0 + 8 * BN));
+                    int4v w = {lo[0], lo[1], hi[0], hi[1]};
+                    bf[j].c[c] = __builtin_bit_cast(short8v, w);
+                }
             } else {
                 int nbyte = (wn * WTN + j * 32) * 2 + tr_nbyte;
                 int k = ks * 16 + tr_k;

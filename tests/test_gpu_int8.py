@@ -86,6 +86,42 @@ def test_matmul_int8_row_major_b_runs_generic():
     assert np.array_equal(got, oracle.matmul_int8(A, B, trans_b=0, **q))
 
 
+@pytest.mark.parametrize("cfg", [None, 0, 1, 4])
+@pytest.mark.parametrize("mnk", [(300, 272, 208), (256, 512, 128), (33, 144, 4096)])
+def test_matmul_int8_row_major_b_on_mfma(cfg, mnk):
+    """Row-major B: the n-major byte tile is read with the 8-bit transposing LDS read."""
+    import oracle
+    m, n, k = mnk
+    A = wl.int8_tensor((m, k), 1); B = wl.int8_tensor((k, n), 2)
+    q = params(n, 3)
+    got, kern = run_matmul(A, B, q, 0, True, None if cfg is None else f"mfma:{cfg}")
+    assert "mfma" in kern
+    assert np.array_equal(got, oracle.matmul_int8(A, B, trans_b=0, **q))
+
+
+@pytest.mark.parametrize("cfg", [None, 0, 1, 4])
+@pytest.mark.parametrize("geom", [((1, 1), (1, 1), (1, 1)), ((2, 2), (1, 1), (1, 1)), ((1, 2), (2, 0), (2, 1))])
+def test_conv_int8_on_mfma(cfg, geom):
+    """The paper's quantised example is a convolution: channels multiples of 16 run on the matrix units."""
+    import torch
+    import oracle
+    import paper_2603_06731_amd as pbk
+    stride, pad, dil = geom
+    n, H, W, Cin, Cout, KH, KW = 2, 15, 14, 32, 48, 3, 3
+    x = wl.int8_tensor((n, H, W, Cin), 1, "normal", 40.0); w = wl.int8_tensor((KH, KW, Cin, Cout), 2, "normal", 30.0)
+    q = params(Cout, 3)
+    want = oracle.conv2d_nhwc_int8(x, w, stride=stride, pad=pad, dil=dil, **q)
+    out = torch.empty(want.size, dtype=torch.int8, device="cuda")
+    d = {k2: dev_or_none(v) if isinstance(v, np.ndarray) else v for k2, v in q.items()}
+    with T.forced_kernel(None if cfg is None else f"mfma:{cfg}"):
+        st = pbk.pbk_conv2d_nhwc_int8(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), out, n, H, W, Cin, Cout,
+                                      KH, KW, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], d["scale"], d["bias"],
+                                      q["mid_scale"], d["mul"], d["add"], q["relu"], q["out_scale"], INT8, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    assert "mfma" in pbk.pbk_last_kernel()
+    assert np.array_equal(out.cpu().numpy().reshape(want.shape), want)
+
+
 def test_matmul_int8_extreme_values_and_saturation():
     import oracle
     m, n, k = 128, 256, 8192

@@ -275,6 +275,30 @@ def test_fp8_matmul_other_layouts_take_generic_kernel(dtype, mnk, trans_b):
     check_full(w, expect_kernel="generic")
 
 
+@pytest.mark.parametrize("dtype", FP8_TYPES)
+@pytest.mark.parametrize("cfg", [None, 1, 4])
+@pytest.mark.parametrize("mnk", [(300, 272, 208), (256, 512, 128), (33, 144, 4096)])
+def test_fp8_matmul_row_major_b_on_mfma(dtype, cfg, mnk):
+    """Row-major B: the n-major byte tile is read with the 8-bit transposing LDS read."""
+    m, n, k = mnk
+    w = wl.Workload("fp8_nn", "matmul", dtype, BF16, C.EPI_BIAS_RELU, M=m, N=n, K=k,
+                    dist_b=("normal", 1.0 / np.sqrt(k)), dist_bias=("normal", 0.5))
+    check_full(w, force=None if cfg is None else f"mfma:{cfg}", expect_kernel="mfma")
+
+
+@pytest.mark.parametrize("dtype", FP8_TYPES)
+@pytest.mark.parametrize("cfg", [None, 1, 4])
+@pytest.mark.parametrize("case", [(2, 14, 13, 32, 48, 3, 3, (1, 1), (1, 1), (1, 1)),
+                                  (1, 17, 16, 128, 64, 3, 3, (2, 2), (1, 1), (1, 1)),
+                                  (2, 12, 12, 48, 80, 2, 3, (1, 2), (0, 2), (2, 1))])
+def test_fp8_conv_on_mfma(dtype, cfg, case):
+    n, H, W, Cin, Cout, KH, KW, stride, pad, dil = case
+    w = wl.Workload("fp8_conv_mfma", "conv", dtype, BF16, C.EPI_BIAS_RELU, n=n, H=H, W=W, Cin=Cin, Cout=Cout,
+                    KH=KH, KW=KW, stride=stride, pad=pad, dil=dil,
+                    dist_b=("normal", float(np.sqrt(2.0 / (KH * KW * Cin)))))
+    check_full(w, force=None if cfg is None else f"mfma:{cfg}", expect_kernel="mfma")
+
+
 def test_fp8_batched_and_conv_generic():
     w = wl.Workload("fp8_bmm", "batched", wl.DTYPE_FP8_E4M3, F16, C.EPI_NONE, alpha=0.25, batch=3, M=136, N=200,
                     K=128, trans_b=1)
