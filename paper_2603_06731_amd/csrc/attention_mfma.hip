@@ -306,7 +306,14 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         for (int ks = 0; ks < KPF; ++ks) read_k(PAR * TILE, ks);
         read_v((2 + PAR) * TILE);
         __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < NT) { issue_v(t + 1); issue_k(t + 1); }
+        // Without a bias the next tile's loads go out right away.  With one, the bias is read
+        // with ordinary loads whose completion (vmcnt counts every vector memory operation, in
+        // order) would also wait for direct-to-LDS loads issued before them: the first block's
+        // bias is therefore requested now, while nothing else is in flight, and the tile loads
+        // are issued after it has been consumed.
+        float bias_first[16];
+        if (HAS_BIAS) load_bias(t * ATT_BKV + 32, bias_first);
+        else if (t + 1 < NT) { issue_v(t + 1); issue_k(t + 1); }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb) {
@@ -351,7 +358,14 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
 
             // ---- phase 2
             float biasn[16];
-            if (HAS_BIAS) load_bias(knext, biasn);
+            if (HAS_BIAS) {
+                if (hb == 0) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) biasn[e] = bias_first[e];
+                } else {
+                    load_bias(knext, biasn);
+                }
+            }
             const bool ragged = knext + 32 > p.Nk;           // wave-uniform
             float bmax = -INFINITY;
             int mfma_idx = 0;
@@ -379,6 +393,7 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
                 }
             }
             move_reference(bmax);
+            if (HAS_BIAS && hb == 0 && t + 1 < NT) { issue_v(t + 1); issue_k(t + 1); }
         }
     };
     int t = 0;
