@@ -38,7 +38,7 @@ bool mfma_supported(const Problem& p) {
 
 static int choose_config(const Problem& p) {
     // 128x256 tiles, two workgroups of four waves per CU: the two barrier domains
-    // fill each other's bubbles; measured best on all large shapes, long or short K
+    // fill each other's bubbles
     long long t = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256) * p.batch;
     if (p.trans_b && !p.is_conv) {
         // k-major B: the 128x256 configuration is slow there (measured 1044 us against 874 us for
@@ -47,6 +47,11 @@ static int choose_config(const Problem& p) {
         if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 3;
         return 1;
     }
+    // Long contractions over many tiles: one 256x256x32 workgroup per CU with a 4-stage ring
+    // (measured on 8192^3 and 8192x14336x4096: 850 / 834 us against 912 / 876 us for configuration 0).
+    // Short contractions (store-dominated) and convolutions stay with two 128x256 workgroups per CU.
+    long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
+    if (!p.is_conv && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 1024) return 3;
     if (p.M >= 128 && p.N >= 256 && t >= 256) return 0;
     return 1;
 }

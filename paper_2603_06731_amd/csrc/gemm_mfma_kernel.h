@@ -116,6 +116,7 @@ struct TileMap {
     int tiles_m, tiles_n, tiles_per_batch, total;
     int group_m;
     int xcds;
+    int prio;          // non-zero: raise the wave's priority while it issues its MFMA groups
 };
 
 __device__ __forceinline__ void map_tile(const TileMap& tm, int bid, int& b, int& tile_m, int& tile_n) {
@@ -828,7 +829,9 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             read_a(sa, ks + 1, af[(ks + 1) & 1]);
             read_b(sb, ks + 1, bf[(ks + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
+            if (tmap.prio) __builtin_amdgcn_s_setprio(2);
             if (SPREAD) mfma_step_loading(ks & 1, ks); else mfma_step(ks & 1);
+            if (tmap.prio) __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (have_next) {
@@ -841,7 +844,9 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             read_b(na + A_BYTES, 0, bf[0]);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (tmap.prio) __builtin_amdgcn_s_setprio(2);
         if (SPREAD) mfma_step_loading((KSUB - 1) & 1, KSUB - 1); else mfma_step((KSUB - 1) & 1);
+        if (tmap.prio) __builtin_amdgcn_s_setprio(0);
         __builtin_amdgcn_sched_barrier(0);
     };
 
