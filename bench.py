@@ -9,8 +9,9 @@ inputs that are already resident in HBM.  Prints ONE JSON line: whole-job
 TFLOP/s (2*M*N*K per step, epilogue flops not counted; 4*Nq*Nk*D per batch
 entry for attention, softmax flops not counted), the roofline position of the kernel from HIP
 event timings of every launch, and the CPU oracle timed on a bounded sample of
-the same workload as a baseline.  --all adds a per-workload table on stderr and
-in gpurun_out/bench_all.json; the JSON line is always the headline workload.
+the same workload as a baseline.  --all adds a per-workload table on stderr (and,
+with --json-out FILE, the same rows as JSON); the JSON line is always the
+headline workload.
 """
 import argparse
 import json
@@ -238,6 +239,7 @@ def main():
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--all", action="store_true", help="also time the other workloads (table on stderr)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--json-out", default=None, help="with --all: also write every workload's line to this file")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -282,9 +284,9 @@ def main():
             print(f"{x['config']['workload']:24s} {x['config']['kernel']:26s} {rf['kernel_ms_avg']*1e3:9.1f} us  "
                   f"{x['value']:8.1f} TFLOP/s  {rf['bound']}: {rf['achieved']:.1f} {rf['unit']} = {rf['frac']*100:.1f}%",
                   file=sys.stderr)
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
-            json.dump(rows, f, indent=1)
+        if args.json_out:
+            with open(args.json_out, "w") as f:
+                json.dump(rows, f, indent=1)
     print(json.dumps(line))
 
 
