@@ -76,7 +76,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = 0;
 
-    for (int k0 = 0; k0 < p.K; k0 += GK) {
+    // One k-tile ahead in registers: the global loads of tile t+1 are in flight while tile t is
+    // multiplied out of LDS (their latency would otherwise be paid once per k-tile).
+    float a_next[4], b_next[4];
+    auto fetch = [&](int k0) {
         // A tile: 64 rows x 16 k; lanes run along k (contiguous in memory)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -88,7 +91,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
                 if (CONV) v = conv_a<T>(A, p.conv, gm, gk);
                 else v = ld_elem<T>(A, (int64_t)gm * p.lda + gk);
             }
-            As[kk][mm] = (acc_t)v;
+            a_next[r] = v;
         }
         // B tile: 16 k x 64 n
 #pragma unroll
@@ -102,9 +105,23 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
             if (gk < p.K && gn < p.N)
                 v = p.trans_b ? ld_elem<T>(B, (int64_t)gn * p.ldb + gk)
                               : ld_elem<T>(B, (int64_t)gk * p.ldb + gn);
-            Bs[kk][nn] = (acc_t)v;
+            b_next[r] = v;
         }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int e = t + 256 * r;
+            As[e % GK][e / GK] = (acc_t)a_next[r];
+            if (p.trans_b) Bs[e % GK][e / GK] = (acc_t)b_next[r];
+            else Bs[e / GT][e % GT] = (acc_t)b_next[r];
+        }
+    };
+    if (p.K > 0) fetch(0);
+    for (int k0 = 0; k0 < p.K; k0 += GK) {
+        stash();
         __syncthreads();
+        if (k0 + GK < p.K) fetch(k0 + GK);
 #pragma unroll
         for (int kk = 0; kk < GK; ++kk) {
             acc_t a[4], bv[4];
