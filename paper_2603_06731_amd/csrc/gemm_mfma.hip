@@ -40,9 +40,10 @@ static int choose_config(const Problem& p) {
     // 128x256 tiles, two workgroups of four waves per CU: the two barrier domains
     // fill each other's bubbles
     long long t = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256) * p.batch;
-    if (p.trans_b && !p.is_conv) {
-        // k-major B: the 128x256 configuration is slow there (measured 1044 us against 874 us for
-        // 256x256x32 on 8192^3); one 256x256 workgroup per CU is the best choice
+    if (p.trans_b && !p.is_conv && p.K >= 1024) {
+        // k-major B, long contraction: the 128x256 configuration is slow there (measured 1044 us
+        // against 874 us for 256x256x32 on 8192^3); short ones (K = 128: 197 us against 217 us)
+        // follow the general rule below
         long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
         if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 3;
         return 1;
