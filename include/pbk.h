@@ -23,7 +23,9 @@
  *    16-bit and 8-bit inputs are widened exactly, products are accumulated in
  *    fp32,
  *    the epilogue runs in fp32, and the result is rounded once to out_dtype
- *    (round-to-nearest-even).  PBK_F32 inputs use true fp32 multiply-add.
+ *    (round-to-nearest-even).  PBK_F32 inputs use true fp32 multiply-add
+ *    (VALU fma, or v_mfma_f32_32x32x2_f32 for large aligned problems; never a
+ *    reduced-precision emulation).
  *  - Epilogue: t = alpha * acc (+ bias[n] for the BIAS variants);
  *    out = t | max(t,0) | 0.5*t*(1+tanh(sqrt(2/pi)*(t+0.044715*t^3))).
  *    bias must be non-NULL for the BIAS variants and is ignored otherwise.

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpbk.so")
 SOURCES = ["pbk_api.hip", "gemm_generic.hip", "gemm_mfma.hip", "gemm_mfma_bf16.hip", "gemm_mfma_f16.hip",
-           "gemm_mfma_fp8.hip", "gemm_mfma_fp8_e5m2.hip", "gemm_mfma_int8.hip", "attention_generic.hip", "attention_mfma.hip"]
+           "gemm_mfma_fp8.hip", "gemm_mfma_fp8_e5m2.hip", "gemm_mfma_int8.hip", "gemm_mfma_f32.hip", "attention_generic.hip", "attention_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,7 +1,7 @@
 // Generic contraction kernel: any dtype, any alignment, any leading dimension,
 // transposed B, and the implicit-GEMM view of a convolution.  True fp32
 // multiply-add on widened inputs.  LDS-tiled 64x64x16, 4x4 outputs per lane.
-// It is the fp32 path and the safety net for shapes the MFMA path declines.
+// It is the fp32 path for small or unaligned problems and the safety net for shapes the MFMA path declines.
 //
 // Tiling and staging follow the paper's scheme (Sec. 4.3 tiling + fast
 // buffers, Sec. 4.5 on-the-fly packing of the im2col tile, partial tiles

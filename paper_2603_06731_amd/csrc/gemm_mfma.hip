@@ -13,16 +13,18 @@ static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 bool mfma_supported(const Problem& p) {
     // 8-bit operand types (FP8, int8): 16 values per 16-byte piece
     const bool e8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2 || p.in_dtype == DT_INT8;
-    if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16 && !e8) return false;
-    const int per16 = e8 ? 16 : 8;                   // elements per 16-byte piece
-    const int esz = e8 ? 1 : 2;
+    const bool f32 = p.in_dtype == DT_F32;
+    if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16 && !e8 && !f32) return false;
+    const int per16 = e8 ? 16 : f32 ? 4 : 8;         // elements per 16-byte piece
+    const int esz = e8 ? 1 : f32 ? 4 : 2;
+    if (f32 && p.K >= (1 << 29)) return false;        // k sizes are doubled for the kernel
     if (p.K < per16 || p.K % per16) return false;
     if (!al16(p.A) || !al16(p.B)) return false;
     if (p.stride_a % per16 || p.stride_b % per16) return false;
     // per-lane buffer offsets are 32-bit and must stay below 2^31
     const int64_t lim = (int64_t)1 << 31;
     if (p.is_conv) {
-        if (e8 && p.conv.transposed) return false;   // the transposed form is built for 16-bit types
+        if ((e8 || f32) && p.conv.transposed) return false;   // the transposed form is built for 16-bit types
         if (p.conv.Cin % per16 || p.N % per16) return false;
         int64_t img = (int64_t)(p.M / (p.conv.OH * p.conv.OW)) * p.conv.H * p.conv.W * p.conv.Cin * esz;
         int64_t halo = ((int64_t)p.conv.pad_h * p.conv.W + p.conv.pad_w + p.conv.W) * p.conv.Cin * esz;
@@ -34,6 +36,14 @@ bool mfma_supported(const Problem& p) {
     }
     if (256 * p.ldb * esz + 1024 >= lim) return false;
     return true;
+}
+
+// fp32 operands take the matrix units only when there is enough work to fill the chip with
+// 128-row tiles; small problems (cfg1-sized) are quicker on the generic kernel's 64x64 tiles.
+bool mfma_preferred(const Problem& p) {
+    if (p.in_dtype != DT_F32) return true;
+    long long t = (long long)((p.M + 127) / 128) * ((p.N + 127) / 128) * p.batch;
+    return p.M >= 128 && p.N >= 128 && t >= 64;
 }
 
 static int choose_config(const Problem& p) {
@@ -59,6 +69,12 @@ static int choose_config(const Problem& p) {
 
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name) {
     const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2;
+    if (p.in_dtype == DT_F32) {
+        long long t = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256) * p.batch;
+        int c = (force_cfg == 0 || force_cfg == 1) ? force_cfg : (p.M >= 128 && p.N >= 256 && t >= 256) ? 0 : 1;
+        *name = c == 0 ? "mfma_f32_128x256x16_w1x4_s3_occ2" : "mfma_f32_128x128x32_w2x2_s2";
+        return launch_mfma_f32(p, stream, c, 8);
+    }
     if (p.in_dtype == DT_INT8) {
         // measured: the 256x256 tile with the deep k-tile is the fastest of the three built for int8
         long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;

@@ -19,7 +19,7 @@ inline Problem to_k_units(const Problem& p) {
 }
 
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC>
-hipError_t launch_8bit_modes(const Problem& q, hipStream_t stream, int group_m) {
+hipError_t launch_typed_modes(const Problem& q, hipStream_t stream, int group_m) {
     if (q.is_conv) return launch_one<T, TO, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC>(q, stream, group_m);
     if (q.trans_b) return launch_one<T, TO, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC>(q, stream, group_m);
     return launch_one<T, TO, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC>(q, stream, group_m);
@@ -29,8 +29,8 @@ hipError_t launch_8bit_modes(const Problem& q, hipStream_t stream, int group_m) 
 template <typename T, typename TO>
 hipError_t launch_fp8_cfg(const Problem& q, hipStream_t stream, int cfg, int group_m) {
     switch (cfg) {
-    case 1: return launch_8bit_modes<T, TO, 128, 128, 64, 2, 2, 2, 1>(q, stream, group_m);
-    case 4: return launch_8bit_modes<T, TO, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
+    case 1: return launch_typed_modes<T, TO, 128, 128, 64, 2, 2, 2, 1>(q, stream, group_m);
+    case 4: return launch_typed_modes<T, TO, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
     default: return hipErrorInvalidValue;
     }
 }

@@ -8,9 +8,9 @@ namespace pbk {
 hipError_t launch_mfma_int8(const Problem& p, hipStream_t stream, int cfg, int group_m) {
     const Problem q = to_k_units(p);
     switch (cfg) {
-    case 0: return launch_8bit_modes<int8_t, bf16_t, 128, 256, 32, 1, 4, 3, 2>(q, stream, group_m);
-    case 1: return launch_8bit_modes<int8_t, bf16_t, 128, 128, 64, 2, 2, 2, 1>(q, stream, group_m);
-    case 4: return launch_8bit_modes<int8_t, bf16_t, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
+    case 0: return launch_typed_modes<int8_t, bf16_t, 128, 256, 32, 1, 4, 3, 2>(q, stream, group_m);
+    case 1: return launch_typed_modes<int8_t, bf16_t, 128, 128, 64, 2, 2, 2, 1>(q, stream, group_m);
+    case 4: return launch_typed_modes<int8_t, bf16_t, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
     default: return hipErrorInvalidValue;
     }
 }

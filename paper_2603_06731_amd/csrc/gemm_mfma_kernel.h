@@ -107,6 +107,20 @@ template <> struct MfmaOp<int8_t> {
     }
 };
 
+// fp32: v_mfma_f32_32x32x2_f32 (true fp32 products and sums), one k value per lane and
+// instruction: the 16-byte fragment (4 consecutive k) feeds four of them.  Lanes 0-31 hold
+// k0..k0+3 and lanes 32-63 k0+4..k0+7, so instruction e contracts k0+e with k0+4+e; any
+// pairing is as good as another as long as both operands use the same one.
+template <> struct MfmaOp<float> {
+    static constexpr int kChunks = 1;
+    static __device__ __forceinline__ f32x16 run(const Frag<1>& a, const Frag<1>& b, f32x16 c) {
+        const f32x4 av = __builtin_bit_cast(f32x4, a.c[0]), bv = __builtin_bit_cast(f32x4, b.c[0]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[e], c, 0, 0, 0);
+        return c;
+    }
+};
+
 // How linear workgroup ids are turned into (batch, tile_m, tile_n).
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; ids
 // are first regrouped so that every XCD owns a contiguous run, then runs are
@@ -497,7 +511,10 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     // 8-bit element types: sizes along k are in 2-byte units, a k-row of the n-major B tile is one
     // k VALUE (so the tile has 2*BK rows of BN bytes) and is read with the 8-bit transposing LDS read
     constexpr bool E8 = sizeof(T) == 1;
-    static_assert(!E8 || MODE != MODE_CONVT, "transposed convolution is built for 16-bit types only");
+    // fp32: a unit is half a value; the n-major B tile has BK/2 rows of BN floats and is read with
+    // plain 4-byte LDS reads (32 lanes along n)
+    constexpr bool E4 = sizeof(T) == 4;
+    static_assert(sizeof(T) == 2 || MODE != MODE_CONVT, "transposed convolution is built for 16-bit types only");
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE = A_BYTES + B_BYTES;
     constexpr int A_BLKS = A_BYTES / 1024, B_BLKS = B_BYTES / 1024;     // 1 KiB per wave-load
@@ -533,6 +550,9 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     // 8-bit n-major tile ([2 BK][BN] bytes): 1 KiB block = NM8_ROWS k-rows of BN/16 slots
     constexpr int NM8_CPR = BN / 16;
     constexpr int NM8_ROWS = 64 / NM8_CPR;
+    // fp32 n-major tile ([BK/2][BN] floats): BN/4 slots per k-row
+    constexpr int NM4_CPR = BN / 4;
+    constexpr int NM4_ROWS = 64 / NM4_CPR;
 
     const char* Abase = (const char*)p.A + (int64_t)b * p.stride_a * 2;
     const char* Bbase = (const char*)p.B + (int64_t)b * p.stride_b * 2;
@@ -591,6 +611,16 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                 b_voff[r] = (n0 + chunk * 16 < p.N) ? (unsigned)(krow * (int)p.ldb * 2 + chunk * 16) : kOob;
                 continue;
             }
+            if (E4) {
+                // 128-byte chunks XOR-swizzled by bit 2 of the k-row: the two rows a 4-byte read
+                // touches (k and k+4, lanes 0-31 and 32-63) fall into different bank halves
+                const int krow = blk * NM4_ROWS + lane / NM4_CPR;
+                const int slot = lane % NM4_CPR;
+                const int sslot = ((((slot >> 3) ^ ((krow >> 2) & 1))) << 3) | (slot & 7);
+                b_kofs[r] = krow * 2;
+                b_voff[r] = (n0 + sslot * 4 < p.N) ? (unsigned)(krow * (int)p.ldb * 2 + sslot * 16) : kOob;
+                continue;
+            }
             int krow = blk * NM_ROWS + nm_row;
             int c64 = (nm_slot >> 2) ^ (krow & 3);
             int nbyte = (c64 << 6) | ((nm_slot & 3) << 4);
@@ -601,7 +631,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 
     // Descriptor bases: A at (m0, 0), B at (0, n0) resp. (n0, 0); advanced by k0 per k-tile.
     const char* a_tile = CONV ? Abase : Abase + (int64_t)m0 * p.lda * 2;
-    const char* b_tile = TRANS_B ? Bbase + (int64_t)n0 * p.ldb * 2 : Bbase + (int64_t)n0 * (E8 ? 1 : 2);
+    const char* b_tile = TRANS_B ? Bbase + (int64_t)n0 * p.ldb * 2 : Bbase + (int64_t)n0 * (E8 ? 1 : E4 ? 4 : 2);
 
     const unsigned lds_base = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr_of(lds));
 
@@ -637,7 +667,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         } else {
             ld_ra = make_rsrc(a_tile + (int64_t)k0 * 2);
         }
-        ld_rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2 : b_tile + (int64_t)k0 * p.ldb * (E8 ? 4 : 2));
+        ld_rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2 : b_tile + (int64_t)k0 * p.ldb * (E8 ? 4 : E4 ? 1 : 2));
     };
 
     // Issue load number r (0 .. LOADS-1) of the current tile: first this wave's
@@ -738,6 +768,14 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 #pragma unroll
                 for (int c = 0; c < CH; ++c)
                     bf[j].c[c] = *(const short8v*)(sb + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
+            } else if (E4) {
+                // column n = lane%32, k = 8 ks + 4 (lane/32) + e for e = 0..3: four 4-byte reads
+                const int nbyte = (wn * WTN + j * 32 + frag_row) * 4;
+                const char* r0 = sb + (ks * 8 + frag_kc * 4) * (BN * 4) + ((((nbyte >> 7) ^ frag_kc)) << 7) + (nbyte & 127);
+                int4v w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = *(const int*)(r0 + e * (BN * 4));
+                bf[j].c[0] = __builtin_bit_cast(short8v, w);
             } else if (E8) {
                 // a lane's fragment: 16*CH consecutive k of column n = lane%32, half lane/32 of the step
                 const int nb = wn * WTN + j * 32 + tr8_n;

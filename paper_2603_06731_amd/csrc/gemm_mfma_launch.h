@@ -92,6 +92,7 @@ hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int grou
 hipError_t launch_mfma_bf16(const Problem& p, hipStream_t stream, int cfg, int group_m);
 hipError_t launch_mfma_fp8(const Problem& p, hipStream_t stream, int cfg, int group_m);
 hipError_t launch_mfma_int8(const Problem& p, hipStream_t stream, int cfg, int group_m);
+hipError_t launch_mfma_f32(const Problem& p, hipStream_t stream, int cfg, int group_m);
 hipError_t launch_mfma_f16(const Problem& p, hipStream_t stream, int cfg, int group_m);
 
 }  // namespace pbk

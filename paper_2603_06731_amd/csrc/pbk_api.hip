@@ -56,7 +56,7 @@ pbk_status dispatch(const pbk::Problem& p_in, void* stream) {
     hipError_t e;
     bool can_mfma = pbk::mfma_supported(p);
     if (force == 2 && !can_mfma) return PBK_ERR_UNSUPPORTED;
-    if (can_mfma && force != 1)
+    if (can_mfma && force != 1 && (force == 2 || pbk::mfma_preferred(p)))
         e = pbk::launch_mfma(p, (hipStream_t)stream, cfg, &name);
     else
         e = pbk::launch_generic(p, (hipStream_t)stream, &name);

@@ -77,6 +77,8 @@ hipError_t launch_generic(const Problem& p, hipStream_t stream, const char** nam
 
 // Returns false if this problem cannot take the MFMA path (alignment, dtype).
 bool mfma_supported(const Problem& p);
+// Returns false where the generic kernel is the better choice although the MFMA path could run.
+bool mfma_preferred(const Problem& p);
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name);
 
 // Attention: generic kernel (any dtype/alignment, D <= 512) and the fused MFMA kernel.

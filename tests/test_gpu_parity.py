@@ -319,3 +319,44 @@ def test_fp8_full_size_sampled():
     err = T.rel_err(T.gather_output(out, w, b, i, j), ref, pre)
     print(f"fp8 8192^3 kernel={pbk.pbk_last_kernel()} err={err:.3e}", flush=True)
     assert err <= T.TIGHT[BF16], err
+
+
+# ----------------------------------------------------------------- fp32 on MFMA
+
+@pytest.mark.parametrize("cfg", [None, 0, 1])
+@pytest.mark.parametrize("mnk,trans_b", [((520, 264, 200), 0), ((256, 512, 64), 1), ((1100, 1032, 132), 0),
+                                         ((300, 260, 36), 1)])
+def test_fp32_matmul_on_mfma(cfg, mnk, trans_b):
+    """fp32 operands on v_mfma_f32_32x32x2_f32: true fp32 arithmetic, the 1e-5 bar."""
+    m, n, k = mnk
+    w = wl.Workload("f32_mfma", "matmul", F32, F32, C.EPI_BIAS_GELU_TANH, alpha=0.75, M=m, N=n, K=k, trans_b=trans_b,
+                    dist_a=("uniform", 1.0), dist_b=("uniform", 1.0), dist_bias=("uniform", 1.0))
+    if cfg is None and m * n < 1024 * 1024:
+        check_full(w, expect_kernel="generic")          # too little work: the dispatcher keeps the generic kernel
+    else:
+        check_full(w, force=None if cfg is None else f"mfma:{cfg}", expect_kernel="mfma_f32")
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_fp32_batched_and_conv_on_mfma(cfg):
+    w = wl.Workload("f32_bmm", "batched", F32, F32, C.EPI_NONE, alpha=0.5, batch=3, M=264, N=200, K=96,
+                    dist_a=("uniform", 1.0), dist_b=("uniform", 1.0))
+    check_full(w, force=f"mfma:{cfg}", expect_kernel="mfma_f32")
+    w = wl.Workload("f32_conv", "conv", F32, F32, C.EPI_BIAS_RELU, n=2, H=14, W=13, Cin=20, Cout=36, KH=3, KW=3,
+                    stride=(2, 1), pad=(1, 2), dil=(1, 2), dist_a=("uniform", 1.0), dist_b=("uniform", 0.2),
+                    dist_bias=("uniform", 0.5))
+    check_full(w, force=f"mfma:{cfg}", expect_kernel="mfma_f32")
+
+
+def test_fp32_large_matmul_takes_mfma_and_is_sampled():
+    import paper_2603_06731_amd as pbk
+    w = wl.Workload("f32_2048", "matmul", F32, F32, C.EPI_BIAS_RELU, M=2048, N=2048, K=1024,
+                    dist_a=("uniform", 1.0), dist_b=("uniform", 1.0), dist_bias=("uniform", 1.0))
+    host = wl.make_inputs(w)
+    st, out = T.run_workload(w, T.upload(host))
+    assert st == 0 and "mfma_f32" in pbk.pbk_last_kernel()
+    b, i, j = T.sample_coords(w, 2000)
+    ref, pre = T.oracle_sampled(w, host, b, i, j)
+    err = T.rel_err(T.gather_output(out, w, b, i, j), ref, pre)
+    print(f"f32 2048x2048x1024 kernel={pbk.pbk_last_kernel()} err={err:.3e}", flush=True)
+    assert err <= T.TOL_F32, err
