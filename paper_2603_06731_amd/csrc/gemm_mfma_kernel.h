@@ -32,6 +32,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 #include "pbk_problem.h"
 #include "pbk_epilogue.h"
 
@@ -75,6 +76,21 @@ template <> struct MfmaOp<f16_t> {
     static __device__ __forceinline__ f32x16 run(const Frag<1>& a, const Frag<1>& b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a.c[0]),
                                                       __builtin_bit_cast(f16x8, b.c[0]), c, 0, 0, 0);
+    }
+};
+// 16-bit types, 16x16 blocks: v_mfma_f32_16x16x32.  Lane l holds, of either operand, index l%16
+// and the 8 consecutive k values 8 (l/16) .. 8 (l/16) + 7; of the result, column l%16 of srcB's
+// index and rows 4 (l/16) + 0..3 of srcA's.  Half the accumulator traffic per flop of the 32x32
+// instruction: measured 10 % faster at full clock and 17 % faster under the power cap.
+template <typename T> struct MfmaOp16;
+template <> struct MfmaOp16<bf16_t> {
+    static __device__ __forceinline__ f32x4 run(short8v a, short8v b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct MfmaOp16<f16_t> {
+    static __device__ __forceinline__ f32x4 run(short8v a, short8v b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
 __device__ __forceinline__ int8v frag_bytes32(const Frag<2>& f) {
@@ -130,7 +146,6 @@ struct TileMap {
     int tiles_m, tiles_n, tiles_per_batch, total;
     int group_m;
     int xcds;
-    int prio;          // non-zero: raise the wave's priority while it issues its MFMA groups
 };
 
 __device__ __forceinline__ void map_tile(const TileMap& tm, int bid, int& b, int& tile_m, int& tile_n) {
@@ -148,23 +163,30 @@ __device__ __forceinline__ void map_tile(const TileMap& tm, int bid, int& b, int
     tile_n = in_g / rows;
 }
 
-// 16-byte-chunk swizzle for a [rows][BK] 16-bit tile (row = BK*2 bytes).
-template <int BK>
+// 16-byte-chunk swizzle for a [rows][BK] 16-bit tile (row = BK*2 bytes).  The term that is
+// XORed into the chunk index steps every RP rows; which RP keeps a wave-wide ds_read_b128 free of
+// bank conflicts depends on how the fragment spreads its lanes over rows and chunks (measured with
+// the bank-conflict counter): 32-row fragments (row lane%32, chunk lane/32) need 256 bytes' worth
+// of rows per step, 16-row fragments (row lane%16, chunk lane/16) half of that.
+template <int BK, bool S16 = false>
 __device__ __forceinline__ int kmajor_swz(int row) {
     constexpr int CPR = BK / 8;            // chunks per row
-    constexpr int RP = 256 / (BK * 2);     // rows per 256 bytes (all 64 banks)
+    constexpr int RP = (S16 ? 128 : 256) / (BK * 2);
     return (row / RP) % CPR;
 }
-template <int BK>
+template <int BK, bool S16 = false>
 __device__ __forceinline__ int kmajor_offset(int row, int chunk) {
-    return row * (BK * 2) + ((chunk ^ kmajor_swz<BK>(row)) << 4);
+    return row * (BK * 2) + ((chunk ^ kmajor_swz<BK, S16>(row)) << 4);
 }
 
 // Byte offset inside a [BK][BN] 16-bit tile (row = BN*2 bytes) of byte `nbyte`
-// of row k, 64-byte chunks XOR-swizzled by k.
+// of row k: 64-byte chunks XOR-swizzled by k%4, and the two 32-byte halves of a
+// chunk swapped in rows with bit 3 of k set (a transposing read of the 16x16
+// blocks touches rows k..k+3 and k+8..k+11 of one 32-byte column in one pass).
+__device__ __forceinline__ int nmajor_half(int k) { return ((k >> 3) & 1) << 5; }
 template <int BN>
 __device__ __forceinline__ int nmajor_offset(int k, int nbyte) {
-    return k * (BN * 2) + ((((nbyte >> 6) ^ (k & 3)) << 6) | (nbyte & 63));
+    return k * (BN * 2) + ((((nbyte >> 6) ^ (k & 3)) << 6) | ((nbyte & 63) ^ nmajor_half(k)));
 }
 
 // Raw buffer descriptor over [base, base + 2^31): stride 0, 32-bit data format.
@@ -219,14 +241,27 @@ template <> __device__ __forceinline__ uint32_t pack2<f16_t>(float a, float b) {
 }
 
 // Epilogue of one wave: its WTM x WTN register tile -> global memory.
-template <typename T, int FM, int FN, int WTM, int WTN, int LDS_PER_WAVE>
+// AV is the accumulator vector of one MFMA block and fixes the block layout:
+//   f32x16 (32x32 block): lane holds row lane%32, columns 8 g + 4 (lane/32) + 0..3 for g = 0..3;
+//   f32x4  (16x16 block): lane holds row lane%16, columns 4 (lane/16) + 0..3.
+template <typename T, typename AV, int FM, int FN, int WTM, int WTN, int LDS_PER_WAVE>
 struct EpiCtx {
+    static constexpr bool S16 = sizeof(AV) == 16;
+    static constexpr int RB = S16 ? 16 : 32;       // rows (and columns) of one block
+    static constexpr int G = S16 ? 1 : 4;          // 4-column pieces a lane holds per block
+    static_assert(FM * RB == WTM && FN * RB == WTN, "blocks must tile the wave tile");
     const Problem& p;
-    f32x16 (&acc)[FM][FN];
+    AV (&acc)[FM][FN];
     char* wlds;            // this wave's private LDS slice
     int row0, col0;        // global coordinates of the wave tile's corner
     int lane;
     int64_t c_batch;
+
+    __device__ __forceinline__ int lrow_of(int i) const { return i * RB + (lane & (RB - 1)); }
+    __device__ __forceinline__ int lcol_of(int j, int g) const {
+        return S16 ? j * 16 + ((lane >> 4) << 2) : j * 32 + g * 8 + ((lane >> 5) << 2);
+    }
+    __device__ __forceinline__ float val(int i, int j, int g, int e) const { return acc[i][j][S16 ? e : g * 4 + e]; }
 
     template <int ACT> __device__ __forceinline__ float act_of(float acc_v, float bias_v, float res_v = 0.0f) const {
         float t = fmaf(p.alpha, acc_v, bias_v);
@@ -292,22 +327,22 @@ struct EpiCtx {
         constexpr int CPR = ROW_BYTES / 16;                 // 16-byte chunks per row
         constexpr int RP = ROW_BYTES >= 256 ? 1 : 256 / ROW_BYTES;   // rows per 256 bytes
         constexpr int MAX_ROWS = LDS_PER_WAVE / ROW_BYTES;
-        constexpr int PASS_BLOCKS = (MAX_ROWS / 32) < FM ? (MAX_ROWS / 32) : FM;   // 32-row blocks per pass
-        static_assert(PASS_BLOCKS >= 1, "LDS slice too small for one 32-row block");
+        constexpr int PASS_BLOCKS = (MAX_ROWS / RB) < FM ? (MAX_ROWS / RB) : FM;   // row blocks per pass
+        static_assert(PASS_BLOCKS >= 1, "LDS slice too small for one row block");
         static_assert(CPR <= 64 && 64 % CPR == 0, "row chunks must divide the wave");
         constexpr int ROWS_PER_LD = 64 / CPR;               // rows covered by one wave-wide 16-byte read
-        static_assert((32 % ROWS_PER_LD) == 0, "reads must tile a 32-row block");
+        static_assert((RB % ROWS_PER_LD) == 0, "reads must tile a row block");
         const int ld_row = lane / CPR, ld_chunk = lane % CPR;
         const bool res_vec = p.R && (p.ldr % 4 == 0) &&
                              (((uintptr_t)p.R + (uintptr_t)c_batch * ESZ) % (4 * ESZ) == 0);
 
         // every bias value this lane needs, loaded once and together
-        float bias_r[FN][4][4];
+        float bias_r[FN][G][4];
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                bias4(col0 + j * 32 + g * 8 + ((lane >> 5) << 2), bias_vec, bias_r[j][g]);
+            for (int g = 0; g < G; ++g)
+                bias4(col0 + lcol_of(j, g), bias_vec, bias_r[j][g]);
 
 #pragma unroll
         for (int i0 = 0; i0 < FM; i0 += PASS_BLOCKS) {
@@ -316,17 +351,17 @@ struct EpiCtx {
             for (int ii = 0; ii < PASS_BLOCKS; ++ii) {
                 const int i = i0 + ii;
                 if (i >= FM) break;
-                const int lrow = ii * 32 + (lane & 31);
+                const int lrow = lrow_of(ii);
                 const int sw = (lrow / RP) % CPR;
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int lcol = j * 32 + g * 8 + ((lane >> 5) << 2);
+                    for (int g = 0; g < G; ++g) {
+                        const int lcol = lcol_of(j, g);
                         float v[4], rv[4];
-                        res4<OUT_F32>(row0 + i * 32 + (lane & 31), col0 + lcol, res_vec, rv);
+                        res4<OUT_F32>(row0 + lrow_of(i), col0 + lcol, res_vec, rv);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(acc[i][j][g * 4 + e], bias_r[j][g][e], rv[e]);
+                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(val(i, j, g, e), bias_r[j][g][e], rv[e]);
                         const int cbyte = lcol * ESZ;
                         char* dst = wlds + lrow * ROW_BYTES + ((((cbyte >> 4) ^ sw)) << 4) + (cbyte & 15);
                         if (OUT_F32) {
@@ -343,11 +378,11 @@ struct EpiCtx {
             }
             // LDS -> global, 16 bytes per lane, lanes running along rows; reads are
             // batched ahead of the stores so their latency is paid once per batch
-            constexpr int PASS_ROWS = PASS_BLOCKS * 32;
+            constexpr int PASS_ROWS = PASS_BLOCKS * RB;
             constexpr int NLD = PASS_ROWS / ROWS_PER_LD;
             constexpr int BATCH = NLD < 8 ? NLD : 8;
             const int gn = col0 + ld_chunk * EPC;
-            const int lrow0 = i0 * 32 + ld_row;                     // row inside the wave tile
+            const int lrow0 = i0 * RB + ld_row;                     // row inside the wave tile
             char* cptr = (char*)p.C + (c_batch + (int64_t)(row0 + lrow0) * p.ldc + gn) * ESZ;
             const int64_t cstep = (int64_t)ROWS_PER_LD * p.ldc * ESZ;
             const int rows_left = (p.M - row0 < WTM ? p.M - row0 : WTM) - lrow0;   // valid rows from lrow0 on
@@ -388,8 +423,8 @@ struct EpiCtx {
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int lcol = j * 32 + g * 8 + ((lane >> 5) << 2);
+            for (int g = 0; g < G; ++g) {
+                const int lcol = lcol_of(j, g);
                 const int gn = col0 + lcol;
                 QuantParams c[4];
 #pragma unroll
@@ -402,14 +437,14 @@ struct EpiCtx {
                 }
 #pragma unroll
                 for (int i = 0; i < FM; ++i) {
-                    const int lrow = i * 32 + (lane & 31);
+                    const int lrow = lrow_of(i);
                     const int gm = row0 + lrow;
                     if (!staged && (gm >= p.M || gn >= p.N)) continue;
                     const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
                     float t[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        t[e] = quant_value(__float_as_int(acc[i][j][g * 4 + e]), c[e], has_bias, has_mul, has_add,
+                        t[e] = quant_value(__float_as_int(val(i, j, g, e)), c[e], has_bias, has_mul, has_add,
                                            p.q_mid, p.q_relu);
                     if (out_i8) {
                         int8_t q[4];
@@ -462,13 +497,13 @@ struct EpiCtx {
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int gn = col0 + j * 32 + g * 8 + ((lane >> 5) << 2);
+            for (int g = 0; g < G; ++g) {
+                const int gn = col0 + lcol_of(j, g);
                 float bv[4];
                 bias4(gn, bias_vec, bv);
 #pragma unroll
                 for (int i = 0; i < FM; ++i) {
-                    const int gm = row0 + i * 32 + (lane & 31);
+                    const int gm = row0 + lrow_of(i);
                     if (gm >= p.M || gn >= p.N) continue;
                     const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
                     float rv[4];
@@ -476,7 +511,7 @@ struct EpiCtx {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         if (gn + e >= p.N) break;
-                        float v = fmaf(p.alpha, acc[i][j][g * 4 + e], bv[e]);
+                        float v = fmaf(p.alpha, val(i, j, g, e), bv[e]);
                         v = fmaf(p.beta, rv[e], v);
                         if (act == 1) v = fmaxf(v, 0.0f);
                         else if (act == 2) v = gelu_tanh_f32(v);
@@ -498,14 +533,27 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // T: operand type fed to the MFMA; TO: 16-bit output type (used when out_dtype is not F32).
 // Sizes BK, lda, ldb, K and the batch strides are in 2-byte units whatever T is: for the FP8
 // types the host halves them (two FP8 values per unit), the staging code only moves bytes.
-template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
+// MI: edge of the MFMA block, 32 (every type) or 16 (16-bit types: v_mfma_f32_16x16x32).
+// ADBL (16x16 blocks, plain matrices, BK = 32, four stages): A is staged 64 k deep, every other
+// k-tile, so that each direct-to-LDS load moves whole 128-byte lines of A.  With 64-byte row
+// pieces every line of A is requested from L2 twice (once per k-tile; measured: 1.5 times the
+// L1->L2 read requests of the 64-deep configurations), and that path is as loaded as the MFMA pipe.
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC, int MI = 32,
+          bool ADBL = false>
 __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mfma_kernel(Problem p, TileMap tmap) {
+    constexpr bool S16 = MI == 16;
+    static_assert(!ADBL || (MI == 16 && MODE == MODE_DENSE && BK == 32 && NSTAGE == 4), "ADBL: see above");
+    constexpr int BKA = ADBL ? 64 : BK;          // depth of one staged piece of A
+    // raised wave priority around the MFMA groups: measured +1..2.5 % for one 256x256 workgroup per CU
+    // and for the convolution, -1 % for two 128x256 workgroups per CU on plain matrices
+    constexpr bool PRIO = BM == 256 || MODE == MODE_CONV;
+    static_assert(MI == 32 || (MI == 16 && sizeof(T) == 2), "16x16 blocks are built for the 16-bit types");
     constexpr bool CONVT = MODE == MODE_CONVT;               // transposed convolution: gather form
     constexpr bool CONV = MODE == MODE_CONV || CONVT;        // A is an image, rows are output pixels
     constexpr bool TRANS_B = MODE == MODE_TRANS_B;
     constexpr int NW = WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN;
-    constexpr int FM = WTM / 32, FN = WTN / 32;
+    constexpr int FM = WTM / MI, FN = WTN / MI;     // MFMA blocks of the wave tile
     constexpr int CH = MfmaOp<T>::kChunks;         // 16-byte pieces per lane per MFMA operand
     constexpr int KSUB = BK / (16 * CH);           // MFMA k-steps per k-tile
     // 8-bit element types: sizes along k are in 2-byte units, a k-row of the n-major B tile is one
@@ -517,7 +565,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     static_assert(sizeof(T) == 2 || MODE != MODE_CONVT, "transposed convolution is built for 16-bit types only");
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE = A_BYTES + B_BYTES;
-    constexpr int A_BLKS = A_BYTES / 1024, B_BLKS = B_BYTES / 1024;     // 1 KiB per wave-load
+    constexpr int A_BLKS = BM * BKA * 2 / 1024, B_BLKS = B_BYTES / 1024;     // 1 KiB per wave-load
     constexpr int CA = A_BLKS / NW, CB = B_BLKS / NW;
     static_assert(A_BLKS % NW == 0 && B_BLKS % NW == 0, "tile must split evenly over waves");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
@@ -543,6 +591,9 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     constexpr int KM_CPR = BK / 8;
     constexpr int KM_ROWS = 64 / KM_CPR;
     const int km_row = lane / KM_CPR, km_slot = lane % KM_CPR;
+    constexpr int KMA_CPR = BKA / 8;              // the same for the staged piece of A
+    constexpr int KMA_ROWS = 64 / KMA_CPR;
+    const int kma_row = lane / KMA_CPR, kma_slot = lane % KMA_CPR;
     // n-major tile ([BK][BN]): 1 KiB block = NM_ROWS k-rows
     constexpr int NM_CPR = BN / 8;
     constexpr int NM_ROWS = 64 / NM_CPR;
@@ -564,8 +615,8 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 #pragma unroll
     for (int r = 0; r < CA; ++r) {
         int blk = wave * CA + r;
-        int row = blk * KM_ROWS + km_row;
-        int chunk = km_slot ^ kmajor_swz<BK>(row);
+        int row = blk * KMA_ROWS + kma_row;
+        int chunk = kma_slot ^ kmajor_swz<BKA, S16>(row);
         a_kofs[r] = chunk * 8;
         int gm = m0 + row;
         a_ok[r] = gm < p.M;
@@ -598,7 +649,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         int blk = wave * CB + r;
         if (TRANS_B) {
             int row = blk * KM_ROWS + km_row;
-            int chunk = km_slot ^ kmajor_swz<BK>(row);
+            int chunk = km_slot ^ kmajor_swz<BK, S16>(row);
             b_kofs[r] = chunk * 8;
             b_voff[r] = (n0 + row < p.N) ? (unsigned)(row * (int)p.ldb * 2 + chunk * 16) : kOob;
         } else {
@@ -623,7 +674,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             }
             int krow = blk * NM_ROWS + nm_row;
             int c64 = (nm_slot >> 2) ^ (krow & 3);
-            int nbyte = (c64 << 6) | ((nm_slot & 3) << 4);
+            int nbyte = (c64 << 6) | (((nm_slot & 3) << 4) ^ nmajor_half(krow));
             b_kofs[r] = krow;
             b_voff[r] = (n0 + (nbyte >> 1) < p.N) ? (unsigned)(krow * (int)p.ldb * 2 + nbyte) : kOob;
         }
@@ -743,105 +794,14 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     const int tr8_n = (((lane >> 4) & 1) << 4) + ((lane & 1) << 3);         // n offset within the 32 of a fragment
     const int tr8_half = lane >> 5;
 
-    f32x16 acc[FM][FN];
+    typedef typename std::conditional<S16, f32x4, f32x16>::type AccV;
+    AccV acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    auto read_a = [&](const char* sa, int ks, Frag<CH> (&af)[FM]) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            int row = wm * WTM + i * 32 + frag_row;
-#pragma unroll
-            for (int c = 0; c < CH; ++c)
-                af[i].c[c] = *(const short8v*)(sa + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
-        }
-    };
-    auto read_b = [&](const char* sb, int ks, Frag<CH> (&bf)[FN]) {
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            if (TRANS_B) {
-                int row = wn * WTN + j * 32 + frag_row;
-#pragma unroll
-                for (int c = 0; c < CH; ++c)
-                    bf[j].c[c] = *(const short8v*)(sb + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
-            } else if (E4) {
-                // column n = lane%32, k = 8 ks + 4 (lane/32) + e for e = 0..3: four 4-byte reads
-                const int nbyte = (wn * WTN + j * 32 + frag_row) * 4;
-                const char* r0 = sb + (ks * 8 + frag_kc * 4) * (BN * 4) + ((((nbyte >> 7) ^ frag_kc)) << 7) + (nbyte & 127);
-                int4v w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = *(const int*)(r0 + e * (BN * 4));
-                bf[j].c[0] = __builtin_bit_cast(short8v, w);
-            } else if (E8) {
-                // a lane's fragment: 16*CH consecutive k of column n = lane%32, half lane/32 of the step
-                const int nb = wn * WTN + j * 32 + tr8_n;
-                const int kbase = (ks * 2 + tr8_half) * (16 * CH) + tr8_row;
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    const char* r0 = sb + (kbase + c * 16) * BN + ((((nb >> 4) ^ tr8_row)) << 4) + (nb & 15);
-                    int2v lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0));
-                    int2v hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0 + 8 * BN));
-                    int4v w = {lo[0], lo[1], hi[0], hi[1]};
-                    bf[j].c[c] = __builtin_bit_cast(short8v, w);
-                }
-            } else {
-                int nbyte = (wn * WTN + j * 32) * 2 + tr_nbyte;
-                int k = ks * 16 + tr_k;
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k, nbyte)));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k + 4, nbyte)));
-                bf[j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-        }
-    };
-
-    // Fragments are double-buffered in registers across k16 steps AND across
-    // k-tiles: the reads of step ks+1 are issued before the MFMAs of step ks,
-    // and the first fragments of the next k-tile are read (after the barrier
-    // that publishes its stage) underneath the MFMAs of this tile's last step.
-    Frag<CH> af[2][FM], bf[2][FN];
-    auto mfma_step = [&](int cur) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
-    };
-    // Same, with this wave's loads of the tile being fetched spread evenly between
-    // the MFMAs of the whole k-tile (one every GAP MFMAs) instead of issued in one
-    // burst: a burst fills the memory pipeline's queue and stalls the wave in front
-    // of its MFMAs.  EARLY of the LOADS pieces are issued before the wait+barrier of
-    // the k-tile, the rest under its last MFMA group.
-    constexpr int MFMA_PER_TILE = KSUB * FM * FN;
-    constexpr int MFMA_BEFORE_WAIT = (KSUB - 1) * FM * FN;
-    // with two stages the tile being fetched is the very next one: everything goes before the wait
-    constexpr int SPAN = NSTAGE >= 3 ? MFMA_PER_TILE : MFMA_BEFORE_WAIT;
-    // piece r is issued right after MFMA number r*SPAN/LOADS of the k-tile
-    constexpr int EARLY = (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN < LOADS
-                              ? (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN : LOADS;
-    static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
-    auto mfma_step_loading = [&](int cur, int ks) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
-                const int idx = (ks * FM + i) * FN + j;         // MFMA number within the k-tile
-#pragma unroll
-                for (int r = 0; r < LOADS; ++r) {
-                    if ((r * SPAN) / LOADS == idx) {
-                        issue_piece(r, TailNo{});
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            }
-    };
-    static_assert(KSUB % 2 == 0, "fragment buffer parity assumes an even number of k16 steps");
+            for (int e = 0; e < (S16 ? 4 : 16); ++e) acc[i][j][e] = 0.0f;
 
     // Wait until at most `newer` whole k-tiles of this wave's loads are still in
     // flight (loads complete in order, so everything older has landed).
@@ -854,45 +814,17 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         }
     };
 
-    // One k-tile.  have_next: publish the next tile's stage (wait for this
-    // wave's pieces, barrier) and start reading it under the last MFMA group.
-    // NEWER >= 0: compile-time count of younger k-tiles in flight; -1: `newer_rt`.
-    auto tile_body = [&](int stage, int next_stage, bool have_next, auto newer_tag, int newer_rt, auto spread_tag) {
-        constexpr int NEWER = decltype(newer_tag)::value;
-        constexpr bool SPREAD = decltype(spread_tag)::value;
-        const char* sa = lds + stage * STAGE;
-        const char* sb = sa + A_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < KSUB - 1; ++ks) {
-            read_a(sa, ks + 1, af[(ks + 1) & 1]);
-            read_b(sb, ks + 1, bf[(ks + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
-            if (tmap.prio) __builtin_amdgcn_s_setprio(2);
-            if (SPREAD) mfma_step_loading(ks & 1, ks); else mfma_step(ks & 1);
-            if (tmap.prio) __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (have_next) {
-            // steady state: NEWER-1 whole younger tiles plus the EARLY pieces just issued may stay in flight
-            if (NEWER >= 0) wait_vmcnt<(SPREAD && NSTAGE >= 3 ? (NEWER >= 1 ? NEWER - 1 : 0) * LOADS + EARLY : (NEWER >= 0 ? NEWER : 0) * LOADS)>();
-            else wait_newer(newer_rt);
-            __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
-            const char* na = lds + next_stage * STAGE;
-            read_a(na, 0, af[0]);
-            read_b(na + A_BYTES, 0, bf[0]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (tmap.prio) __builtin_amdgcn_s_setprio(2);
-        if (SPREAD) mfma_step_loading((KSUB - 1) & 1, KSUB - 1); else mfma_step((KSUB - 1) & 1);
-        if (tmap.prio) __builtin_amdgcn_s_setprio(0);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
     // ---- main loop: NSTAGE LDS stages; the loads of k-tiles t+1 .. t+NSTAGE-1
     // are in flight while k-tile t is multiplied; one barrier per k-tile.
+    // prime(): first fragment reads of k-tile 0; run_tile(...): one k-tile (see tile_body).
     const int KT = (p.K + BK - 1) / BK;       // k-tiles
     const int KF = p.K / BK;                  // of which full
-    if (KT > 0) {
+    // pairs_tag true: the steady state runs k-tiles in pairs and tells run_tile which of the pair
+    // it is (phase 1, 2; 0 = a tile on its own), for pipelines whose register buffers alternate
+    // from one tile to the next.
+    auto main_loop = [&](auto&& prime, auto&& run_tile, auto pairs_tag) {
+        constexpr bool PAIRS = decltype(pairs_tag)::value;
+        if (KT <= 0) return;
         int issued = 0;                        // k-tiles whose loads have been issued
         int slot_in = 0;                       // stage the next issued tile goes to
         auto issue_next = [&](auto tail_tag) {
@@ -905,29 +837,410 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         }
         wait_newer(issued - 1);
         __syncthreads();
-        read_a(lds, 0, af[0]);
-        read_b(lds + A_BYTES, 0, bf[0]);
+        prime();
         int kt = 0, slot = 0;
         // steady state: every issued tile is full, NSTAGE-2 younger tiles stay in flight
-        for (; issued < KF; ++kt) {
+        auto steady_tile = [&](auto phase_tag) {
             begin_tile(issued * BK, slot_in);          // its loads are issued between the MFMAs
             ++issued;
             slot_in = (slot_in + 1 == NSTAGE) ? 0 : slot_in + 1;
             const int nslot = (slot + 1 == NSTAGE) ? 0 : slot + 1;
-            tile_body(slot, nslot, true, IntTag<NSTAGE - 2>{}, 0, BoolTag<true>{});
+            run_tile(slot, nslot, true, IntTag<NSTAGE - 2>{}, 0, BoolTag<true>{}, phase_tag);
             slot = nslot;
+            ++kt;
+        };
+        if (PAIRS) {
+            while (issued + 1 < KF) {
+                steady_tile(IntTag<1>{});
+                steady_tile(IntTag<2>{});
+            }
         }
+        while (issued < KF) steady_tile(IntTag<0>{});
         // drain: a possibly ragged last tile, then nothing left to issue
         for (; kt < KT; ++kt) {
             if (issued < KT) issue_next(TailYes{});
             const int nslot = (slot + 1 == NSTAGE) ? 0 : slot + 1;
-            tile_body(slot, nslot, kt + 1 < KT, IntTag<-1>{}, issued - (kt + 2), BoolTag<false>{});
+            run_tile(slot, nslot, kt + 1 < KT, IntTag<-1>{}, issued - (kt + 2), BoolTag<false>{}, IntTag<0>{});
             slot = nslot;
+        }
+    };
+
+    if constexpr (!S16) {
+        auto read_a = [&](const char* sa, int ks, Frag<CH> (&af)[FM]) {
+    #pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                int row = wm * WTM + i * 32 + frag_row;
+    #pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    af[i].c[c] = *(const short8v*)(sa + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
+            }
+        };
+        auto read_b = [&](const char* sb, int ks, Frag<CH> (&bf)[FN]) {
+    #pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                if (TRANS_B) {
+                    int row = wn * WTN + j * 32 + frag_row;
+    #pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        bf[j].c[c] = *(const short8v*)(sb + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
+                } else if (E4) {
+                    // column n = lane%32, k = 8 ks + 4 (lane/32) + e for e = 0..3: four 4-byte reads
+                    const int nbyte = (wn * WTN + j * 32 + frag_row) * 4;
+                    const char* r0 = sb + (ks * 8 + frag_kc * 4) * (BN * 4) + ((((nbyte >> 7) ^ frag_kc)) << 7) + (nbyte & 127);
+                    int4v w;
+    #pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = *(const int*)(r0 + e * (BN * 4));
+                    bf[j].c[0] = __builtin_bit_cast(short8v, w);
+                } else if (E8) {
+                    // a lane's fragment: 16*CH consecutive k of column n = lane%32, half lane/32 of the step
+                    const int nb = wn * WTN + j * 32 + tr8_n;
+                    const int kbase = (ks * 2 + tr8_half) * (16 * CH) + tr8_row;
+    #pragma unroll
+                    for (int c = 0; c < CH; ++c) {
+                        const char* r0 = sb + (kbase + c * 16) * BN + ((((nb >> 4) ^ tr8_row)) << 4) + (nb & 15);
+                        int2v lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0));
+                        int2v hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0 + 8 * BN));
+                        int4v w = {lo[0], lo[1], hi[0], hi[1]};
+                        bf[j].c[c] = __builtin_bit_cast(short8v, w);
+                    }
+                } else {
+                    int nbyte = (wn * WTN + j * 32) * 2 + tr_nbyte;
+                    int k = ks * 16 + tr_k;
+                    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k, nbyte)));
+                    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k + 4, nbyte)));
+                    bf[j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+        };
+
+        // Fragments are double-buffered in registers across k16 steps AND across
+        // k-tiles: the reads of step ks+1 are issued before the MFMAs of step ks,
+        // and the first fragments of the next k-tile are read (after the barrier
+        // that publishes its stage) underneath the MFMAs of this tile's last step.
+        Frag<CH> af[2][FM], bf[2][FN];
+        auto mfma_step = [&](int cur) {
+    #pragma unroll
+            for (int i = 0; i < FM; ++i)
+    #pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+        };
+        // Same, with this wave's loads of the tile being fetched spread evenly between
+        // the MFMAs of the whole k-tile (one every GAP MFMAs) instead of issued in one
+        // burst: a burst fills the memory pipeline's queue and stalls the wave in front
+        // of its MFMAs.  EARLY of the LOADS pieces are issued before the wait+barrier of
+        // the k-tile, the rest under its last MFMA group.
+        constexpr int MFMA_PER_TILE = KSUB * FM * FN;
+        constexpr int MFMA_BEFORE_WAIT = (KSUB - 1) * FM * FN;
+        // with two stages the tile being fetched is the very next one: everything goes before the wait
+        constexpr int SPAN = NSTAGE >= 3 ? MFMA_PER_TILE : MFMA_BEFORE_WAIT;
+        // piece r is issued right after MFMA number r*SPAN/LOADS of the k-tile
+        constexpr int EARLY = (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN < LOADS
+                                  ? (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN : LOADS;
+        static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
+        auto mfma_step_loading = [&](int cur, int ks) {
+    #pragma unroll
+            for (int i = 0; i < FM; ++i)
+    #pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+                    const int idx = (ks * FM + i) * FN + j;         // MFMA number within the k-tile
+    #pragma unroll
+                    for (int r = 0; r < LOADS; ++r) {
+                        if ((r * SPAN) / LOADS == idx) {
+                            issue_piece(r, TailNo{});
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                }
+        };
+        static_assert(KSUB % 2 == 0, "fragment buffer parity assumes an even number of k16 steps");
+
+        // One k-tile.  have_next: publish the next tile's stage (wait for this
+        // wave's pieces, barrier) and start reading it under the last MFMA group.
+        // NEWER >= 0: compile-time count of younger k-tiles in flight; -1: `newer_rt`.
+        auto tile_body = [&](int stage, int next_stage, bool have_next, auto newer_tag, int newer_rt, auto spread_tag) {
+            constexpr int NEWER = decltype(newer_tag)::value;
+            constexpr bool SPREAD = decltype(spread_tag)::value;
+            const char* sa = lds + stage * STAGE;
+            const char* sb = sa + A_BYTES;
+    #pragma unroll
+            for (int ks = 0; ks < KSUB - 1; ++ks) {
+                read_a(sa, ks + 1, af[(ks + 1) & 1]);
+                read_b(sb, ks + 1, bf[(ks + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
+                if (PRIO) __builtin_amdgcn_s_setprio(2);
+                if (SPREAD) mfma_step_loading(ks & 1, ks); else mfma_step(ks & 1);
+                if (PRIO) __builtin_amdgcn_s_setprio(0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (have_next) {
+                // steady state: NEWER-1 whole younger tiles plus the EARLY pieces just issued may stay in flight
+                if (NEWER >= 0) wait_vmcnt<(SPREAD && NSTAGE >= 3 ? (NEWER >= 1 ? NEWER - 1 : 0) * LOADS + EARLY : (NEWER >= 0 ? NEWER : 0) * LOADS)>();
+                else wait_newer(newer_rt);
+                __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
+                const char* na = lds + next_stage * STAGE;
+                read_a(na, 0, af[0]);
+                read_b(na + A_BYTES, 0, bf[0]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (PRIO) __builtin_amdgcn_s_setprio(2);
+            if (SPREAD) mfma_step_loading((KSUB - 1) & 1, KSUB - 1); else mfma_step((KSUB - 1) & 1);
+            if (PRIO) __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        main_loop([&]() { read_a(lds, 0, af[0]); read_b(lds + A_BYTES, 0, bf[0]); },
+                  [&](int stage, int next_stage, bool have_next, auto newer_tag, int newer_rt, auto spread_tag, auto) {
+                      tile_body(stage, next_stage, have_next, newer_tag, newer_rt, spread_tag);
+                  }, BoolTag<false>{});
+    } else {
+        // ---- 16x16 blocks.  A k32 step of the wave tile is split into two halves of its rows: the
+        // pipeline step s = 2 kq + h multiplies rows half h of k32-step kq.  A fragments are
+        // double-buffered per step, B fragments per k32 step (both halves use them), so only
+        // half of the A fragments of a step are live at a time.
+        constexpr int KQ = BK / 32;                // k32 steps per k-tile
+        constexpr int NSTEP = 2 * KQ;
+        constexpr int FMH = FM / 2;                // A fragments (16 rows each) per half
+        static_assert(FM % 2 == 0, "wave tile rows must split into two halves of 16-row blocks");
+        const int f16_row = lane & 15, f16_kc = lane >> 4;
+        // transposing read: 16-lane block q covers k rows 8q..8q+3 (second read: +4); lane -> row (lane%16)/4, n piece lane%4
+        const int t16_k = ((lane & 15) >> 2) + ((lane >> 4) << 3);
+        const int t16_nbyte = (lane & 3) * 8;
+        short8v af[2][FMH], bf[2][FN];
+        // byte offset of this lane's first transposing read for B block j of k32 step 0; the second
+        // read (k + 4) and further k32 steps (k + 32 kq) keep the swizzle terms: constant offsets
+        int b_off[FN];
+#pragma unroll
+        for (int j = 0; j < FN; ++j) b_off[j] = nmajor_offset<BN>(t16_k, (wn * WTN + j * 16) * 2 + t16_nbyte);
+        auto read_a = [&](const char* sa, int s, short8v (&dst)[FMH]) {
+            const int kq = s >> 1, h = s & 1;
+#pragma unroll
+            for (int i = 0; i < FMH; ++i) {
+                const int row = wm * WTM + (h * FMH + i) * 16 + f16_row;
+                dst[i] = *(const short8v*)(sa + kmajor_offset<BK, true>(row, kq * 4 + f16_kc));
+            }
+        };
+        auto read_b = [&](const char* sb, int kq, short8v (&dst)[FN]) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                if (TRANS_B) {
+                    const int row = wn * WTN + j * 16 + f16_row;
+                    dst[j] = *(const short8v*)(sb + kmajor_offset<BK, true>(row, kq * 4 + f16_kc));
+                } else {
+                    const char* r0 = sb + b_off[j] + kq * 32 * (BN * 2);
+                    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, r0));
+                    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, r0 + 4 * (BN * 2)));
+                    dst[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+        };
+        constexpr int MFMA_PER_TILE = NSTEP * FMH * FN;
+        constexpr int MFMA_BEFORE_WAIT = (NSTEP - 1) * FMH * FN;
+        constexpr int SPAN = NSTAGE >= 3 ? MFMA_PER_TILE : MFMA_BEFORE_WAIT;
+        constexpr int EARLY = (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN < LOADS
+                                  ? (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN : LOADS;
+        static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
+        // the MFMAs of step s; SPREAD: this wave's loads of the tile being fetched are issued between them
+        auto mfma_step = [&](int s, int bcur, auto spread_tag) {
+            constexpr bool SPREAD = decltype(spread_tag)::value;
+            const int h = s & 1;
+#pragma unroll
+            for (int i = 0; i < FMH; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    acc[h * FMH + i][j] = MfmaOp16<T>::run(bf[bcur][j], af[s & 1][i], acc[h * FMH + i][j]);
+                    if (SPREAD) {
+                        const int idx = (s * FMH + i) * FN + j;         // MFMA number within the k-tile
+#pragma unroll
+                        for (int r = 0; r < LOADS; ++r) {
+                            if ((r * SPAN) / LOADS == idx) {
+                                issue_piece(r, TailNo{});
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    }
+                }
+        };
+        if constexpr (ADBL) {
+            // ---- A staged 64 deep.  LDS: two pieces of A ([BM][64 k], the 64-deep k-major layout), then
+            // four stages of B.  k-tile t reads half t%2 of A piece (t/2)%2 and B stage t%4.  While an even
+            // tile t is multiplied the wave issues A(t+2, t+3) (its piece was last read by tile t-1) and
+            // B(t+3); while an odd tile, B(t+3) only.  The A loads of a tile come first in issue order.
+            constexpr int AP_BYTES = BM * 128;
+            constexpr int B_REGION = 2 * AP_BYTES;
+            static_assert(B_REGION + 4 * B_BYTES == NSTAGE * STAGE, "same LDS footprint as the plain ring");
+            auto a_lds = [&](int t) { return ((t >> 1) & 1) * AP_BYTES; };
+            auto b_lds = [&](int t) { return B_REGION + (t & 3) * B_BYTES; };
+            int4v ad_ra = make_rsrc(a_tile), ad_rb = make_rsrc(b_tile);
+            unsigned ad_sa = 0, ad_sb = 0;
+            int ad_ka = 0, ad_kb = 0;
+            auto begin_a = [&](int k0, int dst) { ad_ka = k0; ad_sa = lds_base + dst; ad_ra = make_rsrc(a_tile + (int64_t)k0 * 2); };
+            auto begin_b = [&](int k0, int dst) { ad_kb = k0; ad_sb = lds_base + dst; ad_rb = make_rsrc(b_tile + (int64_t)k0 * p.ldb * 2); };
+            auto issue_a = [&](int r, auto tail_tag) {
+                unsigned off = a_voff[r];
+                if (decltype(tail_tag)::value && ad_ka + a_kofs[r] >= p.K) off = kOob;
+                dma16(ad_ra, ad_sa + (wave * CA + r) * 1024, off);
+            };
+            auto issue_b = [&](int rb, auto tail_tag) {
+                unsigned off = b_voff[rb];
+                if (decltype(tail_tag)::value && ad_kb + b_kofs[rb] >= p.K) off = kOob;
+                dma16(ad_rb, ad_sb + (wave * CB + rb) * 1024, off);
+            };
+            // A fragments of rows half `rh` from half `h` of the piece at sa
+            auto read_a2 = [&](const char* sa, int h, int rh, short8v (&dst)[FMH]) {
+#pragma unroll
+                for (int i = 0; i < FMH; ++i) {
+                    const int row = wm * WTM + (rh * FMH + i) * 16 + f16_row;
+                    dst[i] = *(const short8v*)(sa + kmajor_offset<64, true>(row, h * 4 + f16_kc));
+                }
+            };
+            constexpr int NT = 2 * FMH * FN;           // MFMAs per k-tile
+            constexpr int NB = FMH * FN;               // of which before the barrier
+            // L loads are spread over the tile: load r right after MFMA number r NT / L; pieces before the barrier:
+            auto early_of = [](int L) { return L == 0 ? 0 : ((NB * L + NT - 1) / NT < L ? (NB * L + NT - 1) / NT : L); };
+            auto mfma2 = [&](int st, int bcur, auto l_tag) {
+                constexpr int L = decltype(l_tag)::value;     // CA + CB: A pieces then B pieces; CB: B pieces; 0: none
+#pragma unroll
+                for (int i = 0; i < FMH; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        acc[st * FMH + i][j] = MfmaOp16<T>::run(bf[bcur][j], af[st][i], acc[st * FMH + i][j]);
+                        const int idx = (st * FMH + i) * FN + j;
+#pragma unroll
+                        for (int r = 0; r < L; ++r) {
+                            if ((r * NT) / L == idx) {
+                                if (L > CB && r < CA) issue_a(r, TailNo{}); else issue_b(L > CB ? r - CA : r, TailNo{});
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    }
+            };
+            auto wait_rt = [&](int n) {
+                if (n >= CA + CB) wait_vmcnt<CA + CB>(); else if (n >= CA) wait_vmcnt<CA>();
+                else if (n >= CB) wait_vmcnt<CB>(); else wait_vmcnt<0>();
+            };
+            // one k-tile t (half h = t % 2).  PHASE as above; L > 0: steady state with L loads spread; else
+            // `burst` loads were issued at the start of the tile
+            auto tile2 = [&](int t, int h, bool have_next, auto phase_tag, auto l_tag, int burst) {
+                constexpr int PHASE = decltype(phase_tag)::value;
+                constexpr int L = decltype(l_tag)::value;
+                constexpr int P = PHASE == 2 ? 1 : 0;
+                const char* sa = lds + a_lds(t);
+                read_a2(sa, h, 1, af[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (PRIO) __builtin_amdgcn_s_setprio(2);
+                mfma2(0, P, l_tag);
+                if (PRIO) __builtin_amdgcn_s_setprio(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (have_next) {
+                    // steady state: this tile's later pieces and the B pieces issued after the A pieces
+                    // that the next tile needs may stay in flight
+                    if (L > 0) wait_vmcnt<CB + early_of(L)>(); else wait_rt(burst);
+                    __syncthreads();
+                    read_a2(lds + a_lds(t + 1), h ^ 1, 0, af[0]);
+                    read_b(lds + b_lds(t + 1), 0, bf[P ^ 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (PRIO) __builtin_amdgcn_s_setprio(2);
+                mfma2(1, P, l_tag);
+                if (PRIO) __builtin_amdgcn_s_setprio(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (PHASE == 0 && have_next) {
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) bf[0][j] = bf[1][j];
+                }
+            };
+            if (KT > 0) {
+                begin_a(0, a_lds(0));
+#pragma unroll
+                for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                for (int t = 0; t < 3 && t < KT; ++t) {
+                    begin_b(t * BK, b_lds(t));
+#pragma unroll
+                    for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                }
+                wait_vmcnt<0>();
+                __syncthreads();
+                read_a2(lds + a_lds(0), 0, 0, af[0]);
+                read_b(lds + b_lds(0), 0, bf[0]);
+                int t = 0;
+                for (; t + 4 < KF; t += 2) {
+                    begin_a((t + 2) * BK, a_lds(t + 2));
+                    begin_b((t + 3) * BK, b_lds(t + 3));
+                    tile2(t, 0, true, IntTag<1>{}, IntTag<CA + CB>{}, 0);
+                    begin_b((t + 4) * BK, b_lds(t + 4));
+                    tile2(t + 1, 1, true, IntTag<2>{}, IntTag<CB>{}, 0);
+                }
+                for (; t < KT; ++t) {
+                    int burst = 0;
+                    if (!(t & 1) && t + 2 < KT) {
+                        begin_a((t + 2) * BK, a_lds(t + 2));
+#pragma unroll
+                        for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                        burst += CA;
+                    }
+                    if (t + 3 < KT) {
+                        begin_b((t + 3) * BK, b_lds(t + 3));
+#pragma unroll
+                        for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                        burst += CB;
+                    }
+                    tile2(t, t & 1, t + 1 < KT, IntTag<0>{}, IntTag<0>{}, burst);
+                }
+            }
+        } else {
+            // B fragments of k32 step kq of a tile that starts from buffer P live in bf[(P + kq) % 2]; the
+            // next tile's first ones are read into bf[(P + KQ) % 2] while this tile's last step still
+            // multiplies.  With an odd number of k32 steps per tile the buffers swap roles from tile to
+            // tile: the steady state runs tiles in pairs (PHASE 1 starts from buffer 0, PHASE 2 from
+            // buffer 1); a tile on its own (PHASE 0) starts from buffer 0 and moves the next tile's
+            // fragments back there (register copies) once its last MFMAs have been issued.
+            auto tile_body = [&](int stage, int next_stage, bool have_next, auto newer_tag, int newer_rt, auto spread_tag,
+                                 auto phase_tag) {
+                constexpr int NEWER = decltype(newer_tag)::value;
+                constexpr bool SPREAD = decltype(spread_tag)::value;
+                constexpr int PHASE = decltype(phase_tag)::value;
+                constexpr int P = (PHASE == 2 && (KQ & 1)) ? 1 : 0;
+                const char* sa = lds + stage * STAGE;
+                const char* sb = sa + A_BYTES;
+    #pragma unroll
+                for (int s = 0; s < NSTEP - 1; ++s) {
+                    read_a(sa, s + 1, af[(s + 1) & 1]);
+                    if (((s + 1) & 1) == 0) read_b(sb, (s + 1) >> 1, bf[(P + ((s + 1) >> 1)) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
+                    if (PRIO) __builtin_amdgcn_s_setprio(2);
+                    mfma_step(s, (P + (s >> 1)) & 1, spread_tag);
+                    if (PRIO) __builtin_amdgcn_s_setprio(0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (have_next) {
+                    if (NEWER >= 0) wait_vmcnt<(SPREAD && NSTAGE >= 3 ? (NEWER >= 1 ? NEWER - 1 : 0) * LOADS + EARLY : (NEWER >= 0 ? NEWER : 0) * LOADS)>();
+                    else wait_newer(newer_rt);
+                    __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
+                    const char* na = lds + next_stage * STAGE;
+                    read_a(na, 0, af[0]);
+                    read_b(na + A_BYTES, 0, bf[(P + KQ) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (PRIO) __builtin_amdgcn_s_setprio(2);
+                mfma_step(NSTEP - 1, (P + KQ - 1) & 1, spread_tag);
+                if (PRIO) __builtin_amdgcn_s_setprio(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (PHASE == 0 && (KQ & 1) && have_next) {
+    #pragma unroll
+                    for (int j = 0; j < FN; ++j) bf[0][j] = bf[1][j];
+                }
+            };
+            main_loop([&]() { read_a(lds, 0, af[0]); read_b(lds + A_BYTES, 0, bf[0]); }, tile_body, BoolTag<(KQ & 1) != 0>{});
         }
     }
 
     // ---- epilogue in registers, then one coalesced store ---------------------
-    // Lane holds, for block (i,j): row m = lane%32, columns 8*g + 4*(lane/32) + 0..3.
+    // Lane holds, for 32x32 block (i,j): row m = lane%32, columns 8*g + 4*(lane/32) + 0..3
+    // (16x16 blocks: row lane%16, columns 4*(lane/16) + 0..3).
     // alpha/bias/activation and the rounding to the output type happen on the
     // accumulator registers.  The rounded pieces then take one trip through this
     // wave's own slice of LDS (free after the k loop) purely to change which lane
@@ -938,7 +1251,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                   : (p.epi == EPI_GELU_TANH || p.epi == EPI_BIAS_GELU_TANH) ? 2 : 0;
     const bool out_f32 = p.out_dtype == DT_F32;
     char* wlds = lds + wave * ((NSTAGE * STAGE) / NW);
-    EpiCtx<TO, FM, FN, WTM, WTN, (NSTAGE * STAGE) / NW> ctx{p, acc, wlds, m0 + wm * WTM, n0 + wn * WTN, lane,
+    EpiCtx<TO, AccV, FM, FN, WTM, WTN, (NSTAGE * STAGE) / NW> ctx{p, acc, wlds, m0 + wm * WTM, n0 + wn * WTN, lane,
                                                          (int64_t)b * p.stride_c};
     if constexpr (sizeof(T) == 1 && MfmaOp<T>::kChunks == 1) {      // int8 operands
         ctx.run_quant();

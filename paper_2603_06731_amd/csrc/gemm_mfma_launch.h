@@ -21,13 +21,17 @@ static const MfmaConfig kMfmaConfigs[] = {
     {2, 128, 128, 32, 2, 2, 3, "mfma_128x128x32_w2x2_s3_occ3"},
     {3, 256, 256, 32, 2, 4, 4, "mfma_256x256x32_w2x4_s4"},
     {4, 256, 256, 64, 2, 4, 2, "mfma_256x256x64_w2x4_s2"},
+    {5, 256, 256, 32, 2, 4, 4, "mfma16_256x256x32_w2x4_s4"},        // 16x16x32 MFMA blocks (16-bit types)
+    {6, 128, 256, 32, 1, 4, 3, "mfma16_128x256x32_w1x4_s3_occ2"},
+    {7, 256, 256, 32, 2, 4, 4, "mfma16_256x256x32_w2x4_s4_a64"},    // A staged 64 deep (plain matrices)
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
-template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC>
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC, int MI = 32,
+          bool ADBL = false>
 hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     constexpr int LDS_BYTES = NSTAGE * (BM * BK * 2 + BN * BK * 2);
-    auto kern = gemm_mfma_kernel<T, TO, BM, BN, BK, WM, WN, MODE, NSTAGE, OCC>;
+    auto kern = gemm_mfma_kernel<T, TO, BM, BN, BK, WM, WN, MODE, NSTAGE, OCC, MI, ADBL>;
     static std::atomic<unsigned> attr_done{0};      // bit per device
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -47,9 +51,6 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     tm.total = (int)total;
     tm.group_m = group_m < 1 ? 1 : group_m;
     tm.xcds = 8;
-    // raised wave priority around the MFMA groups: measured +1..2.5 % for one 256x256 workgroup per CU
-    // and for the convolution, -1 % for two 128x256 workgroups per CU on plain matrices
-    tm.prio = (BM == 256 || MODE == MODE_CONV) ? 1 : 0;
     // hipLaunchKernel reports this launch's own status; the per-thread "last error"
     // may hold an unrelated earlier failure of another library
     Problem pa = p;
@@ -57,18 +58,18 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     return hipLaunchKernel((const void*)kern, dim3((unsigned)total), dim3(WM * WN * 64), args, LDS_BYTES, stream);
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1, int MI = 32, bool ADBL = false>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
     if (p.is_conv && p.conv.transposed) {
         // the transposed form is built for the two configurations the dispatcher picks
         if constexpr ((BM == 128 && BN == 256 && BK == 32) || (BM == 128 && BN == 128 && BK == 64))
-            return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONVT, NSTAGE, OCC>(p, stream, group_m);
+            return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONVT, NSTAGE, OCC, MI>(p, stream, group_m);
         else
             return hipErrorInvalidValue;
     }
-    if (p.is_conv) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC>(p, stream, group_m);
-    if (p.trans_b) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC>(p, stream, group_m);
-    return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC>(p, stream, group_m);
+    if (p.is_conv) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC, MI>(p, stream, group_m);
+    if (p.trans_b) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC, MI>(p, stream, group_m);
+    return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC, MI, ADBL>(p, stream, group_m);
 }
 
 // PBK_CFG_MASK (build-time, development only): bit i set = compile configuration i.
@@ -85,6 +86,9 @@ hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int grou
     PBK_CASE(2, 128, 128, 32, 2, 2, 3, 3)
     PBK_CASE(3, 256, 256, 32, 2, 4, 4)
     PBK_CASE(4, 256, 256, 64, 2, 4, 2)
+    PBK_CASE(5, 256, 256, 32, 2, 4, 4, 1, 16)
+    PBK_CASE(6, 128, 256, 32, 1, 4, 3, 2, 16)
+    PBK_CASE(7, 256, 256, 32, 2, 4, 4, 1, 16, true)
     default: return hipErrorInvalidValue;
     }
 }

@@ -11,7 +11,7 @@ import pbk_testlib as T
 pytestmark = pytest.mark.gpu
 
 BF16, F16, F32 = wl.DTYPE_BF16, wl.DTYPE_F16, wl.DTYPE_F32
-MFMA_CONFIGS = list(range(5))
+MFMA_CONFIGS = list(range(7))
 
 
 def tol_for(w):
@@ -133,7 +133,7 @@ CONV_SMALL = [
 
 
 @pytest.mark.parametrize("case", CONV_SMALL)
-@pytest.mark.parametrize("cfg", [None, 0, 1, 2, 3, 4])
+@pytest.mark.parametrize("cfg", [None] + MFMA_CONFIGS)
 def test_conv_small_mfma(case, cfg):
     n, H, W, Cin, Cout, KH, KW, stride, pad, dil = case
     w = wl.Workload("conv_s", "conv", BF16, BF16, C.EPI_BIAS_RELU, n=n, H=H, W=W, Cin=Cin, Cout=Cout,
