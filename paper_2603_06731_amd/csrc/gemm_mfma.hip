@@ -46,24 +46,23 @@ bool mfma_preferred(const Problem& p) {
     return p.M >= 128 && p.N >= 128 && t >= 64;
 }
 
+// 16-bit operands.  Configurations 5-7 use the 16x16x32 MFMA blocks (measured against their
+// 32x32x16 twins 3, 0: 8192^3 786 against 816 us, 3x3 convolution 144 against 151 us, the
+// store-bound attention-score product equal); 7 also stages A 64 deep (762 us).
 static int choose_config(const Problem& p) {
-    // 128x256 tiles, two workgroups of four waves per CU: the two barrier domains
-    // fill each other's bubbles
     long long t = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256) * p.batch;
+    long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
     if (p.trans_b && !p.is_conv && p.K >= 1024) {
-        // k-major B, long contraction: the 128x256 configuration is slow there (measured 1044 us
-        // against 874 us for 256x256x32 on 8192^3); short ones (K = 128: 197 us against 217 us)
-        // follow the general rule below
-        long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
-        if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 3;
+        // k-major B, long contraction: the 128x256 configurations are slow there (1044 us against
+        // 874 us for 256x256x32 on 8192^3); short ones (K = 128) follow the general rule below
+        if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 5;
         return 1;
     }
-    // Long contractions over many tiles: one 256x256x32 workgroup per CU with a 4-stage ring
-    // (measured on 8192^3 and 8192x14336x4096: 850 / 834 us against 912 / 876 us for configuration 0).
-    // Short contractions (store-dominated) and convolutions stay with two 128x256 workgroups per CU.
-    long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
-    if (!p.is_conv && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 1024) return 3;
-    if (p.M >= 128 && p.N >= 256 && t >= 256) return 0;
+    // Long contractions over many tiles: one 256x256x32 workgroup per CU with a 4-stage ring.
+    // Short contractions (store-dominated) and convolutions: two 128x256 workgroups per CU, whose
+    // two barrier domains fill each other's bubbles.
+    if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 1024) return 7;
+    if (p.M >= 128 && p.N >= 256 && t >= 256) return 6;
     return 1;
 }
 
@@ -86,7 +85,7 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
         return launch_mfma_int8(p, stream, c, gm);
     }
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
-    if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1) cfg = choose_config(p);   // only 0 and 1 are built
+    if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1 && cfg != 6) cfg = choose_config(p);   // the ones built
     if (fp8) {
         // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
         // only the 64-deep configurations are built for it

@@ -11,7 +11,7 @@ import pbk_testlib as T
 pytestmark = pytest.mark.gpu
 
 BF16, F16, F32 = wl.DTYPE_BF16, wl.DTYPE_F16, wl.DTYPE_F32
-MFMA_CONFIGS = list(range(7))
+MFMA_CONFIGS = list(range(8))
 
 
 def tol_for(w):
@@ -61,6 +61,22 @@ def test_matmul_bf16_mfma_configs(cfg, mnk):
     w = wl.Workload(f"mm_{m}x{n}x{k}", "matmul", BF16, BF16, C.EPI_BIAS_RELU, M=m, N=n, K=k,
                     dist_b=("normal", 1.0 / np.sqrt(k)), dist_bias=("normal", 0.5))
     check_full(w, force=f"mfma:{cfg}", expect_kernel="mfma")
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("k", [8, 40, 64, 72, 128, 136, 168, 200, 264, 328, 1096])
+def test_matmul_a_staged_64_deep_k_sweep(dtype, k):
+    """Configuration 7 stages A every other k-tile: prologue only, drain only, odd and even numbers
+    of k-tiles, ragged last tile, and enough tiles for the paired steady state."""
+    w = wl.Workload(f"mm_a64_k{k}", "matmul", dtype, dtype, C.EPI_BIAS, M=300, N=520, K=k,
+                    dist_b=("normal", 1.0 / np.sqrt(k)), dist_bias=("normal", 0.5))
+    check_full(w, force="mfma:7", expect_kernel="a64")
+
+
+def test_batched_on_a_staged_64_deep():
+    w = wl.Workload("bmm_a64", "batched", BF16, F32, C.EPI_NONE, alpha=0.5, batch=3, M=264, N=256, K=392,
+                    dist_b=("normal", 0.05))
+    check_full(w, force="mfma:7", expect_kernel="a64")
 
 
 @pytest.mark.parametrize("dtype", [BF16, F16])
