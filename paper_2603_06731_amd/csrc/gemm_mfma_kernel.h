@@ -1,17 +1,19 @@
-// MFMA contraction kernel for gfx950: 16-bit or FP8 inputs, fp32 accumulation.
+// MFMA contraction kernel for gfx950: 16-bit, 8-bit or fp32 inputs, fp32 (int32) accumulation.
 //
 // Structure (paper Sec. 4.3 multi-level tiling and fast buffers, Sec. 4.5
 // on-the-fly packing, Sec. 4.6 mapping to matrix units, App. A.2 overlap of
 // copy and compute), re-designed for CDNA4:
 //   workgroup tile BM x BN x BK  ->  WM x WN waves, each a (BM/WM) x (BN/WN)
-//   register tile of 32x32 MFMA blocks (v_mfma_f32_32x32x16 for 16-bit types,
-//   v_mfma_f32_32x32x64_f8f6f4 for FP8), accumulators live in registers for
-//   the whole K loop.
+//   register tile of MFMA blocks: 16x16 (v_mfma_f32_16x16x32, 16-bit types, the
+//   configurations the dispatcher picks) or 32x32 (v_mfma_f32_32x32x16 for 16-bit
+//   types, v_mfma_f32_32x32x64_f8f6f4 for FP8, v_mfma_i32_32x32x32_i8,
+//   v_mfma_f32_32x32x2_f32); accumulators live in registers for the whole K loop.
 //   Global -> LDS staging without passing through registers: every wave issues
 //   buffer_load_dwordx4 ... lds, each writing 64 x 16 bytes to 1 KiB of LDS.
 //   A ring of NSTAGE LDS stages: the loads of k-tiles t+1 .. t+NSTAGE-1 are in
 //   flight while k-tile t is multiplied; one barrier per k-tile; a wave's loads
-//   are spread between its MFMAs.  Pieces that lie outside the matrix
+//   are spread between its MFMAs.  One configuration stages A 64 deep every
+//   other k-tile instead, so that its loads move whole 128-byte lines.  Pieces that lie outside the matrix
 //   (rows beyond M, columns beyond N, k beyond K, convolution taps in the
 //   padding) are given an out-of-range buffer offset, for which the hardware
 //   writes zeros to LDS: partial tiles are zero-filled for free.
