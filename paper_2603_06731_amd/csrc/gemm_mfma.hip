@@ -61,7 +61,8 @@ static int choose_config(const Problem& p) {
     // Long contractions over many tiles: one 256x256x32 workgroup per CU with a 4-stage ring.
     // Short contractions (store-dominated) and convolutions: two 128x256 workgroups per CU, whose
     // two barrier domains fill each other's bubbles.
-    if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 1024) return 7;
+    // (K = 1024 / 2048: the two 128x256 workgroups are 2-5 % ahead; K = 4096 and 8192: 10 % behind)
+    if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 3072) return 7;
     if (p.M >= 128 && p.N >= 256 && t >= 256) return 6;
     return 1;
 }

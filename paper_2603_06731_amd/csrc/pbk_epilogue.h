@@ -19,7 +19,8 @@ __device__ __forceinline__ float gelu_tanh_f32(float t) {
     const float c = 0.7978845608028654f;
     float u = c * (t + 0.044715f * t * t * t);
     float e = __expf(2.0f * u);
-    float th = 1.0f - 2.0f / (e + 1.0f);
+    // hardware reciprocal (1 ulp) instead of an IEEE division: e = inf gives 0, e = 0 gives 1
+    float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
     return 0.5f * t * (1.0f + th);
 }
 
