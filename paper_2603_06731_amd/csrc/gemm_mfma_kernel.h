@@ -868,66 +868,78 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     };
 
     if constexpr (!S16) {
-        auto read_a = [&](const char* sa, int ks, Frag<CH> (&af)[FM]) {
+        // one fragment: A rows block i, B columns block j of k16 step ks
+        auto read_a1 = [&](const char* sa, int ks, int i) -> Frag<CH> {
+            Frag<CH> f;
+            int row = wm * WTM + i * 32 + frag_row;
     #pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                int row = wm * WTM + i * 32 + frag_row;
+            for (int c = 0; c < CH; ++c)
+                f.c[c] = *(const short8v*)(sa + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
+            return f;
+        };
+        auto read_b1 = [&](const char* sb, int ks, int j) -> Frag<CH> {
+            Frag<CH> f;
+            if (TRANS_B) {
+                int row = wn * WTN + j * 32 + frag_row;
     #pragma unroll
                 for (int c = 0; c < CH; ++c)
-                    af[i].c[c] = *(const short8v*)(sa + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
+                    f.c[c] = *(const short8v*)(sb + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
+            } else if (E4) {
+                // column n = lane%32, k = 8 ks + 4 (lane/32) + e for e = 0..3: four 4-byte reads
+                const int nbyte = (wn * WTN + j * 32 + frag_row) * 4;
+                const char* r0 = sb + (ks * 8 + frag_kc * 4) * (BN * 4) + ((((nbyte >> 7) ^ frag_kc)) << 7) + (nbyte & 127);
+                int4v w;
+    #pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = *(const int*)(r0 + e * (BN * 4));
+                f.c[0] = __builtin_bit_cast(short8v, w);
+            } else if (E8) {
+                // a lane's fragment: 16*CH consecutive k of column n = lane%32, half lane/32 of the step
+                const int nb = wn * WTN + j * 32 + tr8_n;
+                const int kbase = (ks * 2 + tr8_half) * (16 * CH) + tr8_row;
+    #pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const char* r0 = sb + (kbase + c * 16) * BN + ((((nb >> 4) ^ tr8_row)) << 4) + (nb & 15);
+                    int2v lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0));
+                    int2v hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0 + 8 * BN));
+                    int4v w = {lo[0], lo[1], hi[0], hi[1]};
+                    f.c[c] = __builtin_bit_cast(short8v, w);
+                }
+            } else {
+                int nbyte = (wn * WTN + j * 32) * 2 + tr_nbyte;
+                int k = ks * 16 + tr_k;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k, nbyte)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k + 4, nbyte)));
+                f.c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
+            return f;
+        };
+        auto read_a = [&](const char* sa, int ks, Frag<CH> (&af)[FM]) {
+    #pragma unroll
+            for (int i = 0; i < FM; ++i) af[i] = read_a1(sa, ks, i);
         };
         auto read_b = [&](const char* sb, int ks, Frag<CH> (&bf)[FN]) {
     #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                if (TRANS_B) {
-                    int row = wn * WTN + j * 32 + frag_row;
-    #pragma unroll
-                    for (int c = 0; c < CH; ++c)
-                        bf[j].c[c] = *(const short8v*)(sb + kmajor_offset<BK>(row, (ks * 2 + frag_kc) * CH + c));
-                } else if (E4) {
-                    // column n = lane%32, k = 8 ks + 4 (lane/32) + e for e = 0..3: four 4-byte reads
-                    const int nbyte = (wn * WTN + j * 32 + frag_row) * 4;
-                    const char* r0 = sb + (ks * 8 + frag_kc * 4) * (BN * 4) + ((((nbyte >> 7) ^ frag_kc)) << 7) + (nbyte & 127);
-                    int4v w;
-    #pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = *(const int*)(r0 + e * (BN * 4));
-                    bf[j].c[0] = __builtin_bit_cast(short8v, w);
-                } else if (E8) {
-                    // a lane's fragment: 16*CH consecutive k of column n = lane%32, half lane/32 of the step
-                    const int nb = wn * WTN + j * 32 + tr8_n;
-                    const int kbase = (ks * 2 + tr8_half) * (16 * CH) + tr8_row;
-    #pragma unroll
-                    for (int c = 0; c < CH; ++c) {
-                        const char* r0 = sb + (kbase + c * 16) * BN + ((((nb >> 4) ^ tr8_row)) << 4) + (nb & 15);
-                        int2v lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0));
-                        int2v hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(PBK_LDS_PTR(int2v, r0 + 8 * BN));
-                        int4v w = {lo[0], lo[1], hi[0], hi[1]};
-                        bf[j].c[c] = __builtin_bit_cast(short8v, w);
-                    }
-                } else {
-                    int nbyte = (wn * WTN + j * 32) * 2 + tr_nbyte;
-                    int k = ks * 16 + tr_k;
-                    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k, nbyte)));
-                    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        PBK_LDS_PTR(short4v, sb + nmajor_offset<BN>(k + 4, nbyte)));
-                    bf[j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-            }
+            for (int j = 0; j < FN; ++j) bf[j] = read_b1(sb, ks, j);
         };
+        static_assert(FM + FN <= FM * FN, "a step has at least as many MFMA groups as fragments to read under it");
 
         // Fragments are double-buffered in registers across k16 steps AND across
-        // k-tiles: the reads of step ks+1 are issued before the MFMAs of step ks,
-        // and the first fragments of the next k-tile are read (after the barrier
-        // that publishes its stage) underneath the MFMAs of this tile's last step.
+        // k-tiles: the reads of step ks+1 go, one fragment at a time, between the MFMAs
+        // of step ks (mid(k) runs after MFMA group k), and the first fragments of the
+        // next k-tile are read (after the barrier that publishes its stage) between the
+        // MFMAs of this tile's last step: the matrix pipe restarts right after the
+        // barrier instead of after a burst of reads.
         Frag<CH> af[2][FM], bf[2][FN];
-        auto mfma_step = [&](int cur) {
+        auto mfma_step = [&](int cur, auto&& mid) {
     #pragma unroll
             for (int i = 0; i < FM; ++i)
     #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                for (int j = 0; j < FN; ++j) {
                     acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+                    mid(i * FN + j);
+                }
         };
         // Same, with this wave's loads of the tile being fetched spread evenly between
         // the MFMAs of the whole k-tile (one every GAP MFMAs) instead of issued in one
@@ -942,12 +954,13 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         constexpr int EARLY = (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN < LOADS
                                   ? (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN : LOADS;
         static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
-        auto mfma_step_loading = [&](int cur, int ks) {
+        auto mfma_step_loading = [&](int cur, int ks, auto&& mid) {
     #pragma unroll
             for (int i = 0; i < FM; ++i)
     #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     acc[i][j] = MfmaOp<T>::run(bf[cur][j], af[cur][i], acc[i][j]);
+                    mid(i * FN + j);
                     const int idx = (ks * FM + i) * FN + j;         // MFMA number within the k-tile
     #pragma unroll
                     for (int r = 0; r < LOADS; ++r) {
@@ -970,11 +983,13 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             const char* sb = sa + A_BYTES;
     #pragma unroll
             for (int ks = 0; ks < KSUB - 1; ++ks) {
-                read_a(sa, ks + 1, af[(ks + 1) & 1]);
-                read_b(sb, ks + 1, bf[(ks + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
+                auto mid = [&](int k) {
+                    if (k < FM) af[(ks + 1) & 1][k] = read_a1(sa, ks + 1, k);
+                    else if (k < FM + FN) bf[(ks + 1) & 1][k - FM] = read_b1(sb, ks + 1, k - FM);
+                    if (k < FM + FN) __builtin_amdgcn_sched_barrier(0);
+                };
                 if (PRIO) __builtin_amdgcn_s_setprio(2);
-                if (SPREAD) mfma_step_loading(ks & 1, ks); else mfma_step(ks & 1);
+                if (SPREAD) mfma_step_loading(ks & 1, ks, mid); else mfma_step(ks & 1, mid);
                 if (PRIO) __builtin_amdgcn_s_setprio(0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -983,13 +998,16 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                 if (NEWER >= 0) wait_vmcnt<(SPREAD && NSTAGE >= 3 ? (NEWER >= 1 ? NEWER - 1 : 0) * LOADS + EARLY : (NEWER >= 0 ? NEWER : 0) * LOADS)>();
                 else wait_newer(newer_rt);
                 __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
-                const char* na = lds + next_stage * STAGE;
-                read_a(na, 0, af[0]);
-                read_b(na + A_BYTES, 0, bf[0]);
-                __builtin_amdgcn_sched_barrier(0);
             }
+            const char* na = lds + next_stage * STAGE;
+            auto mid_next = [&](int k) {
+                if (!have_next) return;
+                if (k < FM) af[0][k] = read_a1(na, 0, k);
+                else if (k < FM + FN) bf[0][k - FM] = read_b1(na + A_BYTES, 0, k - FM);
+                if (k < FM + FN) __builtin_amdgcn_sched_barrier(0);
+            };
             if (PRIO) __builtin_amdgcn_s_setprio(2);
-            if (SPREAD) mfma_step_loading((KSUB - 1) & 1, KSUB - 1); else mfma_step((KSUB - 1) & 1);
+            if (SPREAD) mfma_step_loading((KSUB - 1) & 1, KSUB - 1, mid_next); else mfma_step((KSUB - 1) & 1, mid_next);
             if (PRIO) __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
         };
@@ -1017,36 +1035,43 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
         int b_off[FN];
 #pragma unroll
         for (int j = 0; j < FN; ++j) b_off[j] = nmajor_offset<BN>(t16_k, (wn * WTN + j * 16) * 2 + t16_nbyte);
-        auto read_a = [&](const char* sa, int s, short8v (&dst)[FMH]) {
+        // one fragment: A rows block i of step s; B columns block j of k32 step kq
+        auto read_a1 = [&](const char* sa, int s, int i) -> short8v {
             const int kq = s >> 1, h = s & 1;
-#pragma unroll
-            for (int i = 0; i < FMH; ++i) {
-                const int row = wm * WTM + (h * FMH + i) * 16 + f16_row;
-                dst[i] = *(const short8v*)(sa + kmajor_offset<BK, true>(row, kq * 4 + f16_kc));
+            const int row = wm * WTM + (h * FMH + i) * 16 + f16_row;
+            return *(const short8v*)(sa + kmajor_offset<BK, true>(row, kq * 4 + f16_kc));
+        };
+        auto read_b1 = [&](const char* sb, int kq, int j) -> short8v {
+            if (TRANS_B) {
+                const int row = wn * WTN + j * 16 + f16_row;
+                return *(const short8v*)(sb + kmajor_offset<BK, true>(row, kq * 4 + f16_kc));
+            } else {
+                const char* r0 = sb + b_off[j] + kq * 32 * (BN * 2);
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, r0));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, r0 + 4 * (BN * 2)));
+                return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
+        };
+        auto read_a = [&](const char* sa, int s, short8v (&dst)[FMH]) {
+#pragma unroll
+            for (int i = 0; i < FMH; ++i) dst[i] = read_a1(sa, s, i);
         };
         auto read_b = [&](const char* sb, int kq, short8v (&dst)[FN]) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                if (TRANS_B) {
-                    const int row = wn * WTN + j * 16 + f16_row;
-                    dst[j] = *(const short8v*)(sb + kmajor_offset<BK, true>(row, kq * 4 + f16_kc));
-                } else {
-                    const char* r0 = sb + b_off[j] + kq * 32 * (BN * 2);
-                    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, r0));
-                    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, r0 + 4 * (BN * 2)));
-                    dst[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-            }
+            for (int j = 0; j < FN; ++j) dst[j] = read_b1(sb, kq, j);
         };
+        static_assert(FMH + FN <= FMH * FN, "a step has at least as many MFMAs as fragments to read under it");
         constexpr int MFMA_PER_TILE = NSTEP * FMH * FN;
         constexpr int MFMA_BEFORE_WAIT = (NSTEP - 1) * FMH * FN;
         constexpr int SPAN = NSTAGE >= 3 ? MFMA_PER_TILE : MFMA_BEFORE_WAIT;
         constexpr int EARLY = (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN < LOADS
                                   ? (MFMA_BEFORE_WAIT * LOADS + SPAN - 1) / SPAN : LOADS;
         static_assert(NSTAGE >= 3 || EARLY == LOADS, "two stages: all pieces must precede the wait");
-        // the MFMAs of step s; SPREAD: this wave's loads of the tile being fetched are issued between them
-        auto mfma_step = [&](int s, int bcur, auto spread_tag) {
+        // the MFMAs of step s; mid(k) runs after MFMA number k of the step (the fragment reads of the next
+        // step go there, one at a time: nothing waits for them before the next step, and the matrix pipe
+        // restarts right after a barrier instead of after a burst of reads; measured 3.6-4 % on 8192^3);
+        // SPREAD: this wave's loads of the tile being fetched are issued between the MFMAs as well
+        auto mfma_step = [&](int s, int bcur, auto spread_tag, auto&& mid) {
             constexpr bool SPREAD = decltype(spread_tag)::value;
             const int h = s & 1;
 #pragma unroll
@@ -1054,6 +1079,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     acc[h * FMH + i][j] = MfmaOp16<T>::run(bf[bcur][j], af[s & 1][i], acc[h * FMH + i][j]);
+                    mid(i * FN + j);
                     if (SPREAD) {
                         const int idx = (s * FMH + i) * FN + j;         // MFMA number within the k-tile
 #pragma unroll
@@ -1103,13 +1129,14 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             constexpr int NB = FMH * FN;               // of which before the barrier
             // L loads are spread over the tile: load r right after MFMA number r NT / L; pieces before the barrier:
             auto early_of = [](int L) { return L == 0 ? 0 : ((NB * L + NT - 1) / NT < L ? (NB * L + NT - 1) / NT : L); };
-            auto mfma2 = [&](int st, int bcur, auto l_tag) {
+            auto mfma2 = [&](int st, int bcur, auto l_tag, auto&& mid) {
                 constexpr int L = decltype(l_tag)::value;     // CA + CB: A pieces then B pieces; CB: B pieces; 0: none
 #pragma unroll
                 for (int i = 0; i < FMH; ++i)
 #pragma unroll
                     for (int j = 0; j < FN; ++j) {
                         acc[st * FMH + i][j] = MfmaOp16<T>::run(bf[bcur][j], af[st][i], acc[st * FMH + i][j]);
+                        mid(i * FN + j);
                         const int idx = (st * FMH + i) * FN + j;
 #pragma unroll
                         for (int r = 0; r < L; ++r) {
@@ -1125,29 +1152,42 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                 else if (n >= CB) wait_vmcnt<CB>(); else wait_vmcnt<0>();
             };
             // one k-tile t (half h = t % 2).  PHASE as above; L > 0: steady state with L loads spread; else
-            // `burst` loads were issued at the start of the tile
+            // `burst` loads were issued at the start of the tile.  The fragment reads (second rows half of
+            // this tile, then the first fragments of the next one after the barrier) go one at a time
+            // between the MFMAs, like in the plain pipeline below.
             auto tile2 = [&](int t, int h, bool have_next, auto phase_tag, auto l_tag, int burst) {
                 constexpr int PHASE = decltype(phase_tag)::value;
                 constexpr int L = decltype(l_tag)::value;
                 constexpr int P = PHASE == 2 ? 1 : 0;
                 const char* sa = lds + a_lds(t);
-                read_a2(sa, h, 1, af[1]);
-                __builtin_amdgcn_sched_barrier(0);
                 if (PRIO) __builtin_amdgcn_s_setprio(2);
-                mfma2(0, P, l_tag);
+                mfma2(0, P, l_tag, [&](int k) {
+                    if (k < FMH) {
+                        const int row = wm * WTM + (FMH + k) * 16 + f16_row;
+                        af[1][k] = *(const short8v*)(sa + kmajor_offset<64, true>(row, h * 4 + f16_kc));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                });
                 if (PRIO) __builtin_amdgcn_s_setprio(0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (have_next) {
-                    // steady state: this tile's later pieces and the B pieces issued after the A pieces
-                    // that the next tile needs may stay in flight
                     if (L > 0) wait_vmcnt<CB + early_of(L)>(); else wait_rt(burst);
                     __syncthreads();
-                    read_a2(lds + a_lds(t + 1), h ^ 1, 0, af[0]);
-                    read_b(lds + b_lds(t + 1), 0, bf[P ^ 1]);
-                    __builtin_amdgcn_sched_barrier(0);
                 }
+                const char* na = lds + a_lds(t + 1);
+                const char* nb = lds + b_lds(t + 1);
                 if (PRIO) __builtin_amdgcn_s_setprio(2);
-                mfma2(1, P, l_tag);
+                mfma2(1, P, l_tag, [&](int k) {
+                    if (!have_next) return;
+                    if (k < FMH) {
+                        const int row = wm * WTM + k * 16 + f16_row;
+                        af[0][k] = *(const short8v*)(na + kmajor_offset<64, true>(row, (h ^ 1) * 4 + f16_kc));
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else if (k < FMH + FN) {
+                        bf[P ^ 1][k - FMH] = read_b1(nb, 0, k - FMH);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                });
                 if (PRIO) __builtin_amdgcn_s_setprio(0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (PHASE == 0 && have_next) {
@@ -1210,11 +1250,16 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                 const char* sb = sa + A_BYTES;
     #pragma unroll
                 for (int s = 0; s < NSTEP - 1; ++s) {
-                    read_a(sa, s + 1, af[(s + 1) & 1]);
-                    if (((s + 1) & 1) == 0) read_b(sb, (s + 1) >> 1, bf[(P + ((s + 1) >> 1)) & 1]);
-                    __builtin_amdgcn_sched_barrier(0);       // keep the reads ahead of the MFMAs they hide under
                     if (PRIO) __builtin_amdgcn_s_setprio(2);
-                    mfma_step(s, (P + (s >> 1)) & 1, spread_tag);
+                    mfma_step(s, (P + (s >> 1)) & 1, spread_tag, [&](int k) {
+                        if (k < FMH) {
+                            af[(s + 1) & 1][k] = read_a1(sa, s + 1, k);
+                            __builtin_amdgcn_sched_barrier(0);
+                        } else if (((s + 1) & 1) == 0 && k < FMH + FN) {
+                            bf[(P + ((s + 1) >> 1)) & 1][k - FMH] = read_b1(sb, (s + 1) >> 1, k - FMH);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    });
                     if (PRIO) __builtin_amdgcn_s_setprio(0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1222,13 +1267,19 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     if (NEWER >= 0) wait_vmcnt<(SPREAD && NSTAGE >= 3 ? (NEWER >= 1 ? NEWER - 1 : 0) * LOADS + EARLY : (NEWER >= 0 ? NEWER : 0) * LOADS)>();
                     else wait_newer(newer_rt);
                     __syncthreads();          // everyone's pieces landed; everyone is done reading `stage`
-                    const char* na = lds + next_stage * STAGE;
-                    read_a(na, 0, af[0]);
-                    read_b(na + A_BYTES, 0, bf[(P + KQ) & 1]);
-                    __builtin_amdgcn_sched_barrier(0);
                 }
+                const char* na = lds + next_stage * STAGE;
                 if (PRIO) __builtin_amdgcn_s_setprio(2);
-                mfma_step(NSTEP - 1, (P + KQ - 1) & 1, spread_tag);
+                mfma_step(NSTEP - 1, (P + KQ - 1) & 1, spread_tag, [&](int k) {
+                    if (!have_next) return;
+                    if (k < FMH) {
+                        af[0][k] = read_a1(na, 0, k);
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else if (k < FMH + FN) {
+                        bf[(P + KQ) & 1][k - FMH] = read_b1(na + A_BYTES, 0, k - FMH);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                });
                 if (PRIO) __builtin_amdgcn_s_setprio(0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (PHASE == 0 && (KQ & 1) && have_next) {
