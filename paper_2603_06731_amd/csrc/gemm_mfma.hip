@@ -87,6 +87,7 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
     }
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
     if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1 && cfg != 6) cfg = choose_config(p);   // the ones built
+    if (!fp8 && cfg >= 2 && cfg <= 4) cfg = choose_config(p);   // 16-bit types: 0, 1, 5, 6, 7 are built
     if (fp8) {
         // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
         // only the 64-deep configurations are built for it

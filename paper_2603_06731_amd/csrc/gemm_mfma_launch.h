@@ -18,9 +18,9 @@ struct MfmaConfig {
 static const MfmaConfig kMfmaConfigs[] = {
     {0, 128, 256, 32, 1, 4, 3, "mfma_128x256x32_w1x4_s3_occ2"},
     {1, 128, 128, 64, 2, 2, 2, "mfma_128x128x64_w2x2_s2"},
-    {2, 128, 128, 32, 2, 2, 3, "mfma_128x128x32_w2x2_s3_occ3"},
+    {2, 128, 128, 32, 2, 2, 3, "mfma_128x128x32_w2x2_s3_occ3"},     // 2, 3: measured and retired, not built
     {3, 256, 256, 32, 2, 4, 4, "mfma_256x256x32_w2x4_s4"},
-    {4, 256, 256, 64, 2, 4, 2, "mfma_256x256x64_w2x4_s2"},
+    {4, 256, 256, 64, 2, 4, 2, "mfma_256x256x64_w2x4_s2"},          // 8-bit types only
     {5, 256, 256, 32, 2, 4, 4, "mfma16_256x256x32_w2x4_s4"},        // 16x16x32 MFMA blocks (16-bit types)
     {6, 128, 256, 32, 1, 4, 3, "mfma16_128x256x32_w1x4_s3_occ2"},
     {7, 256, 256, 32, 2, 4, 4, "mfma16_256x256x32_w2x4_s4_a64"},    // A staged 64 deep (plain matrices)
@@ -83,9 +83,7 @@ hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int grou
     switch (cfg) {
     PBK_CASE(0, 128, 256, 32, 1, 4, 3, 2)
     PBK_CASE(1, 128, 128, 64, 2, 2, 2)
-    PBK_CASE(2, 128, 128, 32, 2, 2, 3, 3)
-    PBK_CASE(3, 256, 256, 32, 2, 4, 4)
-    PBK_CASE(4, 256, 256, 64, 2, 4, 2)
+    // 2-4 (32x32 blocks) are not built for the 16-bit types: their 16x16 twins 5-7 replaced them
     PBK_CASE(5, 256, 256, 32, 2, 4, 4, 1, 16)
     PBK_CASE(6, 128, 256, 32, 1, 4, 3, 2, 16)
     PBK_CASE(7, 256, 256, 32, 2, 4, 4, 1, 16, true)
