@@ -44,7 +44,7 @@ PAD4 = [  # n, H, W, Cin, Cout, KH, KW, stride, pad4, dil
 
 
 @pytest.mark.parametrize("case", PAD4)
-@pytest.mark.parametrize("cfg", [None, 0, 1, 3, "generic"])
+@pytest.mark.parametrize("cfg", [None, 0, 1, 5, 6, 7, "generic"])
 def test_conv_pad4(case, cfg):
     n, H, W, Cin, Cout, KH, KW, stride, pad4, dil = case
     w = wl.Workload("conv_pad4", "conv", BF16, BF16, C.EPI_BIAS_RELU, n=n, H=H, W=W, Cin=Cin, Cout=Cout,

@@ -11,7 +11,7 @@ import pbk_testlib as T
 pytestmark = pytest.mark.gpu
 
 BF16, F16, F32 = wl.DTYPE_BF16, wl.DTYPE_F16, wl.DTYPE_F32
-MFMA_CONFIGS = list(range(8))
+MFMA_CONFIGS = [0, 1, 5, 6, 7]          # the configurations built for the 16-bit types
 
 
 def tol_for(w):
@@ -217,7 +217,7 @@ def test_views_ignore_nan_outside_and_guard_band_survives():
     da, db = T.to_device(a), T.to_device(b)
     sentinel = 0x5A5A
     out = T.device_empty(M * ldc + 64, BF16, fill=np.array(sentinel, dtype=np.uint16).view(np.int16).item())
-    for force in ("mfma:0", "mfma:1", "mfma:3", "generic"):
+    for force in ("mfma:0", "mfma:1", "mfma:5", "mfma:7", "generic"):
         with T.forced_kernel(force):
             st = pbk.pbk_matmul(da, db, out, None, M, N, K, lda, ldb, ldc, BF16, BF16, 0, 1.0, C.EPI_NONE)
         assert st == 0

@@ -15,7 +15,7 @@ def out_tensor(n, dtype):
     return T.device_empty(n, dtype)
 
 
-@pytest.mark.parametrize("cfg", [None, 0, 1, 3, "generic"])
+@pytest.mark.parametrize("cfg", [None, 0, 1, 5, 6, 7, "generic"])
 @pytest.mark.parametrize("mnk", [(300, 264, 200), (256, 512, 64), (33, 520, 136), (130, 257, 72)])
 @pytest.mark.parametrize("dtype,out_dtype", [(BF16, BF16), (F16, F32)])
 def test_matmul_residual(cfg, mnk, dtype, out_dtype):
