@@ -95,6 +95,15 @@ template <> struct MfmaOp16<f16_t> {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
+// int8, 16x16 blocks: v_mfma_i32_16x16x64_i8, the same 16 bytes per lane and operand (16 values)
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+template <> struct MfmaOp16<int8_t> {
+    static __device__ __forceinline__ f32x4 run(short8v a, short8v b, f32x4 c) {
+        i32x4 r = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(int4v, a), __builtin_bit_cast(int4v, b),
+                                                        __builtin_bit_cast(i32x4, c), 0, 0, 0);
+        return __builtin_bit_cast(f32x4, r);
+    }
+};
 __device__ __forceinline__ int8v frag_bytes32(const Frag<2>& f) {
     return __builtin_shufflevector(__builtin_bit_cast(int4v, f.c[0]), __builtin_bit_cast(int4v, f.c[1]),
                                    0, 1, 2, 3, 4, 5, 6, 7);
@@ -549,7 +558,8 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     // raised wave priority around the MFMA groups: measured +1..2.5 % for one 256x256 workgroup per CU
     // and for the convolution, -1 % for two 128x256 workgroups per CU on plain matrices
     constexpr bool PRIO = BM == 256 || MODE == MODE_CONV;
-    static_assert(MI == 32 || (MI == 16 && sizeof(T) == 2), "16x16 blocks are built for the 16-bit types");
+    static_assert(MI == 32 || (MI == 16 && (sizeof(T) == 2 || (std::is_same<T, int8_t>::value && MODE == MODE_TRANS_B))),
+                  "16x16 blocks are built for the 16-bit types and for int8 with both operands k-major");
     constexpr bool CONVT = MODE == MODE_CONVT;               // transposed convolution: gather form
     constexpr bool CONV = MODE == MODE_CONV || CONVT;        // A is an image, rows are output pixels
     constexpr bool TRANS_B = MODE == MODE_TRANS_B;

@@ -24,6 +24,7 @@ static const MfmaConfig kMfmaConfigs[] = {
     {5, 256, 256, 32, 2, 4, 4, "mfma16_256x256x32_w2x4_s4"},        // 16x16x32 MFMA blocks (16-bit types)
     {6, 128, 256, 32, 1, 4, 3, "mfma16_128x256x32_w1x4_s3_occ2"},
     {7, 256, 256, 32, 2, 4, 4, "mfma16_256x256x32_w2x4_s4_a64"},    // A staged 64 deep (plain matrices)
+    {8, 256, 256, 64, 2, 4, 2, "mfma16_256x256x64_w2x4_s2"},        // int8, both operands k-major (16x16x64 blocks)
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
