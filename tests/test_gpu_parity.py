@@ -241,6 +241,28 @@ def test_run_to_run_bit_exact():
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
+@pytest.mark.parametrize("cfg", [5, 6, 7])
+def test_large_run_to_run_bit_exact_and_equal_across_configurations(cfg):
+    """The pipelines reuse LDS stages under explicit wait counts and one barrier per k-tile: a race
+    would show as run-to-run differences on a long contraction.  All 16x16 configurations add the
+    products of an output element in the same order (k ascending inside the MFMA chain), so their
+    results are also bit-identical to each other."""
+    import torch
+    w = wl.Workload("det_big", "matmul", BF16, BF16, C.EPI_BIAS, M=1024, N=1536, K=8192,
+                    dist_b=("normal", 1.0 / np.sqrt(8192)))
+    dev = T.upload(wl.make_inputs(w))
+    with T.forced_kernel("mfma:5"):
+        st, ref = T.run_workload(w, dev)
+    assert st == 0
+    ref = ref.clone()
+    for _ in range(4):
+        with T.forced_kernel(f"mfma:{cfg}"):
+            st, out = T.run_workload(w, dev)
+        assert st == 0
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), cfg
+
+
 def test_zero_sizes_and_k_zero():
     import paper_2603_06731_amd as pbk
     out = T.device_empty(16, F32, fill=7.0)
