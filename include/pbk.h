@@ -246,7 +246,7 @@ int pbk_version(void);
 /*
  * Name of the kernel configuration the most recent successful call ON THIS
  * THREAD dispatched to (for benchmarks and tests; e.g.
- * "mfma_128x256x32_w1x4_s3_occ2", "generic_64x64x16_fma").  Never NULL; ""
+ * "mfma16_128x256x32_w1x4_s3_occ2", "generic_64x64x16_fma").  Never NULL; ""
  * before the first call.
  */
 const char* pbk_last_kernel(void);

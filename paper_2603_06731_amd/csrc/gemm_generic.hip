@@ -16,6 +16,7 @@ namespace {
 
 constexpr int GT = 64;     // tile edge in M and N
 constexpr int GK = 16;     // tile depth
+constexpr int GLD = GT * GK / 256;   // elements of each operand tile a thread moves
 constexpr int GPAD = 4;
 
 template <typename T> __device__ __forceinline__ float ld_elem(const T* p, int64_t i) { return widen<T>(p[i]); }
@@ -55,8 +56,11 @@ __device__ __forceinline__ float conv_a(const T* x, const ConvGeom& g, int i, in
 template <typename T, bool CONV>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_m, int tiles_n) {
     typedef typename AccOf<T>::type acc_t;
-    __shared__ acc_t As[GK][GT + GPAD];
-    __shared__ acc_t Bs[GK][GT + GPAD];
+    // rows are 16-byte aligned (68 values): a lane's four A values and four B values of one k are
+    // one 16-byte LDS read each instead of four 4-byte ones
+    typedef acc_t __attribute__((ext_vector_type(4))) acc4_t;
+    __shared__ __attribute__((aligned(16))) acc_t As[GK][GT + GPAD];
+    __shared__ __attribute__((aligned(16))) acc_t Bs[GK][GT + GPAD];
 
     int bid = blockIdx.x;
     int tn = bid % tiles_n;
@@ -78,11 +82,11 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
 
     // One k-tile ahead in registers: the global loads of tile t+1 are in flight while tile t is
     // multiplied out of LDS (their latency would otherwise be paid once per k-tile).
-    float a_next[4], b_next[4];
+    float a_next[GLD], b_next[GLD];
     auto fetch = [&](int k0) {
-        // A tile: 64 rows x 16 k; lanes run along k (contiguous in memory)
+        // A tile: 64 rows x GK k; lanes run along k (contiguous in memory)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < GLD; ++r) {
             int e = t + 256 * r;
             int mm = e / GK, kk = e % GK;
             int gm = m0 + mm, gk = k0 + kk;
@@ -93,9 +97,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
             }
             a_next[r] = v;
         }
-        // B tile: 16 k x 64 n
+        // B tile: GK k x 64 n
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < GLD; ++r) {
             int e = t + 256 * r;
             int kk, nn;
             if (p.trans_b) { nn = e / GK; kk = e % GK; }
@@ -110,7 +114,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
     };
     auto stash = [&]() {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < GLD; ++r) {
             int e = t + 256 * r;
             As[e % GK][e / GK] = (acc_t)a_next[r];
             if (p.trans_b) Bs[e % GK][e / GK] = (acc_t)b_next[r];
@@ -124,11 +128,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
         if (k0 + GK < p.K) fetch(k0 + GK);
 #pragma unroll
         for (int kk = 0; kk < GK; ++kk) {
-            acc_t a[4], bv[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx * 4 + j];
+            const acc4_t a = *(const acc4_t*)&As[kk][ty * 4];
+            const acc4_t bv = *(const acc4_t*)&Bs[kk][tx * 4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
