@@ -1181,8 +1181,15 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                 if (PRIO) __builtin_amdgcn_s_setprio(0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (have_next) {
+                    // What tile t+1 reads must have landed; a wave's loads complete in issue order, so it
+                    // waits until only the loads issued after those are outstanding.  Steady state, even t:
+                    // A(t, t+1) and B(t+1) were issued during tile t-2; younger are B(t+2) from tile t-1
+                    // (CB loads) and the early_of(CA + CB) pieces of this tile issued so far.  Odd t:
+                    // A(t+1, t+2) are the first CA loads of tile t-1 and B(t+1) is older; younger are the
+                    // CB loads of B(t+2) that followed them and the early_of(CB) pieces of this tile.
+                    // Drain: everything but this tile's own burst.
                     if (L > 0) wait_vmcnt<CB + early_of(L)>(); else wait_rt(burst);
-                    __syncthreads();
+                    __syncthreads();      // also: everyone is done reading what the next loads overwrite
                 }
                 const char* na = lds + a_lds(t + 1);
                 const char* nb = lds + b_lds(t + 1);
