@@ -14,8 +14,8 @@
  *  - All data pointers are DEVICE pointers valid on the device that `stream`
  *    belongs to.  The library never allocates, frees or keeps them.  The
  *    output must not alias any input.
- *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL
- *    = the default stream) and return; ordering is stream ordering.
+ *  - Calls only enqueue work on `stream` (a hipStream_t; NULL = the default
+ *    stream) and return; ordering is stream ordering.
  *  - Matrices are row-major with leading dimensions in ELEMENTS.
  *  - in_dtype is the element type of A and B (image and weights);
  *    out_dtype must be PBK_F32 or equal to in_dtype; for the FP8 input types it
@@ -46,6 +46,10 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The HIP stream handle, declared here exactly as the HIP runtime declares it, so that
+ * this header needs no HIP header (a repeated identical typedef is valid C11 and C++). */
+typedef struct ihipStream_t* hipStream_t;
 
 typedef enum {
     PBK_OK = 0,
@@ -86,10 +90,12 @@ pbk_status pbk_matmul(const void* A, const void* B, void* C, const float* bias,
                       int64_t M, int64_t N, int64_t K,
                       int64_t lda, int64_t ldb, int64_t ldc,
                       pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
-                      float alpha, pbk_epilogue epi, void* stream);
+                      float alpha, pbk_epilogue epi, hipStream_t stream);
 
 /*
- * `batch` independent matmuls; entry b uses A + b*stride_a, B + b*stride_b,
+ * `batch` independent matmuls with one launch (paper Sec. 4.4: the two contractions of
+ * the attention layer are batched over batch x heads; workload configuration
+ * "attention scores" is the first of them).  Entry b uses A + b*stride_a, B + b*stride_b,
  * C + b*stride_c (strides in elements).  stride_a or stride_b may be 0 to
  * share one operand among all entries; stride_c must be >= (M-1)*ldc + N.
  * bias[N] is shared by all entries.
@@ -99,7 +105,7 @@ pbk_status pbk_batched_matmul(const void* A, const void* B, void* C, const float
                               int64_t lda, int64_t ldb, int64_t ldc,
                               int64_t stride_a, int64_t stride_b, int64_t stride_c,
                               pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
-                              float alpha, pbk_epilogue epi, void* stream);
+                              float alpha, pbk_epilogue epi, hipStream_t stream);
 
 /*
  * y[N][OH][OW][Cout] = act(alpha * conv(x, w) + bias[Cout])      (paper Sec. 4.5)
@@ -117,7 +123,7 @@ pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* b
                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                            pbk_dtype in_dtype, pbk_dtype out_dtype,
-                           float alpha, pbk_epilogue epi, void* stream);
+                           float alpha, pbk_epilogue epi, hipStream_t stream);
 
 /*
  * The same convolution with separate padding on the four sides (the "same"-style
@@ -132,7 +138,7 @@ pbk_status pbk_conv2d_nhwc_pad4(const void* x, const void* w, void* y, const flo
                                 int64_t pad_top, int64_t pad_bottom, int64_t pad_left, int64_t pad_right,
                                 int64_t dil_h, int64_t dil_w,
                                 pbk_dtype in_dtype, pbk_dtype out_dtype,
-                                float alpha, pbk_epilogue epi, void* stream);
+                                float alpha, pbk_epilogue epi, hipStream_t stream);
 
 /*
  * Transposed convolution (paper Sec. 4.5: covered by the same lowering).
@@ -151,7 +157,7 @@ pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, cons
                                      int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
                                      int64_t dil_h, int64_t dil_w,
                                      pbk_dtype in_dtype, pbk_dtype out_dtype,
-                                     float alpha, pbk_epilogue epi, void* stream);
+                                     float alpha, pbk_epilogue epi, hipStream_t stream);
 
 /*
  * Residual-add epilogue: C = act(alpha * A . B + bias + beta * R), the shortcut
@@ -164,14 +170,14 @@ pbk_status pbk_matmul_residual(const void* A, const void* B, void* C, const floa
                                int64_t M, int64_t N, int64_t K,
                                int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr,
                                pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
-                               float alpha, float beta, pbk_epilogue epi, void* stream);
+                               float alpha, float beta, pbk_epilogue epi, hipStream_t stream);
 
 pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const float* bias, const void* r,
                                     int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
                                     int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                                     int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                                     pbk_dtype in_dtype, pbk_dtype out_dtype,
-                                    float alpha, float beta, pbk_epilogue epi, void* stream);
+                                    float alpha, float beta, pbk_epilogue epi, hipStream_t stream);
 
 /*
  * int8 x int8 contraction with exact 32-bit integer accumulation and the quantised
@@ -182,8 +188,8 @@ pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const
  *   t = t + bias[j]                      if bias != NULL
  *   if mid_scale > 0:                    a quantise / de-quantise pair
  *       t = float(clamp(roundeven(t / mid_scale), -128, 127)) * mid_scale
- *   t = t * mul[j]                       if mul != NULL   (folded batch-norm scale)
- *   t = t + add[j]                       if add != NULL   (folded batch-norm shift)
+ *   t = t * mul[j]                       if mul != NULL   (batch-norm scale, folded by the caller)
+ *   t = t + add[j]                       if add != NULL   (batch-norm shift, folded by the caller)
  *   t = t > 0 ? t : 0                    if relu != 0
  *   out_dtype PBK_INT8: C = int8(clamp(roundeven(t / out_scale), -128, 127)), out_scale > 0
  *   out_dtype PBK_F32:  C = t
@@ -200,7 +206,7 @@ pbk_status pbk_matmul_int8(const int8_t* A, const int8_t* B, void* C,
                            int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int trans_b,
                            const float* scale, const float* bias, float mid_scale,
                            const float* mul, const float* add, int relu, float out_scale,
-                           pbk_dtype out_dtype, void* stream);
+                           pbk_dtype out_dtype, hipStream_t stream);
 
 pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
                                 int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
@@ -208,7 +214,7 @@ pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
                                 int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                                 const float* scale, const float* bias, float mid_scale,
                                 const float* mul, const float* add, int relu, float out_scale,
-                                pbk_dtype out_dtype, void* stream);
+                                pbk_dtype out_dtype, hipStream_t stream);
 
 /*
  * Attention layer, every operator fused into one kernel          (paper Sec. 4.4)
@@ -235,7 +241,7 @@ pbk_status pbk_attention(const void* Q, const void* K, const void* V, const floa
                          int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
                          int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
                          int64_t ld_bias, int64_t stride_bias,
-                         pbk_dtype dtype, float alpha, void* stream);
+                         pbk_dtype dtype, float alpha, hipStream_t stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* pbk_status_string(pbk_status s);
@@ -250,6 +256,16 @@ int pbk_version(void);
  * before the first call.
  */
 const char* pbk_last_kernel(void);
+
+/*
+ * Benchmarking and test aid, for the calls that follow ON THIS THREAD: "generic" forces
+ * the fallback kernel, "mfma" the matrix-unit path with its automatic tile choice,
+ * "mfma:<id>" one tile configuration (a problem it cannot run then gives
+ * PBK_ERR_UNSUPPORTED); NULL or "" returns to the default.  The default is automatic
+ * choice, or what the environment variable PBK_FORCE_KERNEL (same strings) held when the
+ * process made its first call.  An unknown string is PBK_ERR_UNSUPPORTED and changes nothing.
+ */
+pbk_status pbk_force_kernel(const char* choice);
 
 #ifdef __cplusplus
 }

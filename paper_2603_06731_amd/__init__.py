@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     PbkError, lib, lib_path, pbk_matmul, pbk_batched_matmul, pbk_conv2d_nhwc, pbk_conv2d_nhwc_pad4,
     pbk_conv2d_transpose_nhwc, pbk_attention, pbk_matmul_int8, pbk_conv2d_nhwc_int8,
     pbk_matmul_residual, pbk_conv2d_nhwc_residual,
-    pbk_status_string, pbk_version, pbk_last_kernel, check, EXPORTED_SYMBOLS,
+    pbk_status_string, pbk_version, pbk_last_kernel, pbk_force_kernel, check, EXPORTED_SYMBOLS,
 )

@@ -17,7 +17,7 @@ PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2, PBK_INT8 = 0, 1, 2, 3, 4
 EXPORTED_SYMBOLS = ("pbk_matmul", "pbk_batched_matmul", "pbk_conv2d_nhwc", "pbk_conv2d_nhwc_pad4",
                     "pbk_conv2d_transpose_nhwc", "pbk_attention", "pbk_matmul_int8", "pbk_conv2d_nhwc_int8",
                     "pbk_matmul_residual", "pbk_conv2d_nhwc_residual",
-                    "pbk_status_string", "pbk_version", "pbk_last_kernel")
+                    "pbk_status_string", "pbk_version", "pbk_last_kernel", "pbk_force_kernel")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpbk.so")
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.pbk_status_string.restype = ctypes.c_char_p
         L.pbk_version.restype = i32
         L.pbk_last_kernel.restype = ctypes.c_char_p
+        L.pbk_force_kernel.argtypes = [ctypes.c_char_p]
+        L.pbk_force_kernel.restype = i32
         _lib = L
     return _lib
 
@@ -179,6 +181,10 @@ def pbk_version() -> int:
 
 def pbk_last_kernel() -> str:
     return lib().pbk_last_kernel().decode()
+
+
+def pbk_force_kernel(choice) -> int:
+    return lib().pbk_force_kernel(None if choice is None else str(choice).encode())
 
 
 def check(status: int, where: str = "libpbk") -> None:

@@ -58,7 +58,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // constant, so nothing has to be made uniform again for every load.
 __device__ __forceinline__ void dma16_s(int4v rsrc, unsigned lds_addr, unsigned voff) {
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
 }
 
 // HAS_BIAS: an additive bias is read.  PRE: scores are multiplied by alpha*log2(e) (and the

@@ -84,8 +84,7 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
                 : (p.M >= 256 && p.N >= 256 && t256 >= 128) ? (kmajor ? 8 : 4) : 1;
         if (c == 8 && !kmajor) c = 4;       // the 16x16 blocks are built for k-major operands only
         *name = kMfmaConfigs[c].name;
-        int gm = 8;
-        if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) gm = g; }
+        const int gm = group_m_override() > 0 ? group_m_override() : 8;
         return launch_mfma_int8(p, stream, c, gm);
     }
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
@@ -99,8 +98,7 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
             cfg = (p.M >= 256 && p.N >= 256 && t256 >= 128) ? 4 : 1;
         }
     }
-    int group_m = 8;
-    if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) group_m = g; }
+    const int group_m = group_m_override() > 0 ? group_m_override() : 8;
     *name = kMfmaConfigs[cfg].name;
     if (fp8) return launch_mfma_fp8(p, stream, cfg, group_m);
     return p.in_dtype == DT_BF16 ? launch_mfma_bf16(p, stream, cfg, group_m)

@@ -213,8 +213,8 @@ __device__ __forceinline__ int4v make_rsrc(const void* base) {
 // of the block at LDS byte address lds_addr (wave-uniform, carried in M0).
 // Written as inline assembly so that the compiler does not serialise later LDS
 // reads of the OTHER stage behind it; completion is awaited explicitly with
-// s_waitcnt vmcnt(0) before the barrier that publishes the stage.  Nothing else
-// in this kernel depends on M0.
+// s_waitcnt vmcnt(n) before the barrier that publishes the stage.  M0 is declared
+// clobbered, so whatever else the compiler keeps there is saved around the statement.
 __device__ __forceinline__ void dma16(int4v rsrc, unsigned lds_addr, unsigned voff) {
     // descriptor and LDS address are wave-uniform by construction; readfirstlane pins
     // them to scalar registers whatever the compiler's divergence analysis concluded
@@ -224,7 +224,7 @@ __device__ __forceinline__ void dma16(int4v rsrc, unsigned lds_addr, unsigned vo
     rsrc[3] = __builtin_amdgcn_readfirstlane(rsrc[3]);
     lds_addr = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
 }
 
 __device__ __forceinline__ unsigned lds_addr_of(const char* p) {

@@ -28,6 +28,28 @@ static const MfmaConfig kMfmaConfigs[] = {
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
+// XCD (accelerator complex die, each with its own L2) and compute unit counts of a device,
+// asked once per device.  Workgroup ids are dealt round-robin to the XCDs, which the block
+// mapping undoes.
+struct DeviceShape { int xcds, cus; };
+inline hipError_t device_shape(int dev, DeviceShape* out) {
+    static std::atomic<unsigned> cache[32];          // xcds << 16 | cus; 0 = not asked yet
+    const int slot = dev & 31;
+    unsigned v = cache[slot].load(std::memory_order_acquire);
+    if (!v) {
+        int x = 0, c = 0;
+        hipError_t e = hipDeviceGetAttribute(&x, hipDeviceAttributeNumberOfXccs, dev);
+        if (e != hipSuccess || x < 1) { (void)hipGetLastError(); x = 1; }
+        e = hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        v = ((unsigned)x << 16) | (unsigned)(c & 0xFFFF);
+        cache[slot].store(v, std::memory_order_release);
+    }
+    out->xcds = (int)(v >> 16);
+    out->cus = (int)(v & 0xFFFF);
+    return hipSuccess;
+}
+
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC, int MI = 32,
           bool ADBL = false>
 hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
@@ -51,7 +73,10 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     tm.total = (int)total;
     tm.group_m = group_m < 1 ? 1 : group_m;
-    tm.xcds = 8;
+    DeviceShape ds;
+    e = device_shape(dev, &ds);
+    if (e != hipSuccess) return e;
+    tm.xcds = ds.xcds;
     // hipLaunchKernel reports this launch's own status; the per-thread "last error"
     // may hold an unrelated earlier failure of another library
     Problem pa = p;

@@ -26,16 +26,40 @@ bool valid_out_dtype(int dt) { return dt == PBK_F32 || dt == PBK_BF16 || dt == P
 
 bool aligned(const void* p, int64_t a) { return (reinterpret_cast<uintptr_t>(p) % (uintptr_t)a) == 0; }
 
-// PBK_FORCE_KERNEL: "generic" forces the fallback kernel, "mfma:<id>" forces an
-// MFMA tile configuration (benchmarking aid; unset = automatic choice).
+// Kernel choice overrides (benchmarking and test aid).  A choice is "generic" (the fallback
+// kernel), "mfma" (the matrix-unit path, automatic tile configuration) or "mfma:<id>" (one tile
+// configuration).  The environment variables PBK_FORCE_KERNEL and PBK_GROUP_M are read ONCE,
+// at the first call of the process; pbk_force_kernel() overrides the former per thread.
+struct Choice { int force; int cfg; };        // force: 0 automatic, 1 generic, 2 mfma; cfg: -1 or id
+
+bool parse_choice(const char* e, Choice* c) {
+    c->force = 0; c->cfg = -1;
+    if (!e || !*e) return true;
+    if (!std::strcmp(e, "generic")) { c->force = 1; return true; }
+    if (!std::strcmp(e, "mfma")) { c->force = 2; return true; }
+    if (!std::strncmp(e, "mfma:", 5) && e[5] >= '0' && e[5] <= '9') { c->force = 2; c->cfg = std::atoi(e + 5); return true; }
+    return false;
+}
+
+struct EnvOverrides { Choice choice; int group_m; };
+const EnvOverrides& env_overrides() {
+    static const EnvOverrides o = [] {
+        EnvOverrides r{};
+        if (!parse_choice(std::getenv("PBK_FORCE_KERNEL"), &r.choice)) r.choice = Choice{0, -1};
+        r.group_m = 0;
+        if (const char* e = std::getenv("PBK_GROUP_M")) { int g = std::atoi(e); if (g > 0) r.group_m = g; }
+        return r;
+    }();
+    return o;
+}
+
+thread_local bool g_choice_set = false;      // pbk_force_kernel() was called on this thread
+thread_local Choice g_choice = {0, -1};
+
 int forced_choice(int* cfg) {
-    *cfg = -1;
-    const char* e = std::getenv("PBK_FORCE_KERNEL");
-    if (!e || !*e) return 0;
-    if (!std::strcmp(e, "generic")) return 1;
-    if (!std::strncmp(e, "mfma:", 5)) { *cfg = std::atoi(e + 5); return 2; }
-    if (!std::strcmp(e, "mfma")) return 2;
-    return 0;
+    const Choice& c = g_choice_set ? g_choice : env_overrides().choice;
+    *cfg = c.cfg;
+    return c.force;
 }
 
 pbk_status check_common(int in_dtype, int out_dtype, int epi, const float* bias) {
@@ -47,7 +71,7 @@ pbk_status check_common(int in_dtype, int out_dtype, int epi, const float* bias)
     return PBK_OK;
 }
 
-pbk_status dispatch(const pbk::Problem& p_in, void* stream) {
+pbk_status dispatch(const pbk::Problem& p_in, hipStream_t stream) {
     pbk::Problem p = p_in;
     if (g_residual) { p.R = g_residual; p.ldr = g_ldr; p.beta = g_beta; }
     int cfg = -1;
@@ -57,9 +81,9 @@ pbk_status dispatch(const pbk::Problem& p_in, void* stream) {
     bool can_mfma = pbk::mfma_supported(p);
     if (force == 2 && !can_mfma) return PBK_ERR_UNSUPPORTED;
     if (can_mfma && force != 1 && (force == 2 || pbk::mfma_preferred(p)))
-        e = pbk::launch_mfma(p, (hipStream_t)stream, cfg, &name);
+        e = pbk::launch_mfma(p, stream, cfg, &name);
     else
-        e = pbk::launch_generic(p, (hipStream_t)stream, &name);
+        e = pbk::launch_generic(p, stream, &name);
     if (e != hipSuccess) {
         std::fprintf(stderr, "libpbk: launch of %s failed: %s\n", name, hipGetErrorString(e));
         return PBK_ERR_HIP;
@@ -95,12 +119,16 @@ pbk_status conv_common(const void* x, const void* w, void* y, const float* bias,
                        int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                        int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                        int64_t OH, int64_t OW, int transposed,
-                       int in_dtype, int out_dtype, float alpha, int epi, void* stream,
+                       int in_dtype, int out_dtype, float alpha, int epi, hipStream_t stream,
                        const float* q_scale = nullptr, const float* q_mul = nullptr, const float* q_add = nullptr,
-                       float q_mid = 0.0f, float q_out = 0.0f, int q_relu = 0) {
-    if (in_dtype != PBK_INT8) {          // the int8 entry point has validated its own parameters
+                       float q_mid = 0.0f, float q_out = 0.0f, int q_relu = 0, bool quant = false) {
+    // quant: the call comes from the int8 entry point, which has validated its own parameters;
+    // from every other entry point PBK_INT8 is not an input type (check_common rejects it)
+    if (!quant) {
         pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
         if (s != PBK_OK) return s;
+    } else if (in_dtype != PBK_INT8 || !q_scale) {
+        return PBK_ERR_DTYPE;
     }
     if (N < 0 || H < 1 || W < 1 || Cin < 1 || Cout < 1 || KH < 1 || KW < 1) return PBK_ERR_SHAPE;
     if (stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0 || dil_h < 1 || dil_w < 1)
@@ -134,11 +162,15 @@ pbk_status conv_common(const void* x, const void* w, void* y, const float* bias,
     p.conv.pad_h = (int)pad_h; p.conv.pad_w = (int)pad_w;
     p.conv.dil_h = (int)dil_h; p.conv.dil_w = (int)dil_w;
     p.conv.transposed = transposed;
-    if (in_dtype == PBK_INT8) set_quant(p, q_scale, bias, q_mid, q_mul, q_add, q_relu, q_out);
+    if (quant) set_quant(p, q_scale, bias, q_mid, q_mul, q_add, q_relu, q_out);
     return dispatch(p, stream);
 }
 
 }  // namespace
+
+namespace pbk {
+int group_m_override() { return env_overrides().group_m; }
+}
 
 extern "C" {
 
@@ -147,7 +179,7 @@ pbk_status pbk_batched_matmul(const void* A, const void* B, void* C, const float
                               int64_t lda, int64_t ldb, int64_t ldc,
                               int64_t stride_a, int64_t stride_b, int64_t stride_c,
                               pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
-                              float alpha, pbk_epilogue epi, void* stream) {
+                              float alpha, pbk_epilogue epi, hipStream_t stream) {
     pbk_status s = check_common(in_dtype, out_dtype, epi, bias);
     if (s != PBK_OK) return s;
     if (batch < 0 || M < 0 || N < 0 || K < 0) return PBK_ERR_SHAPE;
@@ -177,7 +209,7 @@ pbk_status pbk_matmul_residual(const void* A, const void* B, void* C, const floa
                                int64_t M, int64_t N, int64_t K,
                                int64_t lda, int64_t ldb, int64_t ldc, int64_t ldr,
                                pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
-                               float alpha, float beta, pbk_epilogue epi, void* stream) {
+                               float alpha, float beta, pbk_epilogue epi, hipStream_t stream) {
     if (!R && M > 0 && N > 0) return PBK_ERR_NULL;
     if (ldr < N) return PBK_ERR_STRIDE;
     if (valid_out_dtype(out_dtype) && !aligned(R, elem_size(out_dtype))) return PBK_ERR_ALIGN;
@@ -192,7 +224,7 @@ pbk_status pbk_matmul(const void* A, const void* B, void* C, const float* bias,
                       int64_t M, int64_t N, int64_t K,
                       int64_t lda, int64_t ldb, int64_t ldc,
                       pbk_dtype in_dtype, pbk_dtype out_dtype, int trans_b,
-                      float alpha, pbk_epilogue epi, void* stream) {
+                      float alpha, pbk_epilogue epi, hipStream_t stream) {
     return pbk_batched_matmul(A, B, C, bias, 1, M, N, K, lda, ldb, ldc, 0, 0, 0,
                               in_dtype, out_dtype, trans_b, alpha, epi, stream);
 }
@@ -203,7 +235,7 @@ pbk_status pbk_conv2d_nhwc_pad4(const void* x, const void* w, void* y, const flo
                                 int64_t pad_top, int64_t pad_bottom, int64_t pad_left, int64_t pad_right,
                                 int64_t dil_h, int64_t dil_w,
                                 pbk_dtype in_dtype, pbk_dtype out_dtype,
-                                float alpha, pbk_epilogue epi, void* stream) {
+                                float alpha, pbk_epilogue epi, hipStream_t stream) {
     int64_t OH = -1, OW = -1;
     const int64_t lim = 1 << 24;
     const bool sane = pad_top >= 0 && pad_bottom >= 0 && pad_left >= 0 && pad_right >= 0 &&
@@ -224,7 +256,7 @@ pbk_status pbk_conv2d_nhwc(const void* x, const void* w, void* y, const float* b
                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                            pbk_dtype in_dtype, pbk_dtype out_dtype,
-                           float alpha, pbk_epilogue epi, void* stream) {
+                           float alpha, pbk_epilogue epi, hipStream_t stream) {
     return pbk_conv2d_nhwc_pad4(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
                                 pad_h, pad_h, pad_w, pad_w, dil_h, dil_w, in_dtype, out_dtype, alpha, epi, stream);
 }
@@ -234,7 +266,7 @@ pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const
                                     int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                                     int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                                     pbk_dtype in_dtype, pbk_dtype out_dtype,
-                                    float alpha, float beta, pbk_epilogue epi, void* stream) {
+                                    float alpha, float beta, pbk_epilogue epi, hipStream_t stream) {
     if (!r && N > 0) return PBK_ERR_NULL;
     if (valid_out_dtype(out_dtype) && !aligned(r, elem_size(out_dtype))) return PBK_ERR_ALIGN;
     g_residual = r; g_ldr = Cout; g_beta = beta;
@@ -250,7 +282,7 @@ pbk_status pbk_conv2d_transpose_nhwc(const void* x, const void* w, void* y, cons
                                      int64_t pad_h, int64_t pad_w, int64_t out_pad_h, int64_t out_pad_w,
                                      int64_t dil_h, int64_t dil_w,
                                      pbk_dtype in_dtype, pbk_dtype out_dtype,
-                                     float alpha, pbk_epilogue epi, void* stream) {
+                                     float alpha, pbk_epilogue epi, hipStream_t stream) {
     int64_t OH = -1, OW = -1;
     const int64_t lim = 1 << 24;
     const bool sane = H >= 1 && W >= 1 && H <= lim && W <= lim && KH >= 1 && KW >= 1 && KH <= 4096 && KW <= 4096 &&
@@ -271,7 +303,7 @@ pbk_status pbk_matmul_int8(const int8_t* A, const int8_t* B, void* C,
                            int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int trans_b,
                            const float* scale, const float* bias, float mid_scale,
                            const float* mul, const float* add, int relu, float out_scale,
-                           pbk_dtype out_dtype, void* stream) {
+                           pbk_dtype out_dtype, hipStream_t stream) {
     pbk_status s = check_quant(scale, bias, mid_scale, mul, add, out_scale, out_dtype);
     if (s != PBK_OK) return s;
     if (M < 0 || N < 0 || K < 0 || M > INT_MAX || N > INT_MAX) return PBK_ERR_SHAPE;
@@ -296,7 +328,7 @@ pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
                                 int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
                                 const float* scale, const float* bias, float mid_scale,
                                 const float* mul, const float* add, int relu, float out_scale,
-                                pbk_dtype out_dtype, void* stream) {
+                                pbk_dtype out_dtype, hipStream_t stream) {
     pbk_status s = check_quant(scale, bias, mid_scale, mul, add, out_scale, out_dtype);
     if (s != PBK_OK) return s;
     if (KH >= 1 && KW >= 1 && Cin >= 1 && KH <= 4096 && KW <= 4096 && Cin <= (1 << 24) && KH * KW * Cin > 131071)
@@ -310,7 +342,7 @@ pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
     }
     return conv_common(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
                        OH, OW, 0, PBK_INT8, out_dtype, 1.0f, PBK_EPI_NONE, stream, scale, mul, add, mid_scale,
-                       out_scale, relu);
+                       out_scale, relu, true);
 }
 
 pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,
@@ -318,7 +350,7 @@ pbk_status pbk_attention(const void* Q, const void* K, const void* V, const floa
                          int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
                          int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
                          int64_t ld_bias, int64_t stride_bias,
-                         pbk_dtype dtype, float alpha, void* stream) {
+                         pbk_dtype dtype, float alpha, hipStream_t stream) {
     if (dtype != PBK_F32 && dtype != PBK_BF16 && dtype != PBK_F16) return PBK_ERR_DTYPE;
     if (batch < 0 || Nq < 0 || Nk < 0 || D < 1) return PBK_ERR_SHAPE;
     if (batch > INT_MAX || Nq > INT_MAX || Nk > INT_MAX || D > INT_MAX) return PBK_ERR_SHAPE;
@@ -349,8 +381,8 @@ pbk_status pbk_attention(const void* Q, const void* K, const void* V, const floa
     const bool use_mfma = can_mfma && force != 1;
     if (!use_mfma && D > 512) return PBK_ERR_UNSUPPORTED;
     const char* name = "";
-    hipError_t e = use_mfma ? pbk::launch_attention_mfma(p, (hipStream_t)stream, &name)
-                            : pbk::launch_attention_generic(p, (hipStream_t)stream, &name);
+    hipError_t e = use_mfma ? pbk::launch_attention_mfma(p, stream, &name)
+                            : pbk::launch_attention_generic(p, stream, &name);
     if (e != hipSuccess) {
         std::fprintf(stderr, "libpbk: launch of %s failed: %s\n", name, hipGetErrorString(e));
         return PBK_ERR_HIP;
@@ -377,5 +409,13 @@ const char* pbk_status_string(pbk_status s) {
 int pbk_version(void) { return 100; }
 
 const char* pbk_last_kernel(void) { return g_last_kernel; }
+
+pbk_status pbk_force_kernel(const char* choice) {
+    Choice c;
+    if (!parse_choice(choice, &c)) return PBK_ERR_UNSUPPORTED;
+    g_choice_set = choice != nullptr && *choice != 0;
+    g_choice = c;
+    return PBK_OK;
+}
 
 }  // extern "C"

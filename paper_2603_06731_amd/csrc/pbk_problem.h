@@ -81,6 +81,10 @@ bool mfma_supported(const Problem& p);
 bool mfma_preferred(const Problem& p);
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name);
 
+// PBK_GROUP_M of the environment as read at the process's first call (0 = not set): tile rows
+// per group of the block mapping, a benchmarking override.
+int group_m_override();
+
 // Attention: generic kernel (any dtype/alignment, D <= 512) and the fused MFMA kernel.
 hipError_t launch_attention_generic(const AttnProblem& p, hipStream_t stream, const char** name);
 bool attention_mfma_supported(const AttnProblem& p);

@@ -63,21 +63,21 @@ def rel_err(got: np.ndarray, ref: np.ndarray, preact: np.ndarray) -> float:
     return float(d.max())
 
 
+_forced = [None]
+
+
 @contextlib.contextmanager
 def forced_kernel(choice: str | None):
-    """Force the dispatcher ("generic", "mfma:<id>") for the calls inside."""
-    old = os.environ.get("PBK_FORCE_KERNEL")
-    if choice is None:
-        os.environ.pop("PBK_FORCE_KERNEL", None)
-    else:
-        os.environ["PBK_FORCE_KERNEL"] = choice
+    """Force the dispatcher ("generic", "mfma", "mfma:<id>") for the calls inside (this thread)."""
+    import paper_2603_06731_amd as pbk
+    old = _forced[0]
+    pbk.check(pbk.pbk_force_kernel(choice), f"pbk_force_kernel({choice!r})")
+    _forced[0] = choice
     try:
         yield
     finally:
-        if old is None:
-            os.environ.pop("PBK_FORCE_KERNEL", None)
-        else:
-            os.environ["PBK_FORCE_KERNEL"] = old
+        pbk.pbk_force_kernel(old)
+        _forced[0] = old
 
 
 def run_workload(w: wl.Workload, dev: dict, out=None, stream=None):

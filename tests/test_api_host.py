@@ -158,3 +158,29 @@ def test_residual_argument_errors(pbk):
     cr = pbk.pbk_conv2d_nhwc_residual
     assert cr(P, P, P, None, None, 1, 4, 4, 2, 2, 3, 3, 1, 1, 1, 1, 1, 1, F32, F32, 1.0, 1.0, 0) == 1
     assert cr(P, P, P, None, P, 1, 4, 4, 2, 2, 3, 3, 0, 1, 1, 1, 1, 1, F32, F32, 1.0, 1.0, 0) == 2
+
+
+def test_int8_is_not_an_input_type_of_the_plain_convolution_calls(pbk):
+    """PBK_INT8 (5) reaches the quantised epilogue only through pbk_conv2d_nhwc_int8, which checks
+    its own parameters; every other convolution entry point must refuse it before any launch."""
+    P = 0x1000
+    INT8, F32 = 5, 0
+    geom = (1, 8, 8, 16, 16, 3, 3, 1, 1)                     # N H W Cin Cout KH KW stride
+    for out in (F32, INT8):
+        assert pbk.pbk_conv2d_nhwc(P, P, P, None, *geom, 1, 1, 1, 1, INT8, out, 1.0, 0) == 5
+        assert pbk.pbk_conv2d_nhwc_pad4(P, P, P, None, *geom, 1, 1, 1, 1, 1, 1, INT8, out, 1.0, 0) == 5
+        assert pbk.pbk_conv2d_transpose_nhwc(P, P, P, None, *geom, 1, 1, 0, 0, 1, 1, INT8, out, 1.0, 0) == 5
+        assert pbk.pbk_conv2d_nhwc_residual(P, P, P, None, P, *geom, 1, 1, 1, 1, INT8, out, 1.0, 1.0, 0) == 5
+    assert pbk.pbk_matmul_residual(P, P, P, None, P, 2, 2, 2, 2, 2, 2, 2, INT8, F32, 0, 1.0, 1.0, 0) == 5
+    # the int8 entry point itself still validates: missing scale, bad output type
+    cq = pbk.pbk_conv2d_nhwc_int8
+    assert cq(P, P, P, *geom, 1, 1, 1, 1, None, None, 0.0, None, None, 0, 1.0, INT8) == 6
+    assert cq(P, P, P, *geom, 1, 1, 1, 1, P, None, 0.0, None, None, 0, 1.0, 1) == 5
+    assert cq(P, P, P, 0, *geom[1:], 1, 1, 1, 1, P, None, 0.0, None, None, 0, 1.0, INT8) == 0     # no images
+
+
+def test_force_kernel_choices(pbk):
+    assert pbk.pbk_force_kernel("generic") == 0
+    assert pbk.pbk_force_kernel("mfma") == 0 and pbk.pbk_force_kernel("mfma:7") == 0
+    assert pbk.pbk_force_kernel("mfma:") == 7 and pbk.pbk_force_kernel("fastest") == 7
+    assert pbk.pbk_force_kernel("") == 0 and pbk.pbk_force_kernel(None) == 0
