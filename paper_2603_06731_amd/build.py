@@ -13,7 +13,9 @@ SOURCES = ["pbk_api.hip", "gemm_generic.hip", "gemm_mfma.hip", "gemm_mfma_bf16.h
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument",
+         # M0 is on the clobber list of the direct-to-LDS load statements; the compiler notes that it is a reserved register
+         "-Wno-inline-asm"]
 
 
 def _headers():

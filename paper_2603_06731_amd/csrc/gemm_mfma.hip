@@ -62,7 +62,9 @@ static int choose_config(const Problem& p) {
     // Short contractions (store-dominated) and convolutions: two 128x256 workgroups per CU, whose
     // two barrier domains fill each other's bubbles.
     // (K = 1024 / 2048: the two 128x256 workgroups are 2-5 % ahead; K = 4096 and 8192: 10 % behind)
-    if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 3072) return 7;
+    // (9 = 7 with one barrier per two k-tiles: 8192^3 739 against 757 us, the MLP shape 711 against 726 us,
+    // interleaved runs; 6 % on a 24-tile problem that is not power limited)
+    if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 3072) return 9;
     if (p.M >= 128 && p.N >= 256 && t >= 256) return 6;
     return 1;
 }
@@ -89,7 +91,8 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
     }
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
     if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1 && cfg != 6) cfg = choose_config(p);   // the ones built
-    if (!fp8 && ((cfg >= 2 && cfg <= 4) || cfg == 8)) cfg = choose_config(p);   // 16-bit types: 0, 1, 5, 6, 7 are built
+    if (!fp8 && ((cfg >= 2 && cfg <= 4) || cfg == 8)) cfg = choose_config(p);   // 16-bit types: 0, 1, 5, 6, 7, 9 are built
+    if (cfg == 9 && (p.is_conv || p.trans_b)) cfg = 7;       // 9 is built for plain row-major operands
     if (fp8) {
         // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
         // only the 64-deep configurations are built for it

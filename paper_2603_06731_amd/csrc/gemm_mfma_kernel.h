@@ -545,15 +545,19 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // Sizes BK, lda, ldb, K and the batch strides are in 2-byte units whatever T is: for the FP8
 // types the host halves them (two FP8 values per unit), the staging code only moves bytes.
 // MI: edge of the MFMA block, 32 (every type) or 16 (16-bit types: v_mfma_f32_16x16x32).
-// ADBL (16x16 blocks, plain matrices, BK = 32, four stages): A is staged 64 k deep, every other
+// ASTG 1 (16x16 blocks, plain matrices, BK = 32, four stages): A is staged 64 k deep, every other
 // k-tile, so that each direct-to-LDS load moves whole 128-byte lines of A.  With 64-byte row
 // pieces every line of A is requested from L2 twice (once per k-tile; measured: 1.5 times the
 // L1->L2 read requests of the 64-deep configurations), and that path is as loaded as the MFMA pipe.
+// ASTG 2: the same staging of A with SIX stages of B (NSTAGE = 5 sizes the LDS: 2 x 32 + 6 x 16 KiB of the 160)
+// and one barrier per PAIR of k-tiles.
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC, int MI = 32,
-          bool ADBL = false>
+          int ASTG = 0>
 __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mfma_kernel(Problem p, TileMap tmap) {
     constexpr bool S16 = MI == 16;
-    static_assert(!ADBL || (MI == 16 && MODE == MODE_DENSE && BK == 32 && NSTAGE == 4), "ADBL: see above");
+    constexpr bool ADBL = ASTG != 0;          // A staged 64 deep
+    constexpr bool PAIRB = ASTG == 2;         // ... with one barrier per pair of k-tiles
+    static_assert(!ADBL || (MI == 16 && MODE == MODE_DENSE && BK == 32 && NSTAGE == (PAIRB ? 5 : 4)), "ASTG: see above");
     constexpr int BKA = ADBL ? 64 : BK;          // depth of one staged piece of A
     // raised wave priority around the MFMA groups: measured +1..2.5 % for one 256x256 workgroup per CU
     // and for the convolution, -1 % for two 128x256 workgroups per CU on plain matrices
@@ -1109,7 +1113,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             // B(t+3); while an odd tile, B(t+3) only.  The A loads of a tile come first in issue order.
             constexpr int AP_BYTES = BM * 128;
             constexpr int B_REGION = 2 * AP_BYTES;
-            static_assert(B_REGION + 4 * B_BYTES == NSTAGE * STAGE, "same LDS footprint as the plain ring");
+            static_assert(B_REGION + (PAIRB ? 6 : 4) * B_BYTES == NSTAGE * STAGE, "LDS footprint: NSTAGE plain stages");
             auto a_lds = [&](int t) { return ((t >> 1) & 1) * AP_BYTES; };
             auto b_lds = [&](int t) { return B_REGION + (t & 3) * B_BYTES; };
             int4v ad_ra = make_rsrc(a_tile), ad_rb = make_rsrc(b_tile);
@@ -1135,119 +1139,286 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     dst[i] = *(const short8v*)(sa + kmajor_offset<64, true>(row, h * 4 + f16_kc));
                 }
             };
-            constexpr int NT = 2 * FMH * FN;           // MFMAs per k-tile
-            constexpr int NB = FMH * FN;               // of which before the barrier
-            // L loads are spread over the tile: load r right after MFMA number r NT / L; pieces before the barrier:
-            auto early_of = [](int L) { return L == 0 ? 0 : ((NB * L + NT - 1) / NT < L ? (NB * L + NT - 1) / NT : L); };
-            auto mfma2 = [&](int st, int bcur, auto l_tag, auto&& mid) {
-                constexpr int L = decltype(l_tag)::value;     // CA + CB: A pieces then B pieces; CB: B pieces; 0: none
+            if constexpr (PAIRB) {
+                // ---- one barrier per PAIR of k-tiles.  LDS: the two pieces of A, then six stages of B; k-tile t
+                // reads half t%2 of A piece (t/2)%2 and B stage t%6.  A pair is four quarters of QM MFMAs (tile,
+                // rows half).  Its barrier stands in front of the LAST quarter, when every LDS read of the pair has
+                // been issued; the next pair's first fragments are read under that last quarter.  Loads: B of pair
+                // p+2 (its stages were last read by pair p-1, which ended at the previous barrier) goes out during
+                // the first three quarters of pair p, A of pair p+2 (into the piece pair p has just finished with)
+                // during the last quarter.  A wave's loads complete in issue order -- B(p+1), A(p+1), B(p+2),
+                // A(p+2), ... -- so at the barrier of pair p all but the 2 CB loads of B(p+2) must have landed.
+                constexpr int NBS = 6;
+                constexpr int QM = FMH * FN;
+                static_assert(QM % CA == 0 && (3 * QM) % (4 * CB) == 0, "load positions");
+                auto stage_add = [](int sidx, int d) { const int r = sidx + d; return r >= NBS ? r - NBS : r; };
+                auto b_at = [&](int sidx) { return B_REGION + sidx * B_BYTES; };
+                int bstage = 0;                  // B stage of the even tile of the current pair
+                int pair_burst = 0;              // drain: loads issued at the start of the current pair
+                auto a_frag = [&](const char* sa, int h, int rh, int i) -> short8v {
+                    const int row = wm * WTM + (rh * FMH + i) * 16 + f16_row;
+                    return *(const short8v*)(sa + kmajor_offset<64, true>(row, h * 4 + f16_kc));
+                };
+                // quarter Q of the pair whose even tile is t: tile Q/2, rows half Q%2, B fragments in bf[Q/2].
+                // STEADY: B load r of the pair goes after MFMA (2r+1) 3QM/(4CB) of the pair, A load r after
+                // MFMA 3QM + r QM/CA.
+                auto quarter = [&](auto q_tag, auto steady_tag, int t, auto&& mid) {
+                    constexpr int Q = decltype(q_tag)::value;
+                    constexpr bool STEADY = decltype(steady_tag)::value;
+                    constexpr int st = Q & 1, P = Q >> 1;
 #pragma unroll
-                for (int i = 0; i < FMH; ++i)
+                    for (int i = 0; i < FMH; ++i)
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) {
-                        acc[st * FMH + i][j] = MfmaOp16<T>::run(bf[bcur][j], af[st][i], acc[st * FMH + i][j]);
-                        mid(i * FN + j);
-                        const int idx = (st * FMH + i) * FN + j;
+                        for (int j = 0; j < FN; ++j) {
+                            acc[st * FMH + i][j] = MfmaOp16<T>::run(bf[P][j], af[st][i], acc[st * FMH + i][j]);
+                            mid(i * FN + j);
+                            if (STEADY) {
+                                const int idx = Q * QM + i * FN + j;
 #pragma unroll
-                        for (int r = 0; r < L; ++r) {
-                            if ((r * NT) / L == idx) {
-                                if (L > CB && r < CA) issue_a(r, TailNo{}); else issue_b(L > CB ? r - CA : r, TailNo{});
-                                __builtin_amdgcn_sched_barrier(0);
+                                for (int r = 0; r < 2 * CB; ++r) {
+                                    if ((2 * r + 1) * (3 * QM) / (4 * CB) == idx) {
+                                        if (r == CB) begin_b((t + 5) * BK, b_at(stage_add(bstage, 5)));
+                                        issue_b(r % CB, TailNo{});
+                                        __builtin_amdgcn_sched_barrier(0);
+                                    }
+                                }
+#pragma unroll
+                                for (int r = 0; r < CA; ++r) {
+                                    if (3 * QM + r * (QM / CA) == idx) {
+                                        issue_a(r, TailNo{});
+                                        __builtin_amdgcn_sched_barrier(0);
+                                    }
+                                }
+                            }
+                        }
+                };
+                auto prio_up = [&]() { if (PRIO) __builtin_amdgcn_s_setprio(2); };
+                auto prio_down = [&]() { if (PRIO) __builtin_amdgcn_s_setprio(0); __builtin_amdgcn_sched_barrier(0); };
+                // steady pair: tiles t, t+1; tiles t+4, t+5 are full
+                auto pair_steady = [&](int t) {
+                    begin_b((t + 4) * BK, b_at(stage_add(bstage, 4)));
+                    begin_a((t + 4) * BK, a_lds(t + 4));
+                    const char* sa = lds + a_lds(t);
+                    const char* sb1 = lds + b_at(stage_add(bstage, 1));
+                    prio_up();
+                    quarter(IntTag<0>{}, BoolTag<true>{}, t, [&](int k) {
+                        if (k < FMH) { af[1][k] = a_frag(sa, 0, 1, k); __builtin_amdgcn_sched_barrier(0); }
+                    });
+                    prio_down();
+                    prio_up();
+                    quarter(IntTag<1>{}, BoolTag<true>{}, t, [&](int k) {
+                        if (k < FMH) { af[0][k] = a_frag(sa, 1, 0, k); __builtin_amdgcn_sched_barrier(0); }
+                        else if (k < FMH + FN) { bf[1][k - FMH] = read_b1(sb1, 0, k - FMH); __builtin_amdgcn_sched_barrier(0); }
+                    });
+                    prio_down();
+                    prio_up();
+                    quarter(IntTag<2>{}, BoolTag<true>{}, t, [&](int k) {
+                        if (k < FMH) { af[1][k] = a_frag(sa, 1, 1, k); __builtin_amdgcn_sched_barrier(0); }
+                    });
+                    prio_down();
+                    wait_vmcnt<2 * CB>();
+                    __syncthreads();          // also: everyone is done reading what the next loads overwrite
+                    const char* na = lds + a_lds(t + 2);
+                    const char* nb = lds + b_at(stage_add(bstage, 2));
+                    prio_up();
+                    quarter(IntTag<3>{}, BoolTag<true>{}, t, [&](int k) {
+                        if (k < FMH) { af[0][k] = a_frag(na, 0, 0, k); __builtin_amdgcn_sched_barrier(0); }
+                        else if (k < FMH + FN) { bf[0][k - FMH] = read_b1(nb, 0, k - FMH); __builtin_amdgcn_sched_barrier(0); }
+                    });
+                    prio_down();
+                    bstage = stage_add(bstage, 2);
+                };
+                // drain: one tile t of parity PAR, loads issued in bursts and only where tiles exist
+                auto drain_tile = [&](auto par_tag, int t, bool have_next) {
+                    constexpr int PAR = decltype(par_tag)::value;
+                    if (PAR == 0) {
+                        pair_burst = 0;
+                        for (int d = 4; d <= 5; ++d) {
+                            if (t + d < KT) {
+                                begin_b((t + d) * BK, b_at(stage_add(bstage, d)));
+#pragma unroll
+                                for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                                pair_burst += CB;
                             }
                         }
                     }
-            };
-            auto wait_rt = [&](int n) {
-                if (n >= CA + CB) wait_vmcnt<CA + CB>(); else if (n >= CA) wait_vmcnt<CA>();
-                else if (n >= CB) wait_vmcnt<CB>(); else wait_vmcnt<0>();
-            };
-            // one k-tile t (half h = t % 2).  PHASE as above; L > 0: steady state with L loads spread; else
-            // `burst` loads were issued at the start of the tile.  The fragment reads (second rows half of
-            // this tile, then the first fragments of the next one after the barrier) go one at a time
-            // between the MFMAs, like in the plain pipeline below.
-            auto tile2 = [&](int t, int h, bool have_next, auto phase_tag, auto l_tag, int burst) {
-                constexpr int PHASE = decltype(phase_tag)::value;
-                constexpr int L = decltype(l_tag)::value;
-                constexpr int P = PHASE == 2 ? 1 : 0;
-                const char* sa = lds + a_lds(t);
-                if (PRIO) __builtin_amdgcn_s_setprio(2);
-                mfma2(0, P, l_tag, [&](int k) {
-                    if (k < FMH) {
-                        const int row = wm * WTM + (FMH + k) * 16 + f16_row;
-                        af[1][k] = *(const short8v*)(sa + kmajor_offset<64, true>(row, h * 4 + f16_kc));
-                        __builtin_amdgcn_sched_barrier(0);
+                    const char* sa = lds + a_lds(t);
+                    prio_up();
+                    quarter(IntTag<2 * PAR>{}, BoolTag<false>{}, t, [&](int k) {
+                        if (k < FMH) { af[1][k] = a_frag(sa, PAR, 1, k); __builtin_amdgcn_sched_barrier(0); }
+                    });
+                    prio_down();
+                    if (PAR == 1 && have_next) {
+                        if (pair_burst >= 2 * CB) wait_vmcnt<2 * CB>(); else if (pair_burst >= CB) wait_vmcnt<CB>();
+                        else wait_vmcnt<0>();
+                        __syncthreads();
+                        if (t + 3 < KT) {
+                            begin_a((t + 3) * BK, a_lds(t + 3));
+#pragma unroll
+                            for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                        }
                     }
-                });
-                if (PRIO) __builtin_amdgcn_s_setprio(0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (have_next) {
-                    // What tile t+1 reads must have landed; a wave's loads complete in issue order, so it
-                    // waits until only the loads issued after those are outstanding.  Steady state, even t:
-                    // A(t, t+1) and B(t+1) were issued during tile t-2; younger are B(t+2) from tile t-1
-                    // (CB loads) and the early_of(CA + CB) pieces of this tile issued so far.  Odd t:
-                    // A(t+1, t+2) are the first CA loads of tile t-1 and B(t+1) is older; younger are the
-                    // CB loads of B(t+2) that followed them and the early_of(CB) pieces of this tile.
-                    // Drain: everything but this tile's own burst.
-                    if (L > 0) wait_vmcnt<CB + early_of(L)>(); else wait_rt(burst);
-                    __syncthreads();      // also: everyone is done reading what the next loads overwrite
-                }
-                const char* na = lds + a_lds(t + 1);
-                const char* nb = lds + b_lds(t + 1);
-                if (PRIO) __builtin_amdgcn_s_setprio(2);
-                mfma2(1, P, l_tag, [&](int k) {
-                    if (!have_next) return;
-                    if (k < FMH) {
-                        const int row = wm * WTM + k * 16 + f16_row;
-                        af[0][k] = *(const short8v*)(na + kmajor_offset<64, true>(row, (h ^ 1) * 4 + f16_kc));
-                        __builtin_amdgcn_sched_barrier(0);
-                    } else if (k < FMH + FN) {
-                        bf[P ^ 1][k - FMH] = read_b1(nb, 0, k - FMH);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                });
-                if (PRIO) __builtin_amdgcn_s_setprio(0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (PHASE == 0 && have_next) {
+                    const char* na = lds + a_lds(t + 1);
+                    const char* nb = lds + b_at(stage_add(bstage, PAR + 1));
+                    prio_up();
+                    quarter(IntTag<2 * PAR + 1>{}, BoolTag<false>{}, t, [&](int k) {
+                        if (!have_next) return;
+                        if (k < FMH) { af[0][k] = a_frag(na, PAR ^ 1, 0, k); __builtin_amdgcn_sched_barrier(0); }
+                        else if (k < FMH + FN) { bf[PAR ^ 1][k - FMH] = read_b1(nb, 0, k - FMH); __builtin_amdgcn_sched_barrier(0); }
+                    });
+                    prio_down();
+                    if (PAR == 1) bstage = stage_add(bstage, 2);
+                };
+                if (KT > 0) {
+                    // what pair 0 reads first, then what pair 1 reads; the first barrier waits for the former only
+                    begin_a(0, a_lds(0));
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) bf[0][j] = bf[1][j];
-                }
-            };
-            if (KT > 0) {
-                begin_a(0, a_lds(0));
-#pragma unroll
-                for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
-                for (int t = 0; t < 3 && t < KT; ++t) {
-                    begin_b(t * BK, b_lds(t));
-#pragma unroll
-                    for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
-                }
-                wait_vmcnt<0>();
-                __syncthreads();
-                read_a2(lds + a_lds(0), 0, 0, af[0]);
-                read_b(lds + b_lds(0), 0, bf[0]);
-                int t = 0;
-                for (; t + 4 < KF; t += 2) {
-                    begin_a((t + 2) * BK, a_lds(t + 2));
-                    begin_b((t + 3) * BK, b_lds(t + 3));
-                    tile2(t, 0, true, IntTag<1>{}, IntTag<CA + CB>{}, 0);
-                    begin_b((t + 4) * BK, b_lds(t + 4));
-                    tile2(t + 1, 1, true, IntTag<2>{}, IntTag<CB>{}, 0);
-                }
-                for (; t < KT; ++t) {
-                    int burst = 0;
-                    if (!(t & 1) && t + 2 < KT) {
-                        begin_a((t + 2) * BK, a_lds(t + 2));
-#pragma unroll
-                        for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
-                        burst += CA;
-                    }
-                    if (t + 3 < KT) {
-                        begin_b((t + 3) * BK, b_lds(t + 3));
+                    for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                    for (int t = 0; t < 2 && t < KT; ++t) {
+                        begin_b(t * BK, b_at(t));
 #pragma unroll
                         for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
-                        burst += CB;
                     }
-                    tile2(t, t & 1, t + 1 < KT, IntTag<0>{}, IntTag<0>{}, burst);
+                    int later = 0;
+                    if (2 < KT) {
+                        begin_a(2 * BK, a_lds(2));
+#pragma unroll
+                        for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                        later += CA;
+                    }
+                    for (int t = 2; t < 4 && t < KT; ++t) {
+                        begin_b(t * BK, b_at(t));
+#pragma unroll
+                        for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                        later += CB;
+                    }
+                    if (later >= CA + 2 * CB) wait_vmcnt<CA + 2 * CB>(); else if (later >= CA + CB) wait_vmcnt<CA + CB>();
+                    else wait_vmcnt<0>();
+                    __syncthreads();
+                    read_a2(lds + a_lds(0), 0, 0, af[0]);
+                    read_b(lds + b_at(0), 0, bf[0]);
+                    int t = 0;
+                    for (; t + 6 <= KF; t += 2) pair_steady(t);
+                    for (; t < KT; t += 2) {
+                        drain_tile(IntTag<0>{}, t, t + 1 < KT);
+                        if (t + 1 < KT) drain_tile(IntTag<1>{}, t + 1, t + 2 < KT);
+                    }
+                }
+            } else {
+                constexpr int NT = 2 * FMH * FN;           // MFMAs per k-tile
+                constexpr int NB = FMH * FN;               // of which before the barrier
+                // L loads are spread over the tile: load r right after MFMA number r NT / L; pieces before the barrier:
+                auto early_of = [](int L) { return L == 0 ? 0 : ((NB * L + NT - 1) / NT < L ? (NB * L + NT - 1) / NT : L); };
+                auto mfma2 = [&](int st, int bcur, auto l_tag, auto&& mid) {
+                    constexpr int L = decltype(l_tag)::value;     // CA + CB: A pieces then B pieces; CB: B pieces; 0: none
+    #pragma unroll
+                    for (int i = 0; i < FMH; ++i)
+    #pragma unroll
+                        for (int j = 0; j < FN; ++j) {
+                            acc[st * FMH + i][j] = MfmaOp16<T>::run(bf[bcur][j], af[st][i], acc[st * FMH + i][j]);
+                            mid(i * FN + j);
+                            const int idx = (st * FMH + i) * FN + j;
+    #pragma unroll
+                            for (int r = 0; r < L; ++r) {
+                                if ((r * NT) / L == idx) {
+                                    if (L > CB && r < CA) issue_a(r, TailNo{}); else issue_b(L > CB ? r - CA : r, TailNo{});
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                            }
+                        }
+                };
+                auto wait_rt = [&](int n) {
+                    if (n >= CA + CB) wait_vmcnt<CA + CB>(); else if (n >= CA) wait_vmcnt<CA>();
+                    else if (n >= CB) wait_vmcnt<CB>(); else wait_vmcnt<0>();
+                };
+                // one k-tile t (half h = t % 2).  PHASE as above; L > 0: steady state with L loads spread; else
+                // `burst` loads were issued at the start of the tile.  The fragment reads (second rows half of
+                // this tile, then the first fragments of the next one after the barrier) go one at a time
+                // between the MFMAs, like in the plain pipeline below.
+                auto tile2 = [&](int t, int h, bool have_next, auto phase_tag, auto l_tag, int burst) {
+                    constexpr int PHASE = decltype(phase_tag)::value;
+                    constexpr int L = decltype(l_tag)::value;
+                    constexpr int P = PHASE == 2 ? 1 : 0;
+                    const char* sa = lds + a_lds(t);
+                    if (PRIO) __builtin_amdgcn_s_setprio(2);
+                    mfma2(0, P, l_tag, [&](int k) {
+                        if (k < FMH) {
+                            const int row = wm * WTM + (FMH + k) * 16 + f16_row;
+                            af[1][k] = *(const short8v*)(sa + kmajor_offset<64, true>(row, h * 4 + f16_kc));
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    });
+                    if (PRIO) __builtin_amdgcn_s_setprio(0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (have_next) {
+                        // What tile t+1 reads must have landed; a wave's loads complete in issue order, so it
+                        // waits until only the loads issued after those are outstanding.  Steady state, even t:
+                        // A(t, t+1) and B(t+1) were issued during tile t-2; younger are B(t+2) from tile t-1
+                        // (CB loads) and the early_of(CA + CB) pieces of this tile issued so far.  Odd t:
+                        // A(t+1, t+2) are the first CA loads of tile t-1 and B(t+1) is older; younger are the
+                        // CB loads of B(t+2) that followed them and the early_of(CB) pieces of this tile.
+                        // Drain: everything but this tile's own burst.
+                        if (L > 0) wait_vmcnt<CB + early_of(L)>(); else wait_rt(burst);
+                        __syncthreads();      // also: everyone is done reading what the next loads overwrite
+                    }
+                    const char* na = lds + a_lds(t + 1);
+                    const char* nb = lds + b_lds(t + 1);
+                    if (PRIO) __builtin_amdgcn_s_setprio(2);
+                    mfma2(1, P, l_tag, [&](int k) {
+                        if (!have_next) return;
+                        if (k < FMH) {
+                            const int row = wm * WTM + k * 16 + f16_row;
+                            af[0][k] = *(const short8v*)(na + kmajor_offset<64, true>(row, (h ^ 1) * 4 + f16_kc));
+                            __builtin_amdgcn_sched_barrier(0);
+                        } else if (k < FMH + FN) {
+                            bf[P ^ 1][k - FMH] = read_b1(nb, 0, k - FMH);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    });
+                    if (PRIO) __builtin_amdgcn_s_setprio(0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (PHASE == 0 && have_next) {
+    #pragma unroll
+                        for (int j = 0; j < FN; ++j) bf[0][j] = bf[1][j];
+                    }
+                };
+                if (KT > 0) {
+                    begin_a(0, a_lds(0));
+    #pragma unroll
+                    for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                    for (int t = 0; t < 3 && t < KT; ++t) {
+                        begin_b(t * BK, b_lds(t));
+    #pragma unroll
+                        for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                    }
+                    wait_vmcnt<0>();
+                    __syncthreads();
+                    read_a2(lds + a_lds(0), 0, 0, af[0]);
+                    read_b(lds + b_lds(0), 0, bf[0]);
+                    int t = 0;
+                    for (; t + 4 < KF; t += 2) {
+                        begin_a((t + 2) * BK, a_lds(t + 2));
+                        begin_b((t + 3) * BK, b_lds(t + 3));
+                        tile2(t, 0, true, IntTag<1>{}, IntTag<CA + CB>{}, 0);
+                        begin_b((t + 4) * BK, b_lds(t + 4));
+                        tile2(t + 1, 1, true, IntTag<2>{}, IntTag<CB>{}, 0);
+                    }
+                    for (; t < KT; ++t) {
+                        int burst = 0;
+                        if (!(t & 1) && t + 2 < KT) {
+                            begin_a((t + 2) * BK, a_lds(t + 2));
+    #pragma unroll
+                            for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                            burst += CA;
+                        }
+                        if (t + 3 < KT) {
+                            begin_b((t + 3) * BK, b_lds(t + 3));
+    #pragma unroll
+                            for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                            burst += CB;
+                        }
+                        tile2(t, t & 1, t + 1 < KT, IntTag<0>{}, IntTag<0>{}, burst);
+                    }
                 }
             }
         } else {

@@ -25,6 +25,7 @@ static const MfmaConfig kMfmaConfigs[] = {
     {6, 128, 256, 32, 1, 4, 3, "mfma16_128x256x32_w1x4_s3_occ2"},
     {7, 256, 256, 32, 2, 4, 4, "mfma16_256x256x32_w2x4_s4_a64"},    // A staged 64 deep (plain matrices)
     {8, 256, 256, 64, 2, 4, 2, "mfma16_256x256x64_w2x4_s2"},        // int8, both operands k-major (16x16x64 blocks)
+    {9, 256, 256, 32, 2, 4, 5, "mfma16_256x256x32_w2x4_a64_b6_pair"},   // as 7 with six B stages, one barrier per two k-tiles
 };
 static const int kNumMfmaConfigs = sizeof(kMfmaConfigs) / sizeof(kMfmaConfigs[0]);
 
@@ -51,10 +52,10 @@ inline hipError_t device_shape(int dev, DeviceShape* out) {
 }
 
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC, int MI = 32,
-          bool ADBL = false>
+          int ASTG = 0>
 hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     constexpr int LDS_BYTES = NSTAGE * (BM * BK * 2 + BN * BK * 2);
-    auto kern = gemm_mfma_kernel<T, TO, BM, BN, BK, WM, WN, MODE, NSTAGE, OCC, MI, ADBL>;
+    auto kern = gemm_mfma_kernel<T, TO, BM, BN, BK, WM, WN, MODE, NSTAGE, OCC, MI, ASTG>;
     static std::atomic<unsigned> attr_done{0};      // bit per device
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -84,8 +85,12 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
     return hipLaunchKernel((const void*)kern, dim3((unsigned)total), dim3(WM * WN * 64), args, LDS_BYTES, stream);
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1, int MI = 32, bool ADBL = false>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1, int MI = 32, int ASTG = 0>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
+    if constexpr (ASTG == 2) {            // built for plain row-major operands only
+        if (p.is_conv || p.trans_b) return hipErrorInvalidValue;
+        return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC, MI, ASTG>(p, stream, group_m);
+    } else {
     if (p.is_conv && p.conv.transposed) {
         // the transposed form is built for the two configurations the dispatcher picks
         if constexpr ((BM == 128 && BN == 256 && BK == 32) || (BM == 128 && BN == 128 && BK == 64))
@@ -95,7 +100,8 @@ hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
     }
     if (p.is_conv) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC, MI>(p, stream, group_m);
     if (p.trans_b) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC, MI>(p, stream, group_m);
-    return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC, MI, ADBL>(p, stream, group_m);
+    return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC, MI, ASTG>(p, stream, group_m);
+    }
 }
 
 // PBK_CFG_MASK (build-time, development only): bit i set = compile configuration i.
@@ -112,7 +118,8 @@ hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int grou
     // 2-4 (32x32 blocks) are not built for the 16-bit types: their 16x16 twins 5-7 replaced them
     PBK_CASE(5, 256, 256, 32, 2, 4, 4, 1, 16)
     PBK_CASE(6, 128, 256, 32, 1, 4, 3, 2, 16)
-    PBK_CASE(7, 256, 256, 32, 2, 4, 4, 1, 16, true)
+    PBK_CASE(7, 256, 256, 32, 2, 4, 4, 1, 16, 1)
+    PBK_CASE(9, 256, 256, 32, 2, 4, 5, 1, 16, 2)
     default: return hipErrorInvalidValue;
     }
 }

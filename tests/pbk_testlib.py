@@ -175,6 +175,63 @@ def oracle_sampled(w: wl.Workload, host: dict, b, i, j):
                                     batch=w.batch, M=w.M, N=w.N, K=w.K)
 
 
+def tile_lines(w: wl.Workload, block: int = 128, seed: int = 2):
+    """One complete output row in every `block` rows and one complete output column in every `block`
+    columns, of every batch entry, at seeded offsets inside the blocks: with block = 128 every
+    workgroup tile of every configuration (128 or 256 on a side) is crossed by at least one full
+    row and one full column.  Returns (rows, cols): row and column indices in GEMM coordinates."""
+    m, n, _ = w.gemm_mnk
+    r = np.random.default_rng(seed)
+    rows = np.array([min(m - 1, q * block + int(r.integers(0, block))) for q in range((m + block - 1) // block)], dtype=np.int64)
+    cols = np.array([min(n - 1, q * block + int(r.integers(0, block))) for q in range((n + block - 1) // block)], dtype=np.int64)
+    return rows, cols
+
+
+def oracle_tile_lines(w: wl.Workload, host: dict, rows, cols):
+    """The oracle on the complete rows `rows` and the complete columns `cols` of every batch entry:
+    (row_ref [batch][len(rows)][N], row_pre, col_ref [batch][M][len(cols)], col_pre), float64."""
+    import oracle
+    m, n, k = w.gemm_mnk
+    if w.kind == "conv":
+        assert not w.transposed and not w.pad4
+        pix = w.OH * w.OW
+
+        def at(i, j):
+            sn, rem = i // pix, i % pix
+            return oracle.conv2d_nhwc_at(host["a"], host["b"], host["bias"], sn, rem // w.OW, rem % w.OW, j,
+                                         dtype=w.in_dtype, stride=w.stride, pad=w.pad, dil=w.dil,
+                                         alpha=w.alpha, epi=w.epi)
+        ri, rj = np.meshgrid(rows, np.arange(n, dtype=np.int64), indexing="ij")
+        ro, rp = at(ri.reshape(-1), rj.reshape(-1))
+        ci, cj = np.meshgrid(np.arange(m, dtype=np.int64), cols, indexing="ij")
+        co, cp = at(ci.reshape(-1), cj.reshape(-1))
+        return (ro.reshape(1, len(rows), n), rp.reshape(1, len(rows), n),
+                co.reshape(1, m, len(cols)), cp.reshape(1, m, len(cols)))
+    a = host["a"].reshape(w.batch, m, k)
+    b = host["b"].reshape(w.batch, n, k) if w.trans_b else host["b"].reshape(w.batch, k, n)
+    bias = host["bias"]
+    ro = np.empty((w.batch, len(rows), n)); rp = np.empty_like(ro)
+    co = np.empty((w.batch, m, len(cols))); cp = np.empty_like(co)
+    for e in range(w.batch):
+        ro[e], rp[e] = oracle.matmul(np.ascontiguousarray(a[e][rows]), b[e], bias, dtype=w.in_dtype,
+                                     trans_b=w.trans_b, alpha=w.alpha, epi=w.epi, want_preact=True)
+        bsub = np.ascontiguousarray(b[e][cols] if w.trans_b else b[e][:, cols])
+        co[e], cp[e] = oracle.matmul(a[e], bsub, None if bias is None else np.ascontiguousarray(bias[cols]),
+                                     dtype=w.in_dtype, trans_b=w.trans_b, alpha=w.alpha, epi=w.epi, want_preact=True)
+    return ro, rp, co, cp
+
+
+def gather_tile_lines(out_t, w: wl.Workload, rows, cols):
+    """The same rows and columns of the device output (flat [batch][M][N]) as float64."""
+    torch = torch_mod()
+    m, n, _ = w.gemm_mnk
+    o = out_t.view(w.batch, m, n)
+    r = o[:, torch.from_numpy(rows).cuda(), :].contiguous()
+    c = o[:, :, torch.from_numpy(cols).cuda()].contiguous()
+    return (to_host_f64(r.view(-1), w.out_dtype).reshape(w.batch, len(rows), n),
+            to_host_f64(c.view(-1), w.out_dtype).reshape(w.batch, m, len(cols)))
+
+
 def gather_output(out_t, w: wl.Workload, b, i, j) -> np.ndarray:
     """Pick sampled outputs from the device tensor (flat [batch][M][N]) as float64."""
     torch = torch_mod()

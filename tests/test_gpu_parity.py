@@ -11,7 +11,7 @@ import pbk_testlib as T
 pytestmark = pytest.mark.gpu
 
 BF16, F16, F32 = wl.DTYPE_BF16, wl.DTYPE_F16, wl.DTYPE_F32
-MFMA_CONFIGS = [0, 1, 5, 6, 7]          # the configurations built for the 16-bit types
+MFMA_CONFIGS = [0, 1, 5, 6, 7, 9]       # the configurations built for the 16-bit types
 
 
 def tol_for(w):
@@ -63,20 +63,23 @@ def test_matmul_bf16_mfma_configs(cfg, mnk):
     check_full(w, force=f"mfma:{cfg}", expect_kernel="mfma")
 
 
+@pytest.mark.parametrize("cfg", [7, 9])
 @pytest.mark.parametrize("dtype", [BF16, F16])
-@pytest.mark.parametrize("k", [8, 40, 64, 72, 128, 136, 168, 200, 264, 328, 1096])
-def test_matmul_a_staged_64_deep_k_sweep(dtype, k):
-    """Configuration 7 stages A every other k-tile: prologue only, drain only, odd and even numbers
-    of k-tiles, ragged last tile, and enough tiles for the paired steady state."""
+@pytest.mark.parametrize("k", [8, 40, 64, 72, 96, 128, 136, 160, 168, 192, 200, 224, 232, 264, 328, 392, 1096])
+def test_matmul_a_staged_64_deep_k_sweep(cfg, dtype, k):
+    """Configurations 7 and 9 stage A every other k-tile (9 with six B stages and one barrier per pair of
+    k-tiles): prologue only, drain only, odd and even numbers of k-tiles (1 to 13 and 35), a ragged
+    last tile, and enough tiles for the paired steady state."""
     w = wl.Workload(f"mm_a64_k{k}", "matmul", dtype, dtype, C.EPI_BIAS, M=300, N=520, K=k,
                     dist_b=("normal", 1.0 / np.sqrt(k)), dist_bias=("normal", 0.5))
-    check_full(w, force="mfma:7", expect_kernel="a64")
+    check_full(w, force=f"mfma:{cfg}", expect_kernel="a64")
 
 
-def test_batched_on_a_staged_64_deep():
+@pytest.mark.parametrize("cfg", [7, 9])
+def test_batched_on_a_staged_64_deep(cfg):
     w = wl.Workload("bmm_a64", "batched", BF16, F32, C.EPI_NONE, alpha=0.5, batch=3, M=264, N=256, K=392,
                     dist_b=("normal", 0.05))
-    check_full(w, force="mfma:7", expect_kernel="a64")
+    check_full(w, force=f"mfma:{cfg}", expect_kernel="a64")
 
 
 @pytest.mark.parametrize("dtype", [BF16, F16])
@@ -192,6 +195,16 @@ def test_full_size_sampled(name):
     print(f"{name} kernel={kern} samples={len(i)} err={err:.3e}", flush=True)
     assert "mfma" in kern
     assert err <= T.TOL_16BIT and err <= T.TIGHT[w.out_dtype], err
+    # every workgroup tile: one complete row per 128 rows and one complete column per 128 columns
+    rows, cols = T.tile_lines(w)
+    ro, rp, co, cp = T.oracle_tile_lines(w, host, rows, cols)
+    gr, gc = T.gather_tile_lines(out, w, rows, cols)
+    floor_pre = np.concatenate([rp.reshape(-1), cp.reshape(-1)])
+    err_r = T.rel_err(gr, ro, floor_pre)
+    err_c = T.rel_err(gc, co, floor_pre)
+    print(f"{name} complete rows {len(rows)} x batch {w.batch}: err={err_r:.3e}; complete columns {len(cols)}: "
+          f"err={err_c:.3e}", flush=True)
+    assert max(err_r, err_c) <= T.TIGHT[w.out_dtype], (err_r, err_c)
     if name == "cfg2_bf16_8192":
         # bias dominates that output; also check the bare contraction
         w2 = wl.Workload("cfg2_noepi", "matmul", BF16, BF16, C.EPI_NONE, M=w.M, N=w.N, K=w.K,
@@ -217,7 +230,7 @@ def test_views_ignore_nan_outside_and_guard_band_survives():
     da, db = T.to_device(a), T.to_device(b)
     sentinel = 0x5A5A
     out = T.device_empty(M * ldc + 64, BF16, fill=np.array(sentinel, dtype=np.uint16).view(np.int16).item())
-    for force in ("mfma:0", "mfma:1", "mfma:5", "mfma:7", "generic"):
+    for force in ("mfma:0", "mfma:1", "mfma:5", "mfma:7", "mfma:9", "generic"):
         with T.forced_kernel(force):
             st = pbk.pbk_matmul(da, db, out, None, M, N, K, lda, ldb, ldc, BF16, BF16, 0, 1.0, C.EPI_NONE)
         assert st == 0
@@ -241,7 +254,17 @@ def test_run_to_run_bit_exact():
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
-@pytest.mark.parametrize("cfg", [5, 6, 7])
+_det_big_cache = {}
+
+
+def _det_big_oracle(w, host):
+    """The oracle's full result for the long many-tile case, computed once per session."""
+    if "ref" not in _det_big_cache:
+        _det_big_cache["ref"] = T.oracle_full(w, host)
+    return _det_big_cache["ref"]
+
+
+@pytest.mark.parametrize("cfg", [5, 6, 7, 9])
 def test_large_run_to_run_bit_exact_and_equal_across_configurations(cfg):
     """The pipelines reuse LDS stages under explicit wait counts and one barrier per k-tile: a race
     would show as run-to-run differences on a long contraction.  All 16x16 configurations add the
@@ -250,11 +273,20 @@ def test_large_run_to_run_bit_exact_and_equal_across_configurations(cfg):
     import torch
     w = wl.Workload("det_big", "matmul", BF16, BF16, C.EPI_BIAS, M=1024, N=1536, K=8192,
                     dist_b=("normal", 1.0 / np.sqrt(8192)))
-    dev = T.upload(wl.make_inputs(w))
+    host = wl.make_inputs(w)
+    dev = T.upload(host)
     with T.forced_kernel("mfma:5"):
         st, ref = T.run_workload(w, dev)
     assert st == 0
     ref = ref.clone()
+    # the whole tensor of this configuration against the oracle, element by element
+    with T.forced_kernel(f"mfma:{cfg}"):
+        st, out = T.run_workload(w, dev)
+    assert st == 0
+    want, pre = _det_big_oracle(w, host)
+    err = T.rel_err(T.to_host_f64(out, w.out_dtype).reshape(want.shape), want, pre)
+    print(f"det_big cfg={cfg} full oracle comparison err={err:.3e}", flush=True)
+    assert err <= T.TIGHT[BF16], (cfg, err)
     for _ in range(4):
         with T.forced_kernel(f"mfma:{cfg}"):
             st, out = T.run_workload(w, dev)

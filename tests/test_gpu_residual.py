@@ -15,7 +15,7 @@ def out_tensor(n, dtype):
     return T.device_empty(n, dtype)
 
 
-@pytest.mark.parametrize("cfg", [None, 0, 1, 5, 6, 7, "generic"])
+@pytest.mark.parametrize("cfg", [None, 0, 1, 5, 6, 7, 9, "generic"])
 @pytest.mark.parametrize("mnk", [(300, 264, 200), (256, 512, 64), (33, 520, 136), (130, 257, 72)])
 @pytest.mark.parametrize("dtype,out_dtype", [(BF16, BF16), (F16, F32)])
 def test_matmul_residual(cfg, mnk, dtype, out_dtype):
@@ -41,6 +41,31 @@ def test_matmul_residual(cfg, mnk, dtype, out_dtype):
     # the residual really takes part: without it the result differs
     ref0 = oracle.matmul(A, B, bias, dtype=dtype, alpha=0.75, epi=C.EPI_BIAS_RELU)
     assert T.rel_err(got, ref0, pre) > 0.05
+
+
+@pytest.mark.parametrize("cfg", [1, 5, 6])
+@pytest.mark.parametrize("dtype,out_dtype", [(BF16, BF16), (F16, F32)])
+@pytest.mark.parametrize("n,ldc,ldr", [(257, 257, 257), (264, 267, 269)])
+def test_matmul_residual_direct_stores_on_mfma(cfg, dtype, out_dtype, n, ldc, ldr):
+    """k-major B keeps a ragged N (or C / R rows that are not 16-byte multiples) on the matrix-unit
+    kernel: the epilogue then reads the residual element by element and stores from registers."""
+    import oracle
+    import paper_2603_06731_amd as pbk
+    m, k = 130, 72
+    A = wl.tensor((m, k), dtype, 1, "normal", 1.0); B = wl.tensor((n, k), dtype, 2, "normal", 1.0 / np.sqrt(k))
+    bias = wl.tensor((n,), F32, 3, "normal", 0.5); R = wl.tensor((m, ldr), out_dtype, 8, "normal", 1.0)
+    out = out_tensor(m * ldc, out_dtype)
+    with T.forced_kernel(f"mfma:{cfg}"):
+        st = pbk.pbk_matmul_residual(T.to_device(A), T.to_device(B), out, T.to_device(bias), T.to_device(R), m, n, k,
+                                     k, k, ldc, ldr, dtype, out_dtype, 1, 0.75, -0.5, C.EPI_BIAS_GELU_TANH, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    assert "mfma" in pbk.pbk_last_kernel()
+    ref, pre = oracle.matmul_residual(A, B, bias, np.ascontiguousarray(R[:, :n]), dtype=dtype, r_dtype=out_dtype,
+                                      trans_b=1, alpha=0.75, beta=-0.5, epi=C.EPI_BIAS_GELU_TANH, want_preact=True)
+    got = T.to_host_f64(out, out_dtype).reshape(m, ldc)[:, :n]
+    err = T.rel_err(got, ref, pre)
+    print(f"residual direct n={n} ldc={ldc} cfg={cfg} kernel={pbk.pbk_last_kernel()} err={err:.3e}", flush=True)
+    assert err <= T.TIGHT[out_dtype], err
 
 
 def test_matmul_residual_fp32_generic():
