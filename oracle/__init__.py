@@ -58,6 +58,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_conv_transpose_out_dim.restype = i64
         L.oracle_matmul_int8.argtypes = ([vp, vp, vp, vp] + [i64] * 6 + [i32, vp, vp, f32, vp, vp, i32, f32, i32])
         L.oracle_conv2d_nhwc_int8.argtypes = ([vp, vp, vp, vp] + [i64] * 13 + [vp, vp, f32, vp, vp, i32, f32, i32])
+        L.oracle_matmul_int8_bn.argtypes = ([vp, vp, vp, vp] + [i64] * 6 + [i32, vp, vp, f32, vp, vp, f32, vp, vp, i32, f32, i32])
+        L.oracle_conv2d_nhwc_int8_bn.argtypes = ([vp, vp, vp, vp] + [i64] * 13
+                                                 + [vp, vp, f32, vp, vp, f32, vp, vp, i32, f32, i32])
         L.oracle_matmul_residual.argtypes = [vp, vp, vp, vp, vp, vp] + [i64] * 7 + [i32, i32, i32, f32, f32, i32]
         L.oracle_conv2d_nhwc_residual.argtypes = [vp, vp, vp, vp, vp, vp] + [i64] * 13 + [i32, i32, f32, f32, i32]
         L.oracle_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32]
@@ -354,6 +357,43 @@ def matmul_int8(A, B, *, scale, bias=None, mid_scale=0.0, mul=None, add=None, re
                                   float(out_scale), int(out_int8))
     _rc(rc, "matmul_int8")
     return (out, acc) if want_acc else out
+
+
+def matmul_int8_bn(A, B, *, scale, mean, var, eps, gamma, beta, bias=None, mid_scale=0.0, relu=False, out_scale=1.0,
+                   out_int8=True, trans_b=0):
+    """int8 matmul with the quantised epilogue whose batch-norm step is unfolded (mean, var, eps, gamma, beta)."""
+    A = np.ascontiguousarray(A); B = np.ascontiguousarray(B)
+    if A.dtype != np.int8 or B.dtype != np.int8:
+        raise TypeError("int8 operands expected")
+    M, K = A.shape
+    N = B.shape[0] if trans_b else B.shape[1]
+    scale, bias, mean, var, gamma, beta = (_f32vec(v, N, n) for v, n in (
+        (scale, "scale"), (bias, "bias"), (mean, "mean"), (var, "var"), (gamma, "gamma"), (beta, "beta")))
+    out = np.empty((M, N), dtype=np.int8 if out_int8 else np.float32)
+    rc = lib().oracle_matmul_int8_bn(_ptr(A), _ptr(B), _ptr(out), None, M, N, K, K, B.shape[1], N, int(trans_b),
+                                     _ptr(scale), _ptr(bias), float(mid_scale), _ptr(mean), _ptr(var), float(eps),
+                                     _ptr(gamma), _ptr(beta), int(relu), float(out_scale), int(out_int8))
+    _rc(rc, "matmul_int8_bn")
+    return out
+
+
+def conv2d_nhwc_int8_bn(x, w, *, scale, mean, var, eps, gamma, beta, bias=None, mid_scale=0.0, relu=False,
+                        out_scale=1.0, out_int8=True, stride=(1, 1), pad=(0, 0), dil=(1, 1)):
+    x = np.ascontiguousarray(x); w = np.ascontiguousarray(w)
+    if x.dtype != np.int8 or w.dtype != np.int8:
+        raise TypeError("int8 operands expected")
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    OH = conv_out_dim(H, KH, stride[0], pad[0], dil[0]); OW = conv_out_dim(W, KW, stride[1], pad[1], dil[1])
+    scale, bias, mean, var, gamma, beta = (_f32vec(v, Cout, n) for v, n in (
+        (scale, "scale"), (bias, "bias"), (mean, "mean"), (var, "var"), (gamma, "gamma"), (beta, "beta")))
+    out = np.empty((N, OH, OW, Cout), dtype=np.int8 if out_int8 else np.float32)
+    rc = lib().oracle_conv2d_nhwc_int8_bn(_ptr(x), _ptr(w), _ptr(out), None, N, H, W, Cin, Cout, KH, KW,
+                                          stride[0], stride[1], pad[0], pad[1], dil[0], dil[1],
+                                          _ptr(scale), _ptr(bias), float(mid_scale), _ptr(mean), _ptr(var), float(eps),
+                                          _ptr(gamma), _ptr(beta), int(relu), float(out_scale), int(out_int8))
+    _rc(rc, "conv2d_nhwc_int8_bn")
+    return out
 
 
 def conv2d_nhwc_int8(x, w, *, scale, bias=None, mid_scale=0.0, mul=None, add=None, relu=False, out_scale=1.0,

@@ -526,8 +526,13 @@ int oracle_conv2d_transpose_nhwc_at(const void* x, const void* w, const float* b
  *   t = t + bias[j]                      (if bias)
  *   if mid_scale > 0:                    the quantise / de-quantise pair that the
  *       q = clamp(roundeven(t / mid_scale), -128, 127);  t = float(q) * mid_scale
- *   t = t * mul[j]   (if mul);  t = t + add[j]   (if add)      folded batch-norm
- *   t = t > 0 ? t : 0                    (if relu)
+ *   the batch-norm step, in one of two forms:
+ *     unfolded, as the figure has it (mean, var, gamma, beta per channel and the scalar eps):
+ *       r = 1 / sqrt(var[j] + eps)       three operations: add, square root, reciprocal by division
+ *       t = t - mean[j];  t = t * r;  t = t * gamma[j];  t = t + beta[j]
+ *     folded by the caller into a multiplier and a shift:
+ *       t = t * mul[j]   (if mul);  t = t + add[j]   (if add)
+ *   t = (t > 0 or t is NaN) ? t : 0      (if relu: the figure's compare is "unordered or greater")
  *   int8 output:  clamp(roundeven(t / out_scale), -128, 127);  float output: t
  * The accumulator is the exact integer sum. */
 typedef struct {
@@ -538,6 +543,12 @@ typedef struct {
     const float* add;
     int relu;
     float out_scale;
+    /* unfolded batch norm (all four arrays, or none) */
+    const float* mean;
+    const float* var;
+    const float* gamma;
+    const float* beta;
+    float eps;
 } quant_epi;
 
 static float quantise_step(float t, float step)
@@ -558,15 +569,26 @@ static float quant_epilogue(int64_t acc, int64_t j, const quant_epi* e)
         volatile float q = quantise_step(t, e->mid_scale);
         t = q * e->mid_scale;
     }
+    if (e->mean) {
+        volatile float r = e->var[j] + e->eps;
+        r = sqrtf(r);                       /* IEEE square root: correctly rounded */
+        r = 1.0f / r;
+        t = t - e->mean[j];
+        t = t * r;
+        t = t * e->gamma[j];
+        t = t + e->beta[j];
+    }
     if (e->mul) t = t * e->mul[j];
     if (e->add) t = t + e->add[j];
-    if (e->relu) t = t > 0.0f ? t : 0.0f;
+    if (e->relu) t = !(t <= 0.0f) ? t : 0.0f;      /* greater than zero, or unordered (NaN stays) */
     return t;
 }
 
 static int check_quant(const quant_epi* e, int out_int8)
 {
     if (!e->scale) return -3;
+    if ((e->mean || e->var || e->gamma || e->beta) && !(e->mean && e->var && e->gamma && e->beta)) return -3;
+    if (e->mean && (e->mul || e->add)) return -3;          /* one form of the batch norm at a time */
     if (e->mid_scale < 0.0f || (out_int8 && !(e->out_scale > 0.0f))) return -2;
     return 0;
 }
@@ -577,14 +599,11 @@ static void store_quant(void* out, int64_t o, float t, const quant_epi* e, int o
     else ((float*)out)[o] = t;
 }
 
-int oracle_matmul_int8(const int8_t* A, const int8_t* B, void* out, int32_t* acc_out,
-                       int64_t M, int64_t N, int64_t K,
-                       int64_t lda, int64_t ldb, int64_t ldo, int trans_b,
-                       const float* scale, const float* bias, float mid_scale,
-                       const float* mul, const float* add, int relu, float out_scale,
-                       int out_int8)
+static int matmul_int8_with(const int8_t* A, const int8_t* B, void* out, int32_t* acc_out,
+                            int64_t M, int64_t N, int64_t K,
+                            int64_t lda, int64_t ldb, int64_t ldo, int trans_b,
+                            quant_epi e, int out_int8)
 {
-    quant_epi e = {scale, bias, mid_scale, mul, add, relu, out_scale};
     int rc = check_quant(&e, out_int8);
     if (rc) return rc;
     if (M < 0 || N < 0 || K < 0 || K > 131071) return -4;
@@ -602,15 +621,35 @@ int oracle_matmul_int8(const int8_t* A, const int8_t* B, void* out, int32_t* acc
     return 0;
 }
 
-int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t* acc_out,
-                            int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
-                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
-                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
-                            const float* scale, const float* bias, float mid_scale,
-                            const float* mul, const float* add, int relu, float out_scale,
-                            int out_int8)
+int oracle_matmul_int8(const int8_t* A, const int8_t* B, void* out, int32_t* acc_out,
+                       int64_t M, int64_t N, int64_t K,
+                       int64_t lda, int64_t ldb, int64_t ldo, int trans_b,
+                       const float* scale, const float* bias, float mid_scale,
+                       const float* mul, const float* add, int relu, float out_scale,
+                       int out_int8)
 {
-    quant_epi e = {scale, bias, mid_scale, mul, add, relu, out_scale};
+    quant_epi e = {scale, bias, mid_scale, mul, add, relu, out_scale, NULL, NULL, NULL, NULL, 0.0f};
+    return matmul_int8_with(A, B, out, acc_out, M, N, K, lda, ldb, ldo, trans_b, e, out_int8);
+}
+
+int oracle_matmul_int8_bn(const int8_t* A, const int8_t* B, void* out, int32_t* acc_out,
+                          int64_t M, int64_t N, int64_t K,
+                          int64_t lda, int64_t ldb, int64_t ldo, int trans_b,
+                          const float* scale, const float* bias, float mid_scale,
+                          const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                          int relu, float out_scale, int out_int8)
+{
+    if (!mean || !var || !gamma || !beta) return -3;
+    quant_epi e = {scale, bias, mid_scale, NULL, NULL, relu, out_scale, mean, var, gamma, beta, eps};
+    return matmul_int8_with(A, B, out, acc_out, M, N, K, lda, ldb, ldo, trans_b, e, out_int8);
+}
+
+static int conv2d_nhwc_int8_with(const int8_t* x, const int8_t* w, void* out, int32_t* acc_out,
+                                 int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                 int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                 int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                 quant_epi e, int out_int8)
+{
     int rc = check_quant(&e, out_int8);
     if (rc) return rc;
     if (N < 0 || Cin < 1 || Cout < 1 || KH * KW * Cin > 131071) return -4;
@@ -641,6 +680,33 @@ int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t
                 }
     }
     return 0;
+}
+
+int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t* acc_out,
+                            int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                            int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                            int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                            const float* scale, const float* bias, float mid_scale,
+                            const float* mul, const float* add, int relu, float out_scale,
+                            int out_int8)
+{
+    quant_epi e = {scale, bias, mid_scale, mul, add, relu, out_scale, NULL, NULL, NULL, NULL, 0.0f};
+    return conv2d_nhwc_int8_with(x, w, out, acc_out, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w,
+                                 dil_h, dil_w, e, out_int8);
+}
+
+int oracle_conv2d_nhwc_int8_bn(const int8_t* x, const int8_t* w, void* out, int32_t* acc_out,
+                               int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                               int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                               int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                               const float* scale, const float* bias, float mid_scale,
+                               const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                               int relu, float out_scale, int out_int8)
+{
+    if (!mean || !var || !gamma || !beta) return -3;
+    quant_epi e = {scale, bias, mid_scale, NULL, NULL, relu, out_scale, mean, var, gamma, beta, eps};
+    return conv2d_nhwc_int8_with(x, w, out, acc_out, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w,
+                                 dil_h, dil_w, e, out_int8);
 }
 
 /* ---- residual-add epilogue ------------------------------------------------ */

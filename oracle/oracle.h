@@ -157,6 +157,24 @@ int oracle_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* out, int32_t
                             const float* mul, const float* add, int relu, float out_scale,
                             int out_int8);
 
+/* The same two with the batch-norm step of the paper's figure unfolded: between the optional quantise /
+ * de-quantise pair and the ReLU,
+ *   r = 1 / sqrt(var[j] + eps);  t = t - mean[j];  t = t * r;  t = t * gamma[j];  t = t + beta[j]
+ * each one binary32 operation (the square root and the division correctly rounded), in this order. */
+int oracle_matmul_int8_bn(const int8_t* A, const int8_t* B, void* out, int32_t* acc_out,
+                          int64_t M, int64_t N, int64_t K,
+                          int64_t lda, int64_t ldb, int64_t ldo, int trans_b,
+                          const float* scale, const float* bias, float mid_scale,
+                          const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                          int relu, float out_scale, int out_int8);
+int oracle_conv2d_nhwc_int8_bn(const int8_t* x, const int8_t* w, void* out, int32_t* acc_out,
+                               int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                               int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                               int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                               const float* scale, const float* bias, float mid_scale,
+                               const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                               int relu, float out_scale, int out_int8);
+
 /* Residual-add epilogue: out = act(alpha * (A . B) + bias + beta * R), R of the
  * output's shape (row stride ldr), element type r_dtype (F32, BF16, F16),
  * widened exactly.  The convolution variant takes r [N][OH][OW][Cout]. */
