@@ -29,7 +29,7 @@
  *  - Epilogue: t = alpha * acc (+ bias[n] for the BIAS variants);
  *    out = t | max(t,0) | 0.5*t*(1+tanh(sqrt(2/pi)*(t+0.044715*t^3))).
  *    bias must be non-NULL for the BIAS variants and is ignored otherwise.
- *    max(NaN, 0) is 0 (hardware maximum).
+ *    The ReLU keeps NaN (it selects t when t > 0 or t is NaN).
  *  - Every function returns a pbk_status.  On any status other than PBK_OK
  *    nothing was launched and the output is untouched.  A dimension of zero
  *    gives PBK_OK and does nothing (K == 0 still writes act(bias)).
@@ -180,9 +180,11 @@ pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const
                                     float alpha, float beta, pbk_epilogue epi, hipStream_t stream);
 
 /*
- * int8 x int8 contraction with exact 32-bit integer accumulation and the quantised
- * epilogue of the paper's appendix on quantisation (the fused de-quantisation /
- * quantisation nest at the output of a quantised convolution), computed in
+ * int8 x int8 contraction with exact 32-bit integer accumulation and a quantised
+ * epilogue after the paper's appendix on quantisation (the fused de-quantisation /
+ * quantisation nest at the output of a quantised convolution) with the batch norm
+ * folded by the caller into a multiplier and a shift (the *_bn calls below take it
+ * unfolded, as the figure has it), computed in
  * binary32, one rounding per operation, in this order, for output column j:
  *   t = float(acc) * scale[j];           de-quantise (scale is required)
  *   t = t + bias[j]                      if bias != NULL
@@ -190,7 +192,7 @@ pbk_status pbk_conv2d_nhwc_residual(const void* x, const void* w, void* y, const
  *       t = float(clamp(roundeven(t / mid_scale), -128, 127)) * mid_scale
  *   t = t * mul[j]                       if mul != NULL   (batch-norm scale, folded by the caller)
  *   t = t + add[j]                       if add != NULL   (batch-norm shift, folded by the caller)
- *   t = t > 0 ? t : 0                    if relu != 0
+ *   t = (t > 0 or t is NaN) ? t : 0      if relu != 0   (the figure's compare is "unordered or greater")
  *   out_dtype PBK_INT8: C = int8(clamp(roundeven(t / out_scale), -128, 127)), out_scale > 0
  *   out_dtype PBK_F32:  C = t
  * Results are bit-exact for a given input whatever kernel runs.  scale, bias, mul,
@@ -215,6 +217,31 @@ pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
                                 const float* scale, const float* bias, float mid_scale,
                                 const float* mul, const float* add, int relu, float out_scale,
                                 pbk_dtype out_dtype, hipStream_t stream);
+
+/*
+ * The same two with the batch-norm step exactly as the paper's fused nest has it (appendix on
+ * quantisation, figure "IR after fusion of de-quantization and quantization"), unfolded: between the
+ * optional quantise / de-quantise pair and the ReLU,
+ *   r = 1 / sqrt(var[j] + eps)           an addition, a square root and a division (the last two
+ *                                        correctly rounded)
+ *   t = t - mean[j];  t = t * r;  t = t * gamma[j];  t = t + beta[j]
+ * each one binary32 operation, in this order.  mean, var, gamma, beta: device float arrays of N (Cout)
+ * entries, all required (PBK_ERR_EPILOGUE).  The caller-folded form above (mul = r * gamma,
+ * add = beta - mean * mul) is cheaper by two operations and differs from this one in the last place.
+ */
+pbk_status pbk_matmul_int8_bn(const int8_t* A, const int8_t* B, void* C,
+                              int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int trans_b,
+                              const float* scale, const float* bias, float mid_scale,
+                              const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                              int relu, float out_scale, pbk_dtype out_dtype, hipStream_t stream);
+
+pbk_status pbk_conv2d_nhwc_int8_bn(const int8_t* x, const int8_t* w, void* y,
+                                   int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                   int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                   int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                   const float* scale, const float* bias, float mid_scale,
+                                   const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                                   int relu, float out_scale, pbk_dtype out_dtype, hipStream_t stream);
 
 /*
  * Attention layer, every operator fused into one kernel          (paper Sec. 4.4)
@@ -260,8 +287,9 @@ const char* pbk_last_kernel(void);
 /*
  * Benchmarking and test aid, for the calls that follow ON THIS THREAD: "generic" forces
  * the fallback kernel, "mfma" the matrix-unit path with its automatic tile choice,
- * "mfma:<id>" one tile configuration (a problem it cannot run then gives
- * PBK_ERR_UNSUPPORTED); NULL or "" returns to the default.  The default is automatic
+ * "mfma:<id>" one tile configuration (operands that the direct-to-LDS kernel cannot take
+ * go to the gathering matrix-unit kernel instead), "gather" that kernel; a problem the
+ * choice cannot run gives PBK_ERR_UNSUPPORTED.  NULL or "" returns to the default.  The default is automatic
  * choice, or what the environment variable PBK_FORCE_KERNEL (same strings) held when the
  * process made its first call.  An unknown string is PBK_ERR_UNSUPPORTED and changes nothing.
  */

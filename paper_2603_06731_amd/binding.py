@@ -16,7 +16,7 @@ PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2, PBK_INT8 = 0, 1, 2, 3, 4
 
 EXPORTED_SYMBOLS = ("pbk_matmul", "pbk_batched_matmul", "pbk_conv2d_nhwc", "pbk_conv2d_nhwc_pad4",
                     "pbk_conv2d_transpose_nhwc", "pbk_attention", "pbk_matmul_int8", "pbk_conv2d_nhwc_int8",
-                    "pbk_matmul_residual", "pbk_conv2d_nhwc_residual",
+                    "pbk_matmul_residual", "pbk_conv2d_nhwc_residual", "pbk_matmul_int8_bn", "pbk_conv2d_nhwc_int8_bn",
                     "pbk_status_string", "pbk_version", "pbk_last_kernel", "pbk_force_kernel")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -65,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.pbk_matmul_int8.restype = i32
         L.pbk_conv2d_nhwc_int8.argtypes = [vp, vp, vp] + [i64] * 13 + [vp, vp, f32, vp, vp, i32, f32, i32, vp]
         L.pbk_conv2d_nhwc_int8.restype = i32
+        L.pbk_matmul_int8_bn.argtypes = [vp, vp, vp] + [i64] * 6 + [i32, vp, vp, f32, vp, vp, f32, vp, vp, i32, f32, i32, vp]
+        L.pbk_matmul_int8_bn.restype = i32
+        L.pbk_conv2d_nhwc_int8_bn.argtypes = [vp, vp, vp] + [i64] * 13 + [vp, vp, f32, vp, vp, f32, vp, vp, i32, f32, i32, vp]
+        L.pbk_conv2d_nhwc_int8_bn.restype = i32
         L.pbk_matmul_residual.argtypes = [vp, vp, vp, vp, vp] + [i64] * 7 + [i32, i32, i32, f32, f32, i32, vp]
         L.pbk_matmul_residual.restype = i32
         L.pbk_conv2d_nhwc_residual.argtypes = [vp, vp, vp, vp, vp] + [i64] * 13 + [i32, i32, f32, f32, i32, vp]
@@ -148,6 +152,21 @@ def pbk_conv2d_nhwc_int8(x, w, y, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w
     return lib().pbk_conv2d_nhwc_int8(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
                                       pad_h, pad_w, dil_h, dil_w, _ptr(scale), _ptr(bias), float(mid_scale),
                                       _ptr(mul), _ptr(add), int(relu), float(out_scale), out_dtype, _stream(stream))
+
+
+def pbk_matmul_int8_bn(A, B, C, M, N, K, lda, ldb, ldc, trans_b, scale, bias, mid_scale, mean, var, eps, gamma, beta, relu,
+                       out_scale, out_dtype, stream=None) -> int:
+    return lib().pbk_matmul_int8_bn(_ptr(A), _ptr(B), _ptr(C), M, N, K, lda, ldb, ldc, int(trans_b), _ptr(scale),
+                                    _ptr(bias), float(mid_scale), _ptr(mean), _ptr(var), float(eps), _ptr(gamma), _ptr(beta),
+                                    int(relu), float(out_scale), out_dtype, _stream(stream))
+
+
+def pbk_conv2d_nhwc_int8_bn(x, w, y, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                            scale, bias, mid_scale, mean, var, eps, gamma, beta, relu, out_scale, out_dtype, stream=None) -> int:
+    return lib().pbk_conv2d_nhwc_int8_bn(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cin, Cout, KH, KW, stride_h, stride_w,
+                                         pad_h, pad_w, dil_h, dil_w, _ptr(scale), _ptr(bias), float(mid_scale),
+                                         _ptr(mean), _ptr(var), float(eps), _ptr(gamma), _ptr(beta), int(relu),
+                                         float(out_scale), out_dtype, _stream(stream))
 
 
 def pbk_matmul_residual(A, B, C, bias, R, M, N, K, lda, ldb, ldc, ldr, in_dtype, out_dtype, trans_b,

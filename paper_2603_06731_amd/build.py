@@ -8,8 +8,16 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpbk.so")
-SOURCES = ["pbk_api.hip", "gemm_generic.hip", "gemm_mfma.hip", "gemm_mfma_bf16.hip", "gemm_mfma_f16.hip",
-           "gemm_mfma_fp8.hip", "gemm_mfma_fp8_e5m2.hip", "gemm_mfma_int8.hip", "gemm_mfma_f32.hip", "attention_generic.hip", "attention_mfma.hip"]
+# (source, object stem, extra defines).  The 16-bit kernels compile once per element type and group of
+# tile configurations (csrc/gemm_mfma_launch.h: kGroupMask16), in parallel.
+N_GROUPS_16 = 5
+SOURCES = [("pbk_api.hip", "pbk_api", []), ("gemm_generic.hip", "gemm_generic", []), ("gemm_mfma.hip", "gemm_mfma", []),
+           ("gemm_mfma_gather.hip", "gemm_mfma_gather", [])]
+SOURCES += [("gemm_mfma_16bit.hip", f"gemm_mfma_{name}_g{g}",
+             [f"-DPBK_16BIT_TYPE={name}_t", f"-DPBK_16BIT_NAME={name}", f"-DPBK_GROUP={g}"])
+            for g in range(N_GROUPS_16) for name in ("bf16", "f16")]
+SOURCES += [(f, f[:-4], []) for f in ("gemm_mfma_fp8.hip", "gemm_mfma_fp8_e5m2.hip", "gemm_mfma_int8.hip", "gemm_mfma_f32.hip",
+                                      "attention_generic.hip", "attention_mfma.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -24,24 +32,26 @@ def _headers():
     return hs
 
 
-def _extra_flags(src: str):
-    """Development aid: PBK_BUILD_CFGS="1,8" compiles only those MFMA tile
-    configurations (bf16 only); the default builds everything."""
+def _extra_flags(stem: str):
+    """Development aid: PBK_BUILD_CFGS="6,9" compiles only those tile configurations of the 16-bit
+    types, and with PBK_BUILD_TYPES="bf16" only that type; the default builds everything."""
     only = os.environ.get("PBK_BUILD_CFGS")
-    if not only or "gemm_mfma_" not in src:
+    if not only or "_g" not in stem:
         return []
     mask = 0
-    if "bf16" in src:
+    types = os.environ.get("PBK_BUILD_TYPES", "bf16,f16").split(",")
+    if any(f"_{t}_" in stem for t in types):
         for c in only.split(","):
             mask |= 1 << int(c)
-    return [f"-DPBK_CFG_MASK={mask}u"]
+    return [f"-DPBK_DEV_MASK={mask}u"]
 
 
-def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    path = os.path.join(CSRC, src)
+def _compile(src, force: bool) -> str:
+    name, stem, defines = src
+    obj = os.path.join(CSRC, stem + ".o")
+    path = os.path.join(CSRC, name)
     newest = max([os.path.getmtime(path)] + [os.path.getmtime(h) for h in _headers()])
-    cmd = [HIPCC, *FLAGS, *_extra_flags(src), "-c", path, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *defines, *_extra_flags(stem), "-c", path, "-o", obj]
     stamp = obj + ".cmd"                     # the command line the object was built with
     same_cmd = os.path.exists(stamp) and open(stamp).read() == " ".join(cmd)
     if force or not same_cmd or not os.path.exists(obj) or os.path.getmtime(obj) < newest:

@@ -150,9 +150,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
             int64_t o = (int64_t)b * p.stride_c + (int64_t)gm * p.ldc + gn;
             if constexpr (std::is_same<T, int8_t>::value) {
                 QuantParams c = {p.q_scale[gn], p.bias ? p.bias[gn] : 0.0f, p.q_mul ? p.q_mul[gn] : 1.0f,
-                                 p.q_add ? p.q_add[gn] : 0.0f};
-                float t = quant_value(acc[i][j], c, p.bias != nullptr, p.q_mul != nullptr, p.q_add != nullptr,
-                                      p.q_mid, p.q_relu);
+                                 p.q_add ? p.q_add[gn] : 0.0f, p.q_mean ? p.q_mean[gn] : 0.0f,
+                                 p.q_mean ? bn_rinv(p.q_var[gn], p.q_eps) : 1.0f};
+                float t = quant_value(acc[i][j], c, p.bias != nullptr, p.q_mean != nullptr, p.q_mul != nullptr,
+                                      p.q_add != nullptr, p.q_mid, p.q_relu);
                 if (p.out_dtype == DT_INT8) ((int8_t*)p.C)[o] = quant_code(t, p.q_out);
                 else ((float*)p.C)[o] = t;
                 continue;

@@ -69,6 +69,25 @@ static int choose_config(const Problem& p) {
     return 1;
 }
 
+// 16-bit types: the translation unit (group) that holds a configuration
+typedef hipError_t GroupFn(const Problem&, hipStream_t, int, int);
+static hipError_t launch_group16(int cfg, GroupFn* const (&groups)[kNumGroups16], const Problem& p, hipStream_t stream, int group_m) {
+    if (cfg < 0 || cfg > 31) return hipErrorInvalidValue;
+    for (int g = 0; g < kNumGroups16; ++g)
+        if ((kGroupMask16[g] >> cfg) & 1u) return groups[g](p, stream, cfg, group_m);
+    return hipErrorInvalidValue;
+}
+hipError_t launch_mfma_bf16(const Problem& p, hipStream_t stream, int cfg, int group_m) {
+    static GroupFn* const g[kNumGroups16] = {launch_mfma_bf16_g0, launch_mfma_bf16_g1, launch_mfma_bf16_g2,
+                                             launch_mfma_bf16_g3, launch_mfma_bf16_g4};
+    return launch_group16(cfg, g, p, stream, group_m);
+}
+hipError_t launch_mfma_f16(const Problem& p, hipStream_t stream, int cfg, int group_m) {
+    static GroupFn* const g[kNumGroups16] = {launch_mfma_f16_g0, launch_mfma_f16_g1, launch_mfma_f16_g2,
+                                             launch_mfma_f16_g3, launch_mfma_f16_g4};
+    return launch_group16(cfg, g, p, stream, group_m);
+}
+
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name) {
     const bool fp8 = p.in_dtype == DT_FP8_E4M3 || p.in_dtype == DT_FP8_E5M2;
     if (p.in_dtype == DT_F32) {

@@ -274,10 +274,10 @@ struct EpiCtx {
     }
     __device__ __forceinline__ float val(int i, int j, int g, int e) const { return acc[i][j][S16 ? e : g * 4 + e]; }
 
-    template <int ACT> __device__ __forceinline__ float act_of(float acc_v, float bias_v, float res_v = 0.0f) const {
+    template <int ACT, bool HAS_RES = true> __device__ __forceinline__ float act_of(float acc_v, float bias_v, float res_v = 0.0f) const {
         float t = fmaf(p.alpha, acc_v, bias_v);
-        t = fmaf(p.beta, res_v, t);            // beta is 0 when there is no residual operand
-        if (ACT == 1) t = fmaxf(t, 0.0f);
+        if (HAS_RES) t = fmaf(p.beta, res_v, t);
+        if (ACT == 1) t = relu_keep_nan(t);
         if (ACT == 2) t = gelu_tanh_f32(t);
         return t;
     }
@@ -327,11 +327,15 @@ struct EpiCtx {
         const bool fast = (p.N % EPC == 0) && (p.ldc % EPC == 0) &&
                           (((uintptr_t)p.C + (uintptr_t)c_batch * ESZ) % 16 == 0);
         const bool bias_vec = ((uintptr_t)p.bias % 16) == 0;
-        if (fast) run_staged<ACT, OUT_F32>(bias_vec); else run_direct<OUT_F32>(bias_vec, ACT);
+        // the residual operand is a compile-time property of the staged path: its loads and bounds tests
+        // would otherwise sit, as branches, in front of every 4-wide piece of every epilogue
+        if (!fast) run_direct<OUT_F32>(bias_vec, ACT);
+        else if (p.R) run_staged<ACT, OUT_F32, true>(bias_vec);
+        else run_staged<ACT, OUT_F32, false>(bias_vec);
     }
 
     // ---- fast path: registers -> (epilogue) -> LDS slice -> 16-byte row stores
-    template <int ACT, bool OUT_F32> __device__ __forceinline__ void run_staged(bool bias_vec) {
+    template <int ACT, bool OUT_F32, bool HAS_RES> __device__ __forceinline__ void run_staged(bool bias_vec) {
         constexpr int ESZ = OUT_F32 ? 4 : 2;
         constexpr int EPC = 16 / ESZ;                       // elements per 16-byte chunk
         constexpr int ROW_BYTES = WTN * ESZ;
@@ -344,7 +348,7 @@ struct EpiCtx {
         constexpr int ROWS_PER_LD = 64 / CPR;               // rows covered by one wave-wide 16-byte read
         static_assert((RB % ROWS_PER_LD) == 0, "reads must tile a row block");
         const int ld_row = lane / CPR, ld_chunk = lane % CPR;
-        const bool res_vec = p.R && (p.ldr % 4 == 0) &&
+        const bool res_vec = HAS_RES && (p.ldr % 4 == 0) &&
                              (((uintptr_t)p.R + (uintptr_t)c_batch * ESZ) % (4 * ESZ) == 0);
 
         // every bias value this lane needs, loaded once and together
@@ -369,10 +373,10 @@ struct EpiCtx {
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
                         const int lcol = lcol_of(j, g);
-                        float v[4], rv[4];
-                        res4<OUT_F32>(row0 + lrow_of(i), col0 + lcol, res_vec, rv);
+                        float v[4], rv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (HAS_RES) res4<OUT_F32>(row0 + lrow_of(i), col0 + lcol, res_vec, rv);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT>(val(i, j, g, e), bias_r[j][g][e], rv[e]);
+                        for (int e = 0; e < 4; ++e) v[e] = act_of<ACT, HAS_RES>(val(i, j, g, e), bias_r[j][g][e], rv[e]);
                         const int cbyte = lcol * ESZ;
                         char* dst = wlds + lrow * ROW_BYTES + ((((cbyte >> 4) ^ sw)) << 4) + (cbyte & 15);
                         if (OUT_F32) {
@@ -420,6 +424,7 @@ struct EpiCtx {
     __device__ __forceinline__ void run_quant() {
         const bool out_i8 = p.out_dtype == DT_INT8;
         const bool has_bias = p.bias != nullptr, has_mul = p.q_mul != nullptr, has_add = p.q_add != nullptr;
+        const bool has_bn = p.q_mean != nullptr;
         const int esz = out_i8 ? 1 : 4;
         const bool vec = (p.N % 4 == 0) && (p.ldc % 4 == 0) &&
                          (((uintptr_t)p.C + (uintptr_t)c_batch * esz) % (4 * esz) == 0);
@@ -445,6 +450,8 @@ struct EpiCtx {
                     c[e].bias = (in && has_bias) ? p.bias[gn + e] : 0.0f;
                     c[e].mul = (in && has_mul) ? p.q_mul[gn + e] : 1.0f;
                     c[e].add = (in && has_add) ? p.q_add[gn + e] : 0.0f;
+                    c[e].mean = (in && has_bn) ? p.q_mean[gn + e] : 0.0f;
+                    c[e].rinv = (in && has_bn) ? bn_rinv(p.q_var[gn + e], p.q_eps) : 1.0f;
                 }
 #pragma unroll
                 for (int i = 0; i < FM; ++i) {
@@ -455,7 +462,7 @@ struct EpiCtx {
                     float t[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        t[e] = quant_value(__float_as_int(val(i, j, g, e)), c[e], has_bias, has_mul, has_add,
+                        t[e] = quant_value(__float_as_int(val(i, j, g, e)), c[e], has_bias, has_bn, has_mul, has_add,
                                            p.q_mid, p.q_relu);
                     if (out_i8) {
                         int8_t q[4];
@@ -524,7 +531,7 @@ struct EpiCtx {
                         if (gn + e >= p.N) break;
                         float v = fmaf(p.alpha, val(i, j, g, e), bv[e]);
                         v = fmaf(p.beta, rv[e], v);
-                        if (act == 1) v = fmaxf(v, 0.0f);
+                        if (act == 1) v = relu_keep_nan(v);
                         else if (act == 2) v = gelu_tanh_f32(v);
                         if (OUT_F32) ((float*)p.C)[o + e] = v;
                         else ((uint16_t*)p.C)[o + e] = to_bits16<T>(v);

@@ -104,13 +104,15 @@ hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
     }
 }
 
-// PBK_CFG_MASK (build-time, development only): bit i set = compile configuration i.
-#ifndef PBK_CFG_MASK
-#define PBK_CFG_MASK 0xFFFFFFFFu
+// The 16-bit instantiations are split over several translation units (groups of configurations) so
+// that they compile in parallel: MASK has bit i set where this unit builds configuration i.
+// PBK_DEV_MASK (build-time, development only) removes configurations from every group.
+#ifndef PBK_DEV_MASK
+#define PBK_DEV_MASK 0xFFFFFFFFu
 #endif
-#define PBK_CASE(ID, ...) case ID: if constexpr (((PBK_CFG_MASK) >> ID) & 1u) return launch_modes<T, __VA_ARGS__>(p, stream, group_m); else return hipErrorInvalidValue;
+#define PBK_CASE(ID, ...) case ID: if constexpr (((MASK & (PBK_DEV_MASK)) >> ID) & 1u) return launch_modes<T, __VA_ARGS__>(p, stream, group_m); else return hipErrorInvalidValue;
 
-template <typename T>
+template <typename T, unsigned MASK>
 hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int group_m) {
     switch (cfg) {
     PBK_CASE(0, 128, 256, 32, 1, 4, 3, 2)
@@ -123,6 +125,19 @@ hipError_t launch_config(const Problem& p, hipStream_t stream, int cfg, int grou
     default: return hipErrorInvalidValue;
     }
 }
+
+// configuration groups of the 16-bit translation units (gemm_mfma_16bit.hip, once per type and group)
+constexpr unsigned kGroupMask16[] = {
+    (1u << 0) | (1u << 1),            // 0: the 32x32-block configurations
+    (1u << 5),                        // 1: 256x256x32, plain ring
+    (1u << 6),                        // 2: 128x256x32, two workgroups per compute unit
+    (1u << 7),                        // 3: A staged 64 deep
+    (1u << 9),                        // 4: ... with six B stages and one barrier per pair of k-tiles
+};
+constexpr int kNumGroups16 = sizeof(kGroupMask16) / sizeof(kGroupMask16[0]);
+#define PBK_DECLARE_GROUP16(NAME, G) hipError_t launch_mfma_##NAME##_g##G(const Problem& p, hipStream_t stream, int cfg, int group_m);
+PBK_DECLARE_GROUP16(bf16, 0) PBK_DECLARE_GROUP16(bf16, 1) PBK_DECLARE_GROUP16(bf16, 2) PBK_DECLARE_GROUP16(bf16, 3) PBK_DECLARE_GROUP16(bf16, 4)
+PBK_DECLARE_GROUP16(f16, 0) PBK_DECLARE_GROUP16(f16, 1) PBK_DECLARE_GROUP16(f16, 2) PBK_DECLARE_GROUP16(f16, 3) PBK_DECLARE_GROUP16(f16, 4)
 
 hipError_t launch_mfma_bf16(const Problem& p, hipStream_t stream, int cfg, int group_m);
 hipError_t launch_mfma_fp8(const Problem& p, hipStream_t stream, int cfg, int group_m);

@@ -27,16 +27,17 @@ bool valid_out_dtype(int dt) { return dt == PBK_F32 || dt == PBK_BF16 || dt == P
 bool aligned(const void* p, int64_t a) { return (reinterpret_cast<uintptr_t>(p) % (uintptr_t)a) == 0; }
 
 // Kernel choice overrides (benchmarking and test aid).  A choice is "generic" (the fallback
-// kernel), "mfma" (the matrix-unit path, automatic tile configuration) or "mfma:<id>" (one tile
-// configuration).  The environment variables PBK_FORCE_KERNEL and PBK_GROUP_M are read ONCE,
+// kernel), "mfma" (the matrix-unit path, automatic tile configuration), "mfma:<id>" (one tile
+// configuration) or "gather" (the matrix-unit kernel that stages through registers).  The environment variables PBK_FORCE_KERNEL and PBK_GROUP_M are read ONCE,
 // at the first call of the process; pbk_force_kernel() overrides the former per thread.
-struct Choice { int force; int cfg; };        // force: 0 automatic, 1 generic, 2 mfma; cfg: -1 or id
+struct Choice { int force; int cfg; };        // force: 0 automatic, 1 generic, 2 mfma, 3 the gathering mfma kernel; cfg: -1 or id
 
 bool parse_choice(const char* e, Choice* c) {
     c->force = 0; c->cfg = -1;
     if (!e || !*e) return true;
     if (!std::strcmp(e, "generic")) { c->force = 1; return true; }
     if (!std::strcmp(e, "mfma")) { c->force = 2; return true; }
+    if (!std::strcmp(e, "gather")) { c->force = 3; return true; }
     if (!std::strncmp(e, "mfma:", 5) && e[5] >= '0' && e[5] <= '9') { c->force = 2; c->cfg = std::atoi(e + 5); return true; }
     return false;
 }
@@ -78,10 +79,16 @@ pbk_status dispatch(const pbk::Problem& p_in, hipStream_t stream) {
     int force = forced_choice(&cfg);
     const char* name = "";
     hipError_t e;
-    bool can_mfma = pbk::mfma_supported(p);
-    if (force == 2 && !can_mfma) return PBK_ERR_UNSUPPORTED;
-    if (can_mfma && force != 1 && (force == 2 || pbk::mfma_preferred(p)))
+    const bool can_mfma = pbk::mfma_supported(p);
+    // operands the direct-to-LDS kernel cannot take (ragged K, N, leading dimensions, channel counts,
+    // unaligned bases) still run on the matrix units, staged through registers, when there is enough work
+    const bool can_gather = pbk::mfma_gather_supported(p);
+    const bool want_gather = !can_mfma && can_gather && (long long)p.M * p.N >= 4096 && p.K >= 16;
+    if ((force == 2 && !can_mfma && !can_gather) || (force == 3 && !can_gather)) return PBK_ERR_UNSUPPORTED;
+    if (can_mfma && force != 1 && force != 3 && (force == 2 || pbk::mfma_preferred(p)))
         e = pbk::launch_mfma(p, stream, cfg, &name);
+    else if (force == 3 || (force == 2 && !can_mfma) || (force == 0 && want_gather))
+        e = pbk::launch_mfma_gather(p, stream, &name);
     else
         e = pbk::launch_generic(p, stream, &name);
     if (e != hipSuccess) {
@@ -103,8 +110,14 @@ pbk_status check_quant(const float* scale, const float* bias, float mid_scale, c
     return PBK_OK;
 }
 
+// Unfolded batch norm of the call being assembled on this thread (set by the *_int8_bn entry points)
+thread_local const float* g_bn_mean = nullptr;
+thread_local const float* g_bn_var = nullptr;
+thread_local float g_bn_eps = 0.0f;
+
 void set_quant(pbk::Problem& p, const float* scale, const float* bias, float mid_scale, const float* mul,
                const float* add, int relu, float out_scale) {
+    p.q_mean = g_bn_mean; p.q_var = g_bn_var; p.q_eps = g_bn_eps;
     p.in_dtype = pbk::DT_INT8;
     p.bias = bias;
     p.q_scale = scale; p.q_mul = mul; p.q_add = add;
@@ -343,6 +356,36 @@ pbk_status pbk_conv2d_nhwc_int8(const int8_t* x, const int8_t* w, void* y,
     return conv_common(x, w, y, bias, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
                        OH, OW, 0, PBK_INT8, out_dtype, 1.0f, PBK_EPI_NONE, stream, scale, mul, add, mid_scale,
                        out_scale, relu, true);
+}
+
+pbk_status pbk_matmul_int8_bn(const int8_t* A, const int8_t* B, void* C,
+                              int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, int trans_b,
+                              const float* scale, const float* bias, float mid_scale,
+                              const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                              int relu, float out_scale, pbk_dtype out_dtype, hipStream_t stream) {
+    if (!mean || !var || !gamma || !beta) return PBK_ERR_EPILOGUE;
+    if (!aligned(mean, 4) || !aligned(var, 4)) return PBK_ERR_ALIGN;
+    g_bn_mean = mean; g_bn_var = var; g_bn_eps = eps;
+    pbk_status s = pbk_matmul_int8(A, B, C, M, N, K, lda, ldb, ldc, trans_b, scale, bias, mid_scale, gamma, beta, relu,
+                                   out_scale, out_dtype, stream);
+    g_bn_mean = nullptr; g_bn_var = nullptr;
+    return s;
+}
+
+pbk_status pbk_conv2d_nhwc_int8_bn(const int8_t* x, const int8_t* w, void* y,
+                                   int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                   int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                   int64_t pad_h, int64_t pad_w, int64_t dil_h, int64_t dil_w,
+                                   const float* scale, const float* bias, float mid_scale,
+                                   const float* mean, const float* var, float eps, const float* gamma, const float* beta,
+                                   int relu, float out_scale, pbk_dtype out_dtype, hipStream_t stream) {
+    if (!mean || !var || !gamma || !beta) return PBK_ERR_EPILOGUE;
+    if (!aligned(mean, 4) || !aligned(var, 4)) return PBK_ERR_ALIGN;
+    g_bn_mean = mean; g_bn_var = var; g_bn_eps = eps;
+    pbk_status s = pbk_conv2d_nhwc_int8(x, w, y, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                                        scale, bias, mid_scale, gamma, beta, relu, out_scale, out_dtype, stream);
+    g_bn_mean = nullptr; g_bn_var = nullptr;
+    return s;
 }
 
 pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,

@@ -24,6 +24,10 @@ __device__ __forceinline__ float gelu_tanh_f32(float t) {
     return 0.5f * t * (1.0f + th);
 }
 
+// ReLU that keeps NaN: "greater than zero, or unordered" selects t (the compare of the paper's fused nest;
+// the hardware maximum would turn NaN into 0)
+__device__ __forceinline__ float relu_keep_nan(float t) { return !(t <= 0.0f) ? t : 0.0f; }
+
 // t = alpha*acc + bias + beta*res ; act(t).  `bias` must be 0 when the epilogue has none.
 __device__ __forceinline__ float apply_epilogue(float acc, float alpha, float bias, int epi,
                                                 float beta = 0.0f, float res = 0.0f) {
@@ -32,7 +36,7 @@ __device__ __forceinline__ float apply_epilogue(float acc, float alpha, float bi
     switch (epi) {
     case EPI_RELU:
     case EPI_BIAS_RELU:
-        return fmaxf(t, 0.0f);
+        return relu_keep_nan(t);
     case EPI_BIAS_GELU_TANH:
     case EPI_GELU_TANH:
         return gelu_tanh_f32(t);
@@ -66,7 +70,8 @@ template <> __device__ __forceinline__ float widen<fp8_e4m3_t>(fp8_e4m3_t x) {
 }
 
 // ---- quantised epilogue of the int8 path (paper appendix on quantisation: de-quantise, bias,
-// optional quantise/de-quantise pair, folded batch-norm affine, ReLU, output quantisation).
+// optional quantise/de-quantise pair, batch norm (unfolded as in the paper's figure, or folded by the
+// caller into a multiplier and a shift), ReLU, output quantisation).
 // Every step is a single binary32 operation in this order; contraction into fused
 // multiply-adds is switched off so that the integer codes come out bit-exact.
 __device__ __forceinline__ float quantise_step(float t, float step) {
@@ -77,11 +82,22 @@ __device__ __forceinline__ float quantise_step(float t, float step) {
     return q;
 }
 
-struct QuantParams {       // per-column values of one output element, plus the uniform ones
+struct QuantParams {       // per-column values of one output element
     float scale, bias, mul, add;
+    float mean, rinv;      // unfolded batch norm: subtract mean, multiply by rinv = 1 / sqrt(var + eps)
 };
 
-__device__ __forceinline__ float quant_value(int acc, const QuantParams& c, bool has_bias, bool has_mul,
+// 1 / sqrt(var + eps) as the paper's nest computes it: an addition, a correctly rounded square root and a
+// correctly rounded division, one binary32 operation each
+__device__ __forceinline__ float bn_rinv(float var, float eps) {
+#pragma clang fp contract(off)
+    float r = var + eps;
+    r = __builtin_sqrtf(r);
+    r = 1.0f / r;
+    return r;
+}
+
+__device__ __forceinline__ float quant_value(int acc, const QuantParams& c, bool has_bias, bool has_bn, bool has_mul,
                                              bool has_add, float mid, int relu) {
 #pragma clang fp contract(off)
     float t = (float)acc;                             // v_cvt_f32_i32: round to nearest even
@@ -91,9 +107,13 @@ __device__ __forceinline__ float quant_value(int acc, const QuantParams& c, bool
         float q = quantise_step(t, mid);
         t = q * mid;
     }
+    if (has_bn) {                                     // then mul = gamma, add = beta
+        t = t - c.mean;
+        t = t * c.rinv;
+    }
     if (has_mul) t = t * c.mul;
     if (has_add) t = t + c.add;
-    if (relu) t = t > 0.0f ? t : 0.0f;
+    if (relu) t = !(t <= 0.0f) ? t : 0.0f;            // greater than zero or unordered: NaN stays NaN
     return t;
 }
 

@@ -42,6 +42,7 @@ struct Problem {
     float beta;
     // int8 operands (in_dtype DT_INT8): integer accumulation and the quantised epilogue
     //   t = float(acc)*q_scale[n] (+ bias[n]); optional requantise/dequantise with q_mid;
+    //   unfolded batch norm if q_mean: t = (t - q_mean[n]) * (1 / sqrt(q_var[n] + q_eps)), q_mul = gamma, q_add = beta;
     //   t = t*q_mul[n] + q_add[n] (each if given); ReLU if q_relu;
     //   out = int8(clamp(roundeven(t/q_out))) for out_dtype DT_INT8, else t as fp32.
     const float* q_scale;
@@ -49,6 +50,9 @@ struct Problem {
     const float* q_add;
     float q_mid, q_out;
     int q_relu;
+    const float* q_mean;
+    const float* q_var;
+    float q_eps;
 };
 
 // One attention layer call (paper Sec. 4.4): O = softmax(alpha Q K^T + bias) V
@@ -80,6 +84,11 @@ bool mfma_supported(const Problem& p);
 // Returns false where the generic kernel is the better choice although the MFMA path could run.
 bool mfma_preferred(const Problem& p);
 hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, const char** name);
+
+// The matrix-unit kernel that gathers its tiles element by element: 16-bit operands of any alignment, K, N
+// and leading dimensions; convolutions with at least 8 input channels.
+bool mfma_gather_supported(const Problem& p);
+hipError_t launch_mfma_gather(const Problem& p, hipStream_t stream, const char** name);
 
 // PBK_GROUP_M of the environment as read at the process's first call (0 = not set): tile rows
 // per group of the block mapping, a benchmarking override.

@@ -184,3 +184,18 @@ def test_force_kernel_choices(pbk):
     assert pbk.pbk_force_kernel("mfma") == 0 and pbk.pbk_force_kernel("mfma:7") == 0
     assert pbk.pbk_force_kernel("mfma:") == 7 and pbk.pbk_force_kernel("fastest") == 7
     assert pbk.pbk_force_kernel("") == 0 and pbk.pbk_force_kernel(None) == 0
+
+
+def test_int8_unfolded_batch_norm_argument_errors(pbk):
+    P = 0x1000
+    mm = pbk.pbk_matmul_int8_bn
+
+    def call(mean=P, var=P, gamma=P, beta=P, scale=P, out=5, M=4):
+        return mm(P, P, P, M, 4, 16, 16, 16, 4, 1, scale, None, 0.0, mean, var, 1e-5, gamma, beta, 1, 1.0, out)
+    assert call(mean=None) == 6 and call(var=None) == 6 and call(gamma=None) == 6 and call(beta=None) == 6
+    assert call(mean=P + 2) == 4 and call(scale=None) == 6 and call(out=1) == 5
+    assert call(M=0) == 0
+    cv = pbk.pbk_conv2d_nhwc_int8_bn
+    geom = (1, 8, 8, 16, 16, 3, 3, 1, 1, 1, 1, 1, 1)
+    assert cv(P, P, P, *geom, P, None, 0.0, None, P, 1e-5, P, P, 0, 1.0, 5) == 6
+    assert cv(P, P, P, 0, *geom[1:], P, None, 0.0, P, P, 1e-5, P, P, 0, 1.0, 5) == 0

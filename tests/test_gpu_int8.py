@@ -190,3 +190,85 @@ def test_matmul_int8_full_size_sampled_rows():
     print(f"int8 8192^3 kernel={kern} codes={len(np.unique(want))}", flush=True)
     assert "256x256x64" in kern
     assert np.array_equal(got[rows], want) and len(np.unique(want)) > 50
+
+
+# ------------------------------------------- the batch-norm step unfolded, as in the paper's figure
+
+def bn_params(n, seed=0, relu=True, mid=0.031):
+    r = np.random.default_rng(2000 + seed)
+    return dict(scale=(r.uniform(0.5, 2.0, n) * 2e-4).astype(np.float32), bias=r.normal(0, 0.5, n).astype(np.float32),
+                mid_scale=mid, mean=r.normal(0, 0.5, n).astype(np.float32), var=r.uniform(0.3, 3.0, n).astype(np.float32),
+                eps=1e-5, gamma=r.uniform(0.5, 1.5, n).astype(np.float32), beta=r.normal(0, 0.3, n).astype(np.float32),
+                relu=relu, out_scale=0.043)
+
+
+@pytest.mark.parametrize("force", [None, "mfma:1", "mfma:4", "mfma:8", "generic"])
+@pytest.mark.parametrize("out_int8", [True, False])
+@pytest.mark.parametrize("mnk", [(300, 264, 208), (130, 272, 4096)])
+def test_matmul_int8_unfolded_batch_norm_is_bit_exact(force, out_int8, mnk):
+    import torch
+    import oracle
+    import paper_2603_06731_amd as pbk
+    m, n, k = mnk
+    A = wl.int8_tensor((m, k), 1, "normal", 40.0); B = wl.int8_tensor((n, k), 2, "normal", 30.0)
+    q = bn_params(n, seed=m)
+    d = {k2: dev_or_none(v) if isinstance(v, np.ndarray) else v for k2, v in q.items()}
+    out = torch.empty(m * n, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+    with T.forced_kernel(force):
+        st = pbk.pbk_matmul_int8_bn(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), out, m, n, k, k, k, n, 1,
+                                    d["scale"], d["bias"], q["mid_scale"], d["mean"], d["var"], q["eps"], d["gamma"], d["beta"],
+                                    q["relu"], q["out_scale"], INT8 if out_int8 else F32, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    want = oracle.matmul_int8_bn(A, B, trans_b=1, out_int8=out_int8, **q)
+    got = out.cpu().numpy().reshape(m, n)
+    view = np.uint8 if out_int8 else np.uint32
+    assert np.array_equal(got.view(view), want.view(view)), pbk.pbk_last_kernel()
+    if out_int8:
+        assert len(np.unique(want)) > 40
+    # and it is not the folded form: the caller-folded parameters give other bits somewhere
+    if not out_int8:
+        rr = (np.float32(1) / np.sqrt(q["var"] + np.float32(q["eps"]))).astype(np.float32)
+        mul = (rr * q["gamma"]).astype(np.float32); add = (q["beta"] - q["mean"] * mul).astype(np.float32)
+        folded = oracle.matmul_int8(A, B, trans_b=1, out_int8=False, scale=q["scale"], bias=q["bias"],
+                                    mid_scale=q["mid_scale"], mul=mul, add=add, relu=q["relu"])
+        assert np.any(folded != want)
+
+
+@pytest.mark.parametrize("force", [None, "generic"])
+def test_conv_int8_unfolded_batch_norm_is_bit_exact(force):
+    import torch
+    import oracle
+    import paper_2603_06731_amd as pbk
+    n, H, W, Cin, Cout = 2, 14, 13, 32, 48
+    x = wl.int8_tensor((n, H, W, Cin), 1, "normal", 40.0); w = wl.int8_tensor((3, 3, Cin, Cout), 2, "normal", 30.0)
+    q = bn_params(Cout, seed=5)
+    d = {k2: dev_or_none(v) if isinstance(v, np.ndarray) else v for k2, v in q.items()}
+    out = torch.empty(n * H * W * Cout, dtype=torch.int8, device="cuda")
+    with T.forced_kernel(force):
+        st = pbk.pbk_conv2d_nhwc_int8_bn(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), out, n, H, W, Cin, Cout,
+                                         3, 3, 1, 1, 1, 1, 1, 1, d["scale"], d["bias"], q["mid_scale"], d["mean"], d["var"],
+                                         q["eps"], d["gamma"], d["beta"], q["relu"], q["out_scale"], INT8, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    want = oracle.conv2d_nhwc_int8_bn(x, w, pad=(1, 1), **q)
+    assert np.array_equal(out.cpu().numpy().reshape(want.shape), want), pbk.pbk_last_kernel()
+
+
+@pytest.mark.parametrize("force", [None, "generic"])
+def test_int8_relu_keeps_nan(force):
+    """A NaN de-quantisation scale makes a column NaN; the ReLU (greater or unordered) keeps it."""
+    import torch
+    import oracle
+    import paper_2603_06731_amd as pbk
+    m, n, k = 64, 32, 64
+    A = wl.int8_tensor((m, k), 1); B = wl.int8_tensor((n, k), 2)
+    scale = np.full(n, 1e-3, np.float32); scale[5] = np.nan
+    out = torch.empty(m * n, dtype=torch.float32, device="cuda")
+    with T.forced_kernel(force):
+        st = pbk.pbk_matmul_int8(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), out, m, n, k, k, k, n, 1,
+                                 T.to_device(scale), None, 0.0, None, None, 1, 1.0, F32, None)
+    assert st == 0
+    got = out.cpu().numpy().reshape(m, n)
+    want = oracle.matmul_int8(A, B, trans_b=1, scale=scale, relu=True, out_int8=False)
+    assert np.isnan(got[:, 5]).all() and np.isnan(want[:, 5]).all()
+    keep = np.ones(n, bool); keep[5] = False
+    assert np.array_equal(got[:, keep], want[:, keep])

@@ -108,7 +108,10 @@ def test_matmul_generic_odd_shapes(dtype, mnk, trans_b):
     m, n, k = mnk
     w = wl.Workload("mm_odd", "matmul", dtype, dtype, C.EPI_BIAS_GELU_TANH, alpha=0.5, M=m, N=n, K=k,
                     trans_b=trans_b, dist_b=("normal", 1.0 / np.sqrt(k)))
-    check_full(w, expect_kernel="generic")
+    # 16-bit operands with enough work (M N >= 4096, K >= 16) take the gathering matrix-unit kernel
+    gather = dtype != F32 and m * n >= 4096 and k >= 16
+    check_full(w, expect_kernel="gather" if gather else "generic")
+    check_full(w, force="generic", expect_kernel="generic")
 
 
 def test_cfg1_fp32_256():
@@ -173,7 +176,8 @@ def test_conv_paper_example_shape_reduced():
     # stride-2 3x3 over 127 channels (paper's first worked example, fewer images/outputs)
     w = wl.Workload("conv_p1", "conv", F16, F32, C.EPI_NONE, n=2, H=44, W=44, Cin=127, Cout=24,
                     KH=3, KW=3, stride=(2, 2), dist_b=("normal", 0.03))
-    check_full(w, expect_kernel="generic")
+    check_full(w, expect_kernel="mfma")           # 127 channels: the gathering matrix-unit kernel
+    check_full(w, force="generic", expect_kernel="generic")
 
 
 # ---------------------------------------------------- full-size, sampled outputs
@@ -430,3 +434,23 @@ def test_fp32_large_matmul_takes_mfma_and_is_sampled():
     err = T.rel_err(T.gather_output(out, w, b, i, j), ref, pre)
     print(f"f32 2048x2048x1024 kernel={pbk.pbk_last_kernel()} err={err:.3e}", flush=True)
     assert err <= T.TOL_F32, err
+
+
+@pytest.mark.parametrize("force", [None, "mfma:1", "mfma:6", "generic"])
+def test_relu_keeps_nan(force):
+    """ReLU(NaN) is NaN on both sides (the oracle's definition; the paper's nest compares 'unordered or
+    greater'): a NaN in one row of A makes that output row NaN, every other row stays as the oracle has it."""
+    import paper_2603_06731_amd as pbk
+    w = wl.Workload("relu_nan", "matmul", BF16, BF16, C.EPI_BIAS_RELU, M=264, N=264, K=136, dist_b=("normal", 0.1))
+    host = wl.make_inputs(w)
+    host["a"][7, 3] = 0x7FC0                     # a bf16 NaN
+    with T.forced_kernel(force):
+        st, out = T.run_workload(w, T.upload(host))
+    assert st == 0
+    got = T.to_host_f64(out, BF16).reshape(w.M, w.N)
+    ref, pre = T.oracle_full(w, host)
+    ref, pre = ref.reshape(w.M, w.N), pre.reshape(w.M, w.N)
+    assert np.isnan(ref[7]).all() and np.isnan(got[7]).all(), pbk.pbk_last_kernel()
+    rows = np.arange(w.M) != 7
+    assert np.isfinite(got[rows]).all()
+    assert T.rel_err(got[rows], ref[rows], pre[rows]) <= T.TIGHT[BF16]
