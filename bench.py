@@ -30,6 +30,7 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 DTYPE_NAMES = {0: "f32", 1: "bf16", 2: "f16", 3: "fp8_e4m3", 4: "fp8_e5m2", 5: "int8"}
 PEAK_MFMA_FP8_TFLOPS = 5033.2       # twice the 16-bit rate
+ROTATE_OVER_BYTES = 512 << 20       # twice the 256 MB memory-side cache
 
 
 def is_attention(w):
@@ -87,24 +88,57 @@ def time_workload(w, steps, warmup):
         run = T.run_workload
     if not is_int8(w):
         dev = T.upload(host)
+    # Working sets that fit the 256 MB memory-side cache are rotated over several copies of the inputs and
+    # the output (enough to exceed twice that cache, at most 8), so that a launch does not find the operands
+    # of the previous one still cached; larger ones need no rotation.
+    set_bytes = sum(t.numel() * t.element_size() for t in dev.values() if hasattr(t, "numel")) + out.numel() * out.element_size()
+    nsets = max(1, min(8, -(-ROTATE_OVER_BYTES // max(set_bytes, 1)))) if set_bytes < ROTATE_OVER_BYTES // 2 else 1
+    sets = [(dev, out)] + [({k: (v.clone() if hasattr(v, "clone") else v) for k, v in dev.items()}, out.clone())
+                           for _ in range(nsets - 1)]
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        st, _o = run(w, dev, out=out, stream=stream)
+    for i in range(warmup):
+        d, o = sets[i % nsets]
+        st, _o = run(w, d, out=o, stream=stream)
         pbk.check(st, w.name)
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
+        d, o = sets[i % nsets]
         starts[i].record(stream)
-        st, _o = run(w, dev, out=out, stream=stream)
+        st, _o = run(w, d, out=o, stream=stream)
         ends[i].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     pbk.check(st, w.name)
     ev_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
     return {"wall_ms_per_step": (t1 - t0) * 1e3 / steps, "event_ms": ev_ms,
-            "kernel": pbk.pbk_last_kernel(), "host": host, "out": out}
+            "kernel": pbk.pbk_last_kernel(), "host": host, "out": out, "buffer_sets": nsets,
+            "set_bytes": set_bytes}
+
+
+def measure_copy_bandwidth(nbytes=1 << 30, reps=10):
+    """Achievable HBM bandwidth in this run: a device copy of `nbytes` (read + write counted), and a fill
+    (write only), timed with events."""
+    import torch
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    res = {}
+    for name, fn, moved in (("copy", lambda: dst.copy_(src), 2 * nbytes), ("fill", lambda: dst.fill_(2), nbytes)):
+        for _ in range(2):
+            fn()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    return res
 
 
 def cpu_baseline_attention(w, host, budget_s=15.0):
@@ -194,7 +228,58 @@ def load_traffic(name):
     return None
 
 
-def report(w, r, steps, warmup, with_cpu=True):
+def _pmc_child(counter, extra, outdir, tag, timeout_s):
+    """One rocprofv3 --pmc run of this script as a child process; returns {kernel name: mean counter value}."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    exe = shutil.which("rocprofv3")
+    if not exe:
+        return None
+    env = dict(os.environ, TMPDIR="/tmp")
+    cmd = [exe, "--pmc", counter, "-d", outdir, "-o", tag, "--output-format", "csv", "--",
+           sys.executable, os.path.abspath(__file__), *extra]
+    try:
+        subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL,
+                       timeout=timeout_s, check=True)
+    except Exception:
+        return None
+    vals = {}
+    for f in glob.glob(os.path.join(outdir, "**", tag + "_counter_collection.csv"), recursive=True):
+        with open(f) as fh:
+            for r in csv.DictReader(fh):
+                if r["Counter_Name"] == counter:
+                    vals.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+    return {k: sum(v) / len(v) for k, v in vals.items()} or None
+
+
+def measure_traffic(workload, timeout_s=150):
+    """HBM-side bytes per launch of the workload's kernel, measured now: FETCH_SIZE and WRITE_SIZE (KiB per
+    dispatch) from one rocprofv3 --pmc child run each, scaled by what the same counters read for a 1 GiB
+    device copy.  Must run before this process initialises the GPU.  None if the profiler is not usable."""
+    import tempfile
+    out = tempfile.mkdtemp(prefix="pbk_traffic_")
+    res = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        k = _pmc_child(counter, ["--workload", workload, "--steps", "3", "--warmup", "1", "--no-cpu-baseline",
+                                 "--no-traffic", "--no-copy"], out, "w_" + counter, timeout_s)
+        c = _pmc_child(counter, ["--calibrate-copy", "--steps", "2"], out, "c_" + counter, timeout_s)
+        if not k or not c:
+            return None
+        ker = [v for n, v in k.items() if "pbk" in n]
+        cop = [v for n, v in c.items() if "copy" in n.lower()]
+        if not ker or not cop or cop[0] <= 0:
+            return None
+        scale = (1 << 20) / cop[0]                    # the copy moves 2^20 KiB each way
+        res[counter] = max(ker) * 1024.0 * scale
+        res[counter + "_scale"] = scale
+    return {"bytes": res["FETCH_SIZE"] + res["WRITE_SIZE"], "fetch_bytes": res["FETCH_SIZE"],
+            "write_bytes": res["WRITE_SIZE"], "fetch_scale": res["FETCH_SIZE_scale"],
+            "write_scale": res["WRITE_SIZE_scale"]}
+
+
+def report(w, r, steps, warmup, with_cpu=True, traffic=None, copy_bw=None):
     bound, peak = bound_of(w)
     avg_ms = sum(r["event_ms"]) / len(r["event_ms"])
     if bound == "mfma":
@@ -220,12 +305,24 @@ def report(w, r, steps, warmup, with_cpu=True):
                    {"workload": w.name, "kind": w.kind, "gemm_mnk": list(w.gemm_mnk), "batch": w.batch,
                     "epilogue": w.epi, "out_dtype": DTYPE_NAMES[w.out_dtype], "kernel": r["kernel"]}),
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                     "frac": achieved / peak, "traffic": load_traffic(w.name),
+                     "frac": achieved / peak,
+                     "traffic": traffic["bytes"] if traffic else load_traffic(w.name),
+                     "traffic_source": ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE child runs of this command, scaled by a "
+                                        "1 GiB device copy" if traffic else "profiles/hbm_traffic.json (committed summary)"),
                      "kernel_ms_avg": avg_ms, "kernel_ms_min": min(r["event_ms"]),
-                     "algorithmic_bytes": w.algorithmic_bytes, "flops": w.flops},
+                     "algorithmic_bytes": w.algorithmic_bytes, "flops": w.flops,
+                     "buffer_sets": r.get("buffer_sets", 1)},
     }
+    if traffic:
+        line["roofline"]["traffic_detail"] = {k: traffic[k] for k in ("fetch_bytes", "write_bytes", "fetch_scale", "write_scale")}
     if bound == "hbm":
         line["roofline"]["mfma_frac"] = w.flops / (avg_ms * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS
+    if copy_bw:
+        # what a plain device copy / fill reaches in this run, beside the 8 TB/s of the data sheet
+        line["roofline"]["copy_GBps"] = copy_bw["copy"]
+        line["roofline"]["fill_GBps"] = copy_bw["fill"]
+        if bound == "hbm":
+            line["roofline"]["frac_of_copy"] = achieved / copy_bw["copy"]
     if with_cpu:
         line["cpu_baseline"] = cpu_baseline(w, r["host"])
     return line
@@ -240,6 +337,10 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads (table on stderr)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--json-out", default=None, help="with --all: also write every workload's line to this file")
+    ap.add_argument("--table-out", default=None, help="with --all: also write the per-workload table to this text file")
+    ap.add_argument("--extra", action="store_true", help="with --all: include the FP8, int8 and attention workloads")
+    ap.add_argument("--no-traffic", action="store_true", help="do not measure HBM traffic with rocprofv3 child runs")
+    ap.add_argument("--no-copy", action="store_true", help="do not time the device copy / fill")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -247,6 +348,11 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the contraction shards by output tiles without "
                  "any exchange; nothing multi-GPU is implemented). Use --gpus 1.")
+
+    # HBM traffic counters: child runs under the profiler, before this process touches the GPU
+    traffic = None
+    if not (args.no_traffic or args.calibrate_copy or args.all):
+        traffic = measure_traffic(args.workload)
 
     import torch
     import workloads as wl
@@ -267,23 +373,38 @@ def main():
         return
 
     w = {**wl.CONFIGS, **wl.EXTRA_CONFIGS, **wl.ATTENTION_CONFIGS, **wl.INT8_CONFIGS}[args.workload]
+    copy_bw = None if args.no_copy else measure_copy_bandwidth()
     r = time_workload(w, args.steps, args.warmup)
-    line = report(w, r, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline)
+    line = report(w, r, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline, traffic=traffic, copy_bw=copy_bw)
     del r
 
     if args.all:
         rows = [line]
-        for name, ww in wl.CONFIGS.items():
+        pool = dict(wl.CONFIGS)
+        if args.extra:
+            pool.update({**wl.EXTRA_CONFIGS, **wl.INT8_CONFIGS,
+                         **{k: v for k, v in wl.ATTENTION_CONFIGS.items() if "8192" in k or "2048" in k}})
+        for name, ww in pool.items():
             if name == args.workload:
                 continue
             rr = time_workload(ww, args.steps, args.warmup)
-            rows.append(report(ww, rr, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline))
+            rows.append(report(ww, rr, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline, copy_bw=copy_bw))
             del rr
+        table = []
         for x in rows:
             rf = x["roofline"]
-            print(f"{x['config']['workload']:24s} {x['config']['kernel']:26s} {rf['kernel_ms_avg']*1e3:9.1f} us  "
-                  f"{x['value']:8.1f} TFLOP/s  {rf['bound']}: {rf['achieved']:.1f} {rf['unit']} = {rf['frac']*100:.1f}%",
-                  file=sys.stderr)
+            extra = f"  ({rf['frac_of_copy']*100:.1f}% of this run's device copy)" if "frac_of_copy" in rf else ""
+            table.append(f"{x['config']['workload']:24s} {x['config']['kernel']:36s} {rf['kernel_ms_avg']*1e3:9.1f} us (min "
+                         f"{rf['kernel_ms_min']*1e3:7.1f})  {x['value']:8.1f} TFLOP/s  {rf['bound']}: {rf['achieved']:.1f} "
+                         f"{rf['unit']} = {rf['frac']*100:.1f}% of {rf['peak']:g}  sets={rf['buffer_sets']}{extra}")
+        print("\n".join(table), file=sys.stderr)
+        if args.table_out:
+            with open(args.table_out, "w") as f:
+                f.write("python bench.py " + " ".join(sys.argv[1:]) + "\n")
+                f.write("kernel time: HIP events around every launch, mean (min) over the timed steps; TFLOP/s from wall time\n")
+                if copy_bw:
+                    f.write(f"device copy of 1 GiB in this run: {copy_bw['copy']:.0f} GB/s (read + write), fill {copy_bw['fill']:.0f} GB/s\n")
+                f.write("\n".join(table) + "\n")
         if args.json_out:
             with open(args.json_out, "w") as f:
                 json.dump(rows, f, indent=1)
