@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libpbk.so")
 # tile configurations (csrc/gemm_mfma_launch.h: kGroupMask16), in parallel.
 N_GROUPS_16 = 5
 SOURCES = [("pbk_api.hip", "pbk_api", []), ("gemm_generic.hip", "gemm_generic", []), ("gemm_mfma.hip", "gemm_mfma", []),
-           ("gemm_mfma_gather.hip", "gemm_mfma_gather", [])]
+           ("gemm_mfma_gather.hip", "gemm_mfma_gather", []), ("gemm_small_f32.hip", "gemm_small_f32", [])]
 SOURCES += [("gemm_mfma_16bit.hip", f"gemm_mfma_{name}_g{g}",
              [f"-DPBK_16BIT_TYPE={name}_t", f"-DPBK_16BIT_NAME={name}", f"-DPBK_GROUP={g}"])
             for g in range(N_GROUPS_16) for name in ("bf16", "f16")]

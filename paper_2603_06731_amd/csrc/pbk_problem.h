@@ -78,6 +78,10 @@ __host__ __device__ inline bool epi_has_bias(int epi) {
 // Launchers.  Each returns hipSuccess or the launch error; `name` receives a
 // static string naming the configuration that ran.
 hipError_t launch_generic(const Problem& p, hipStream_t stream, const char** name);
+// small fp32 matmuls, one wave per 16 x 16 tile
+bool small_f32_supported(const Problem& p);
+bool small_f32_preferred(const Problem& p);
+hipError_t launch_small_f32(const Problem& p, hipStream_t stream, const char** name);
 
 // Returns false if this problem cannot take the MFMA path (alignment, dtype).
 bool mfma_supported(const Problem& p);

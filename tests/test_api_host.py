@@ -182,6 +182,7 @@ def test_int8_is_not_an_input_type_of_the_plain_convolution_calls(pbk):
 def test_force_kernel_choices(pbk):
     assert pbk.pbk_force_kernel("generic") == 0
     assert pbk.pbk_force_kernel("mfma") == 0 and pbk.pbk_force_kernel("mfma:7") == 0
+    assert pbk.pbk_force_kernel("gather") == 0 and pbk.pbk_force_kernel("small") == 0
     assert pbk.pbk_force_kernel("mfma:") == 7 and pbk.pbk_force_kernel("fastest") == 7
     assert pbk.pbk_force_kernel("") == 0 and pbk.pbk_force_kernel(None) == 0
 
