@@ -139,6 +139,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
     }
 
     const bool has_bias = epi_has_bias(p.epi);
+    StepDiv mid_div = {}, out_div = {};
+    if constexpr (std::is_same<T, int8_t>::value) { mid_div = make_step_div(p.q_mid); out_div = make_step_div(p.q_out); }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int gm = m0 + ty * 4 + i;
@@ -153,8 +155,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Problem p, int tiles_
                                  p.q_add ? p.q_add[gn] : 0.0f, p.q_mean ? p.q_mean[gn] : 0.0f,
                                  p.q_mean ? bn_rinv(p.q_var[gn], p.q_eps) : 1.0f};
                 float t = quant_value(acc[i][j], c, p.bias != nullptr, p.q_mean != nullptr, p.q_mul != nullptr,
-                                      p.q_add != nullptr, p.q_mid, p.q_relu);
-                if (p.out_dtype == DT_INT8) ((int8_t*)p.C)[o] = quant_code(t, p.q_out);
+                                      p.q_add != nullptr, mid_div, p.q_relu);
+                if (p.out_dtype == DT_INT8) ((int8_t*)p.C)[o] = quant_code(t, out_div);
                 else ((float*)p.C)[o] = t;
                 continue;
             }

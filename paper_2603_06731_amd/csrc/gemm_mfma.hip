@@ -55,7 +55,9 @@ static int choose_config(const Problem& p) {
     if (p.trans_b && !p.is_conv && p.K >= 1024) {
         // k-major B, long contraction: the 128x256 configurations are slow there (1044 us against
         // 874 us for 256x256x32 on 8192^3); short ones (K = 128) follow the general rule below
-        if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 5;
+        // (9: both operands staged 64 deep, one barrier per pair of k-tiles: 715 against 800 us on 8192^3,
+        // 5-7 % ahead of 5 from K = 1024 up and down to 4096^2 outputs)
+        if (p.M >= 256 && p.N >= 256 && t256 >= 128) return 9;
         return 1;
     }
     // Long contractions over many tiles: one 256x256x32 workgroup per CU with a 4-stage ring.
@@ -101,9 +103,9 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
         long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
         // (with both operands k-major the 16x16x64 blocks: 0.54 against 0.59 ms on 8192^3)
         const bool kmajor = p.trans_b && !p.is_conv;
-        int c = (force_cfg == 0 || force_cfg == 1 || force_cfg == 4 || force_cfg == 8) ? force_cfg
-                : (p.M >= 256 && p.N >= 256 && t256 >= 128) ? (kmajor ? 8 : 4) : 1;
-        if (c == 8 && !kmajor) c = 4;       // the 16x16 blocks are built for k-major operands only
+        int c = (force_cfg == 0 || force_cfg == 1 || force_cfg == 4 || force_cfg == 8 || force_cfg == 9) ? force_cfg
+                : (p.M >= 256 && p.N >= 256 && t256 >= 128) ? (kmajor ? 9 : 4) : 1;
+        if ((c == 8 || c == 9) && !kmajor) c = 4;       // the 16x16 blocks are built for k-major operands only
         *name = kMfmaConfigs[c].name;
         const int gm = group_m_override() > 0 ? group_m_override() : 8;
         return launch_mfma_int8(p, stream, c, gm);
@@ -111,7 +113,7 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
     if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1 && cfg != 6) cfg = choose_config(p);   // the ones built
     if (!fp8 && ((cfg >= 2 && cfg <= 4) || cfg == 8)) cfg = choose_config(p);   // 16-bit types: 0, 1, 5, 6, 7, 9 are built
-    if (cfg == 9 && (p.is_conv || p.trans_b)) cfg = 7;       // 9 is built for plain row-major operands
+    if (cfg == 9 && p.is_conv) cfg = 7;       // 9 is built for plain matrices
     if (fp8) {
         // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
         // only the 64-deep configurations are built for it

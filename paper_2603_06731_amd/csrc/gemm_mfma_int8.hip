@@ -15,6 +15,10 @@ hipError_t launch_mfma_int8(const Problem& p, hipStream_t stream, int cfg, int g
         if (q.trans_b && !q.is_conv)
             return launch_one<int8_t, bf16_t, 256, 256, 64, 2, 4, MODE_TRANS_B, 2, 1, 16>(q, stream, group_m);
         return launch_typed_modes<int8_t, bf16_t, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
+    case 9:     // ... both staged 64 deep (128 values), one barrier per pair of k-tiles
+        if (q.trans_b && !q.is_conv)
+            return launch_one<int8_t, bf16_t, 256, 256, 32, 2, 4, MODE_TRANS_B, 5, 1, 16, 2>(q, stream, group_m);
+        return launch_typed_modes<int8_t, bf16_t, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
     default: return hipErrorInvalidValue;
     }
 }

@@ -421,19 +421,26 @@ struct EpiCtx {
 
     // ---- int8 path: the accumulators are 32-bit integers; quantised epilogue, stores straight
     // from registers (4 consecutive columns per lane: one dword of int8 codes, or 16 bytes of fp32)
-    __device__ __forceinline__ void run_quant() {
+    // WM_ x WN_ waves form the workgroup tile; lds_all: the workgroup's LDS (free after the k loop, at least
+    // one byte per element of the tile); wm, wn: this wave's place
+    // PATH 0: any parameters (a division per element and step); 1 + HAS_MID + 2 HAS_BN: both steps allow the
+    // reciprocal sequence, the element code is free of branches
+    template <int WM_, int WN_, int PATH> __device__ __forceinline__ void run_quant(char* lds_all, int wm, int wn) {
+        constexpr bool FAST = PATH > 0, F_MID = ((PATH - 1) & 1) != 0, F_BN = ((PATH - 1) & 2) != 0;
         const bool out_i8 = p.out_dtype == DT_INT8;
         const bool has_bias = p.bias != nullptr, has_mul = p.q_mul != nullptr, has_add = p.q_add != nullptr;
         const bool has_bn = p.q_mean != nullptr;
+        const StepDiv mid_div = make_step_div(p.q_mid), out_div = make_step_div(p.q_out);
+        const bool relu = p.q_relu != 0;
         const int esz = out_i8 ? 1 : 4;
         const bool vec = (p.N % 4 == 0) && (p.ldc % 4 == 0) &&
                          (((uintptr_t)p.C + (uintptr_t)c_batch * esz) % (4 * esz) == 0);
-        // int8 codes of the whole wave tile pass through the wave's LDS slice once, so that the
-        // global stores are 16 bytes per lane along rows (needs whole aligned 16-byte chunks of C)
-        constexpr int ROW_BYTES = WTN;
+        // int8 codes of the whole WORKGROUP tile pass through LDS once, so that a store instruction writes whole
+        // rows of the tile (128 or 256 bytes; a wave tile alone is 64 bytes wide: half a cache line, and stores
+        // of half lines ran at a fraction of the memory rate).  Needs whole aligned 16-byte chunks of C.
+        constexpr int BM_ = WM_ * WTM, ROW_BYTES = WN_ * WTN;
         constexpr int CPR = ROW_BYTES / 16;
-        constexpr int RP = ROW_BYTES >= 256 ? 1 : 256 / ROW_BYTES;
-        constexpr bool CAN_STAGE = WTM * WTN <= LDS_PER_WAVE && 64 % CPR == 0;
+        constexpr bool CAN_STAGE = BM_ * ROW_BYTES <= WM_ * WN_ * LDS_PER_WAVE && CPR <= 64 && 64 % CPR == 0;
         const bool staged = CAN_STAGE && out_i8 && (p.N % 16 == 0) && (p.ldc % 16 == 0) &&
                             (((uintptr_t)p.C + (uintptr_t)c_batch) % 16 == 0);
 #pragma unroll
@@ -447,9 +454,9 @@ struct EpiCtx {
                 for (int e = 0; e < 4; ++e) {
                     const bool in = gn + e < p.N;
                     c[e].scale = in ? p.q_scale[gn + e] : 0.0f;
-                    c[e].bias = (in && has_bias) ? p.bias[gn + e] : 0.0f;
+                    c[e].bias = (in && has_bias) ? p.bias[gn + e] : (FAST ? -0.0f : 0.0f);
                     c[e].mul = (in && has_mul) ? p.q_mul[gn + e] : 1.0f;
-                    c[e].add = (in && has_add) ? p.q_add[gn + e] : 0.0f;
+                    c[e].add = (in && has_add) ? p.q_add[gn + e] : (FAST ? -0.0f : 0.0f);
                     c[e].mean = (in && has_bn) ? p.q_mean[gn + e] : 0.0f;
                     c[e].rinv = (in && has_bn) ? bn_rinv(p.q_var[gn + e], p.q_eps) : 1.0f;
                 }
@@ -461,18 +468,20 @@ struct EpiCtx {
                     const int64_t o = c_batch + (int64_t)gm * p.ldc + gn;
                     float t[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        t[e] = quant_value(__float_as_int(val(i, j, g, e)), c[e], has_bias, has_bn, has_mul, has_add,
-                                           p.q_mid, p.q_relu);
+                    for (int e = 0; e < 4; ++e) {
+                        const int a = __float_as_int(val(i, j, g, e));
+                        t[e] = FAST ? quant_value_fast<F_MID, F_BN>(a, c[e], mid_div, relu)
+                                    : quant_value(a, c[e], has_bias, has_bn, has_mul, has_add, mid_div, p.q_relu);
+                    }
                     if (out_i8) {
                         int8_t q[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) q[e] = quant_code(t[e], p.q_out);
+                        for (int e = 0; e < 4; ++e) q[e] = FAST ? (int8_t)quant_code_fast(t[e], out_div) : quant_code(t[e], out_div);
                         const unsigned w = (unsigned)(uint8_t)q[0] | ((unsigned)(uint8_t)q[1] << 8) |
                                            ((unsigned)(uint8_t)q[2] << 16) | ((unsigned)(uint8_t)q[3] << 24);
                         if (staged) {
-                            const int sw = (lrow / RP) % CPR;
-                            *(unsigned*)(wlds + lrow * ROW_BYTES + ((((lcol >> 4) ^ sw)) << 4) + (lcol & 15)) = w;
+                            const int trow = wm * WTM + lrow, tcol = wn * WTN + lcol;       // place in the workgroup tile
+                            *(unsigned*)(lds_all + trow * ROW_BYTES + ((((tcol >> 4) ^ (trow % CPR))) << 4) + (tcol & 15)) = w;
                         } else if (vec) {
                             *(unsigned*)((int8_t*)p.C + o) = w;
                         } else {
@@ -493,18 +502,20 @@ struct EpiCtx {
         }
         if constexpr (CAN_STAGE) {
             if (staged) {
-                constexpr int ROWS_PER_LD = 64 / CPR;
-                constexpr int NLD = WTM / ROWS_PER_LD;
-                const int ld_row = lane / CPR, ld_chunk = lane % CPR;
-                const int gn = col0 + ld_chunk * 16;
-                const int rows_left = (p.M - row0 < WTM ? p.M - row0 : WTM);
+                __syncthreads();              // the tile's codes are complete
+                constexpr int ROWS_PER_ST = 64 / CPR;                    // tile rows per store instruction
+                constexpr int ROWS_PER_WAVE = BM_ / (WM_ * WN_);
+                static_assert(ROWS_PER_WAVE % ROWS_PER_ST == 0, "rows of the tile split evenly over the waves' stores");
+                const int st_row = lane / CPR, st_chunk = lane % CPR;
+                const int m_tile = row0 - wm * WTM, n_tile = col0 - wn * WTN;
+                const int gn = n_tile + st_chunk * 16;
+                const int wave_rows = (wm * WN_ + wn) * ROWS_PER_WAVE;
 #pragma unroll
-                for (int q = 0; q < NLD; ++q) {
-                    const int lrow = q * ROWS_PER_LD + ld_row;
-                    const int sw = (lrow / RP) % CPR;
-                    const int4v w = *(const int4v*)(wlds + lrow * ROW_BYTES + ((ld_chunk ^ sw) << 4));
-                    if (lrow < rows_left && gn < p.N)
-                        *(int4v*)((int8_t*)p.C + c_batch + (int64_t)(row0 + lrow) * p.ldc + gn) = w;
+                for (int q = 0; q < ROWS_PER_WAVE / ROWS_PER_ST; ++q) {
+                    const int trow = wave_rows + q * ROWS_PER_ST + st_row;
+                    const int4v w = *(const int4v*)(lds_all + trow * ROW_BYTES + ((st_chunk ^ (trow % CPR)) << 4));
+                    if (m_tile + trow < p.M && gn < p.N)
+                        *(int4v*)((int8_t*)p.C + c_batch + (int64_t)(m_tile + trow) * p.ldc + gn) = w;
                 }
             }
         }
@@ -557,14 +568,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // pieces every line of A is requested from L2 twice (once per k-tile; measured: 1.5 times the
 // L1->L2 read requests of the 64-deep configurations), and that path is as loaded as the MFMA pipe.
 // ASTG 2: the same staging of A with SIX stages of B (NSTAGE = 5 sizes the LDS: 2 x 32 + 6 x 16 KiB of the 160)
-// and one barrier per PAIR of k-tiles.
+// and one barrier per PAIR of k-tiles.  With a k-major B (MODE_TRANS_B) the six stages are three pieces of
+// B staged 64 deep like A.
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC, int MI = 32,
           int ASTG = 0>
 __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mfma_kernel(Problem p, TileMap tmap) {
     constexpr bool S16 = MI == 16;
     constexpr bool ADBL = ASTG != 0;          // A staged 64 deep
     constexpr bool PAIRB = ASTG == 2;         // ... with one barrier per pair of k-tiles
-    static_assert(!ADBL || (MI == 16 && MODE == MODE_DENSE && BK == 32 && NSTAGE == (PAIRB ? 5 : 4)), "ASTG: see above");
+    static_assert(!ADBL || (MI == 16 && (MODE == MODE_DENSE || (PAIRB && MODE == MODE_TRANS_B)) && BK == 32 &&
+                            NSTAGE == (PAIRB ? 5 : 4)), "ASTG: see above");
     constexpr int BKA = ADBL ? 64 : BK;          // depth of one staged piece of A
     // raised wave priority around the MFMA groups: measured +1..2.5 % for one 256x256 workgroup per CU
     // and for the convolution, -1 % for two 128x256 workgroups per CU on plain matrices
@@ -665,12 +678,20 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             a_voff[r] = a_ok[r] ? (unsigned)(row * (int)p.lda * 2 + chunk * 16) : kOob;
         }
     }
-    unsigned b_voff[CB];
-    int b_kofs[CB];
+    // (pair pipeline with a k-major B: the pieces of B are 64 deep like A's, 2 CB loads per wave and PAIR)
+    constexpr bool BDBL = PAIRB && MODE == MODE_TRANS_B;
+    constexpr int CBP = BDBL ? 2 * CB : CB;
+    unsigned b_voff[CBP];
+    int b_kofs[CBP];
 #pragma unroll
-    for (int r = 0; r < CB; ++r) {
-        int blk = wave * CB + r;
-        if (TRANS_B) {
+    for (int r = 0; r < CBP; ++r) {
+        int blk = wave * CBP + r;
+        if (BDBL) {
+            int row = blk * KMA_ROWS + kma_row;
+            int chunk = kma_slot ^ kmajor_swz<BKA, S16>(row);
+            b_kofs[r] = chunk * 8;
+            b_voff[r] = (n0 + row < p.N) ? (unsigned)(row * (int)p.ldb * 2 + chunk * 16) : kOob;
+        } else if (TRANS_B) {
             int row = blk * KM_ROWS + km_row;
             int chunk = km_slot ^ kmajor_swz<BK, S16>(row);
             b_kofs[r] = chunk * 8;
@@ -1127,7 +1148,10 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             unsigned ad_sa = 0, ad_sb = 0;
             int ad_ka = 0, ad_kb = 0;
             auto begin_a = [&](int k0, int dst) { ad_ka = k0; ad_sa = lds_base + dst; ad_ra = make_rsrc(a_tile + (int64_t)k0 * 2); };
-            auto begin_b = [&](int k0, int dst) { ad_kb = k0; ad_sb = lds_base + dst; ad_rb = make_rsrc(b_tile + (int64_t)k0 * p.ldb * 2); };
+            auto begin_b = [&](int k0, int dst) {
+                ad_kb = k0; ad_sb = lds_base + dst;
+                ad_rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2 : b_tile + (int64_t)k0 * p.ldb * 2);
+            };
             auto issue_a = [&](int r, auto tail_tag) {
                 unsigned off = a_voff[r];
                 if (decltype(tail_tag)::value && ad_ka + a_kofs[r] >= p.K) off = kOob;
@@ -1136,7 +1160,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             auto issue_b = [&](int rb, auto tail_tag) {
                 unsigned off = b_voff[rb];
                 if (decltype(tail_tag)::value && ad_kb + b_kofs[rb] >= p.K) off = kOob;
-                dma16(ad_rb, ad_sb + (wave * CB + rb) * 1024, off);
+                dma16(ad_rb, ad_sb + (wave * CBP + rb) * 1024, off);
             };
             // A fragments of rows half `rh` from half `h` of the piece at sa
             auto read_a2 = [&](const char* sa, int h, int rh, short8v (&dst)[FMH]) {
@@ -1159,7 +1183,17 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                 constexpr int QM = FMH * FN;
                 static_assert(QM % CA == 0 && (3 * QM) % (4 * CB) == 0, "load positions");
                 auto stage_add = [](int sidx, int d) { const int r = sidx + d; return r >= NBS ? r - NBS : r; };
-                auto b_at = [&](int sidx) { return B_REGION + sidx * B_BYTES; };
+                // (k-major B: stages 2i and 2i+1 are the halves of the 64-deep piece i)
+                auto b_at = [&](int sidx) { return BDBL ? B_REGION + (sidx >> 1) * 2 * B_BYTES : B_REGION + sidx * B_BYTES; };
+                // B fragment j of the k-tile in stage sidx
+                auto read_bs = [&](int sidx, int j) -> short8v {
+                    if (BDBL) {
+                        const int row = wn * WTN + j * 16 + f16_row;
+                        return *(const short8v*)(lds + b_at(sidx) + kmajor_offset<64, true>(row, (sidx & 1) * 4 + f16_kc));
+                    } else {
+                        return read_b1(lds + b_at(sidx), 0, j);
+                    }
+                };
                 int bstage = 0;                  // B stage of the even tile of the current pair
                 int pair_burst = 0;              // drain: loads issued at the start of the current pair
                 auto a_frag = [&](const char* sa, int h, int rh, int i) -> short8v {
@@ -1184,8 +1218,8 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
 #pragma unroll
                                 for (int r = 0; r < 2 * CB; ++r) {
                                     if ((2 * r + 1) * (3 * QM) / (4 * CB) == idx) {
-                                        if (r == CB) begin_b((t + 5) * BK, b_at(stage_add(bstage, 5)));
-                                        issue_b(r % CB, TailNo{});
+                                        if (!BDBL && r == CB) begin_b((t + 5) * BK, b_at(stage_add(bstage, 5)));
+                                        issue_b(BDBL ? r : r % CB, TailNo{});
                                         __builtin_amdgcn_sched_barrier(0);
                                     }
                                 }
@@ -1206,7 +1240,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     begin_b((t + 4) * BK, b_at(stage_add(bstage, 4)));
                     begin_a((t + 4) * BK, a_lds(t + 4));
                     const char* sa = lds + a_lds(t);
-                    const char* sb1 = lds + b_at(stage_add(bstage, 1));
+                    const int s1 = stage_add(bstage, 1), s2 = stage_add(bstage, 2);
                     prio_up();
                     quarter(IntTag<0>{}, BoolTag<true>{}, t, [&](int k) {
                         if (k < FMH) { af[1][k] = a_frag(sa, 0, 1, k); __builtin_amdgcn_sched_barrier(0); }
@@ -1215,7 +1249,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     prio_up();
                     quarter(IntTag<1>{}, BoolTag<true>{}, t, [&](int k) {
                         if (k < FMH) { af[0][k] = a_frag(sa, 1, 0, k); __builtin_amdgcn_sched_barrier(0); }
-                        else if (k < FMH + FN) { bf[1][k - FMH] = read_b1(sb1, 0, k - FMH); __builtin_amdgcn_sched_barrier(0); }
+                        else if (k < FMH + FN) { bf[1][k - FMH] = read_bs(s1, k - FMH); __builtin_amdgcn_sched_barrier(0); }
                     });
                     prio_down();
                     prio_up();
@@ -1226,11 +1260,10 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     wait_vmcnt<2 * CB>();
                     __syncthreads();          // also: everyone is done reading what the next loads overwrite
                     const char* na = lds + a_lds(t + 2);
-                    const char* nb = lds + b_at(stage_add(bstage, 2));
                     prio_up();
                     quarter(IntTag<3>{}, BoolTag<true>{}, t, [&](int k) {
                         if (k < FMH) { af[0][k] = a_frag(na, 0, 0, k); __builtin_amdgcn_sched_barrier(0); }
-                        else if (k < FMH + FN) { bf[0][k - FMH] = read_b1(nb, 0, k - FMH); __builtin_amdgcn_sched_barrier(0); }
+                        else if (k < FMH + FN) { bf[0][k - FMH] = read_bs(s2, k - FMH); __builtin_amdgcn_sched_barrier(0); }
                     });
                     prio_down();
                     bstage = stage_add(bstage, 2);
@@ -1240,12 +1273,21 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     constexpr int PAR = decltype(par_tag)::value;
                     if (PAR == 0) {
                         pair_burst = 0;
-                        for (int d = 4; d <= 5; ++d) {
-                            if (t + d < KT) {
-                                begin_b((t + d) * BK, b_at(stage_add(bstage, d)));
+                        if (BDBL) {
+                            if (t + 4 < KT) {                 // one 64-deep piece: k-tiles t+4 and t+5 (zeros beyond K)
+                                begin_b((t + 4) * BK, b_at(stage_add(bstage, 4)));
 #pragma unroll
-                                for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
-                                pair_burst += CB;
+                                for (int r = 0; r < CBP; ++r) issue_b(r, TailYes{});
+                                pair_burst += CBP;
+                            }
+                        } else {
+                            for (int d = 4; d <= 5; ++d) {
+                                if (t + d < KT) {
+                                    begin_b((t + d) * BK, b_at(stage_add(bstage, d)));
+#pragma unroll
+                                    for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                                    pair_burst += CB;
+                                }
                             }
                         }
                     }
@@ -1266,12 +1308,12 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                         }
                     }
                     const char* na = lds + a_lds(t + 1);
-                    const char* nb = lds + b_at(stage_add(bstage, PAR + 1));
+                    const int sn = stage_add(bstage, PAR + 1);
                     prio_up();
                     quarter(IntTag<2 * PAR + 1>{}, BoolTag<false>{}, t, [&](int k) {
                         if (!have_next) return;
                         if (k < FMH) { af[0][k] = a_frag(na, PAR ^ 1, 0, k); __builtin_amdgcn_sched_barrier(0); }
-                        else if (k < FMH + FN) { bf[PAR ^ 1][k - FMH] = read_b1(nb, 0, k - FMH); __builtin_amdgcn_sched_barrier(0); }
+                        else if (k < FMH + FN) { bf[PAR ^ 1][k - FMH] = read_bs(sn, k - FMH); __builtin_amdgcn_sched_barrier(0); }
                     });
                     prio_down();
                     if (PAR == 1) bstage = stage_add(bstage, 2);
@@ -1281,10 +1323,16 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     begin_a(0, a_lds(0));
 #pragma unroll
                     for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
-                    for (int t = 0; t < 2 && t < KT; ++t) {
-                        begin_b(t * BK, b_at(t));
+                    if (BDBL) {
+                        begin_b(0, b_at(0));
 #pragma unroll
-                        for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                        for (int r = 0; r < CBP; ++r) issue_b(r, TailYes{});
+                    } else {
+                        for (int t = 0; t < 2 && t < KT; ++t) {
+                            begin_b(t * BK, b_at(t));
+#pragma unroll
+                            for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                        }
                     }
                     int later = 0;
                     if (2 < KT) {
@@ -1293,17 +1341,27 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                         for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
                         later += CA;
                     }
-                    for (int t = 2; t < 4 && t < KT; ++t) {
-                        begin_b(t * BK, b_at(t));
+                    if (BDBL) {
+                        if (2 < KT) {
+                            begin_b(2 * BK, b_at(2));
 #pragma unroll
-                        for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
-                        later += CB;
+                            for (int r = 0; r < CBP; ++r) issue_b(r, TailYes{});
+                            later += CBP;
+                        }
+                    } else {
+                        for (int t = 2; t < 4 && t < KT; ++t) {
+                            begin_b(t * BK, b_at(t));
+#pragma unroll
+                            for (int r = 0; r < CB; ++r) issue_b(r, TailYes{});
+                            later += CB;
+                        }
                     }
                     if (later >= CA + 2 * CB) wait_vmcnt<CA + 2 * CB>(); else if (later >= CA + CB) wait_vmcnt<CA + CB>();
                     else wait_vmcnt<0>();
                     __syncthreads();
                     read_a2(lds + a_lds(0), 0, 0, af[0]);
-                    read_b(lds + b_at(0), 0, bf[0]);
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) bf[0][j] = read_bs(0, j);
                     int t = 0;
                     for (; t + 6 <= KF; t += 2) pair_steady(t);
                     for (; t < KT; t += 2) {
@@ -1502,7 +1560,13 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     EpiCtx<TO, AccV, FM, FN, WTM, WTN, (NSTAGE * STAGE) / NW> ctx{p, acc, wlds, m0 + wm * WTM, n0 + wn * WTN, lane,
                                                          (int64_t)b * p.stride_c};
     if constexpr (sizeof(T) == 1 && MfmaOp<T>::kChunks == 1) {      // int8 operands
-        ctx.run_quant();
+        const bool has_mid = p.q_mid > 0.0f, has_bn = p.q_mean != nullptr;
+        const bool fast = (!has_mid || make_step_div(p.q_mid).fast) && (p.out_dtype != DT_INT8 || make_step_div(p.q_out).fast);
+        if (!fast) ctx.template run_quant<WM, WN, 0>(lds, wm, wn);
+        else if (!has_mid && !has_bn) ctx.template run_quant<WM, WN, 1>(lds, wm, wn);
+        else if (has_mid && !has_bn) ctx.template run_quant<WM, WN, 2>(lds, wm, wn);
+        else if (!has_mid) ctx.template run_quant<WM, WN, 3>(lds, wm, wn);
+        else ctx.template run_quant<WM, WN, 4>(lds, wm, wn);
     } else if (out_f32) {
         if (act == 0) ctx.template run<0, true>(); else if (act == 1) ctx.template run<1, true>();
         else ctx.template run<2, true>();

@@ -87,8 +87,9 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
 
 template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1, int MI = 32, int ASTG = 0>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
-    if constexpr (ASTG == 2) {            // built for plain row-major operands only
-        if (p.is_conv || p.trans_b) return hipErrorInvalidValue;
+    if constexpr (ASTG == 2) {            // built for plain matrices (B row-major or k-major) only
+        if (p.is_conv) return hipErrorInvalidValue;
+        if (p.trans_b) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC, MI, ASTG>(p, stream, group_m);
         return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC, MI, ASTG>(p, stream, group_m);
     } else {
     if (p.is_conv && p.conv.transposed) {

@@ -74,9 +74,53 @@ template <> __device__ __forceinline__ float widen<fp8_e4m3_t>(fp8_e4m3_t x) {
 // caller into a multiplier and a shift), ReLU, output quantisation).
 // Every step is a single binary32 operation in this order; contraction into fused
 // multiply-adds is switched off so that the integer codes come out bit-exact.
-__device__ __forceinline__ float quantise_step(float t, float step) {
+// t / step as the IEEE quotient, for one divisor used many times.  With y = RN(1 / step) (one real division
+// per kernel), q0 = RN(t y), r = t - step q0 (exact in a fused multiply-add) and q1 = RN(q0 + r y), q1 is the
+// correctly rounded quotient (the final step of the classic FMA division sequences; it needs y correctly
+// rounded, which fails only for a divisor whose significand is all ones) as long as nothing over- or
+// underflows on the way.  fast: the divisor is a normal number in [2^-63, 2^63] without that significand;
+// the dividend must be below 2^62 in magnitude, otherwise (and for NaN) the real division is taken.
+// Quotients too small to be normal numbers are not exact, which the callers do not need: they round the
+// quotient to an integer.
+struct StepDiv {
+    float step, rcp;
+    bool fast;
+};
+__device__ __forceinline__ StepDiv make_step_div(float step) {
 #pragma clang fp contract(off)
-    float q = __builtin_rintf(t / step);             // v_rndne_f32: nearest, ties to even
+    StepDiv d;
+    d.step = step;
+    d.rcp = 1.0f / step;
+    const uint32_t b = __builtin_bit_cast(uint32_t, step);
+    const uint32_t e = (b >> 23) & 0xFFu;
+    d.fast = e >= 64u && e <= 190u && (b & 0x7FFFFFu) != 0x7FFFFFu;
+    return d;
+}
+__device__ __forceinline__ float step_quotient(float t, const StepDiv& d) {
+#pragma clang fp contract(off)
+    if (d.fast && __builtin_fabsf(t) < 0x1p62f) {
+        const float q0 = t * d.rcp;
+        const float r = __builtin_fmaf(-d.step, q0, t);
+        return __builtin_fmaf(r, d.rcp, q0);
+    }
+    return t / d.step;
+}
+
+// The same for a divisor known to be `fast`, without the test of the dividend: the first product is kept
+// within +-2^30 (v_med3_f32; a quotient that large saturates whatever its last bits are, and the correction
+// still pushes it the right way), so that a huge or infinite dividend does not turn into NaN; a NaN dividend
+// stays NaN through the remainder.
+__device__ __forceinline__ float step_quotient_fast(float t, const StepDiv& d) {
+#pragma clang fp contract(off)
+    float q0 = t * d.rcp;
+    q0 = __builtin_amdgcn_fmed3f(q0, -0x1p30f, 0x1p30f);
+    const float r = __builtin_fmaf(-d.step, q0, t);
+    return __builtin_fmaf(r, d.rcp, q0);
+}
+
+__device__ __forceinline__ float quantise_step(float t, const StepDiv& d) {
+#pragma clang fp contract(off)
+    float q = __builtin_rintf(step_quotient(t, d));  // v_rndne_f32: nearest, ties to even
     q = q < -128.0f ? -128.0f : q;
     q = q > 127.0f ? 127.0f : q;
     return q;
@@ -98,14 +142,14 @@ __device__ __forceinline__ float bn_rinv(float var, float eps) {
 }
 
 __device__ __forceinline__ float quant_value(int acc, const QuantParams& c, bool has_bias, bool has_bn, bool has_mul,
-                                             bool has_add, float mid, int relu) {
+                                             bool has_add, const StepDiv& mid, int relu) {
 #pragma clang fp contract(off)
     float t = (float)acc;                             // v_cvt_f32_i32: round to nearest even
     t = t * c.scale;
     if (has_bias) t = t + c.bias;
-    if (mid > 0.0f) {
+    if (mid.step > 0.0f) {
         float q = quantise_step(t, mid);
-        t = q * mid;
+        t = q * mid.step;
     }
     if (has_bn) {                                     // then mul = gamma, add = beta
         t = t - c.mean;
@@ -117,7 +161,39 @@ __device__ __forceinline__ float quant_value(int acc, const QuantParams& c, bool
     return t;
 }
 
-__device__ __forceinline__ int8_t quant_code(float t, float out_scale) {
+// Branch-free form for the matrix-unit kernels: both steps `fast`; a part of the epilogue that is absent is
+// given its neutral value in `c` (bias and add: -0.0f, which leaves every value and the sign of zero as they
+// are; mul and rinv: 1.0f; mean: +0.0f).  Same operations in the same order as quant_value.
+template <bool HAS_MID, bool HAS_BN>
+__device__ __forceinline__ float quant_value_fast(int acc, const QuantParams& c, const StepDiv& mid, bool relu) {
+#pragma clang fp contract(off)
+    float t = (float)acc;
+    t = t * c.scale;
+    t = t + c.bias;
+    if (HAS_MID) {
+        float q = __builtin_rintf(step_quotient_fast(t, mid));
+        q = q < -128.0f ? -128.0f : q;                // (compare and select: NaN stays NaN)
+        q = q > 127.0f ? 127.0f : q;
+        t = q * mid.step;
+    }
+    if (HAS_BN) {
+        t = t - c.mean;
+        t = t * c.rinv;
+    }
+    t = t * c.mul;
+    t = t + c.add;
+    const bool zero = (t <= 0.0f) & relu;
+    return zero ? 0.0f : t;
+}
+// the output code; a NaN has no code that the method defines
+__device__ __forceinline__ int quant_code_fast(float t, const StepDiv& out_scale) {
+#pragma clang fp contract(off)
+    float q = __builtin_rintf(step_quotient_fast(t, out_scale));
+    q = __builtin_amdgcn_fmed3f(q, -128.0f, 127.0f);
+    return (int)q;
+}
+
+__device__ __forceinline__ int8_t quant_code(float t, const StepDiv& out_scale) {
     return (int8_t)(int)quantise_step(t, out_scale);
 }
 

@@ -47,7 +47,7 @@ def run_matmul(A, B, q, trans_b, out_int8, force=None, lda=None, ldb=None):
 SHAPES = [(300, 264, 208), (256, 256, 64), (520, 136, 80), (33, 520, 144), (64, 8, 16), (130, 260, 4096)]
 
 
-@pytest.mark.parametrize("cfg", [None, 0, 1, 4, 8, "generic"])
+@pytest.mark.parametrize("cfg", [None, 0, 1, 4, 8, 9, "generic"])
 @pytest.mark.parametrize("mnk", SHAPES)
 def test_matmul_int8_kmajor(cfg, mnk):
     import oracle
@@ -60,6 +60,19 @@ def test_matmul_int8_kmajor(cfg, mnk):
     print(f"int8 {mnk} force={force} kernel={kern} codes={len(np.unique(want))}", flush=True)
     assert ("generic" in kern) == (cfg == "generic")
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("k", [16, 64, 80, 128, 144, 192, 256, 272, 320, 400, 448, 528, 656, 2192])
+def test_matmul_int8_pair_pipeline_k_sweep(k):
+    """Both operands staged 128 values deep, one barrier per pair of 64-value k-tiles: prologue only, drain
+    only, odd and even tile counts, ragged last tiles, the paired steady state."""
+    import oracle
+    m, n = 300, 517
+    A = wl.int8_tensor((m, k), 1); B = wl.int8_tensor((n, k), 2)
+    q = params(n, 3)
+    got, kern = run_matmul(A, B, q, 1, True, "mfma:9")
+    assert "pair" in kern, kern
+    assert np.array_equal(got, oracle.matmul_int8(A, B, trans_b=1, **q))
 
 
 @pytest.mark.parametrize("variant", range(6))
@@ -86,7 +99,7 @@ def test_matmul_int8_row_major_b_runs_generic():
     assert np.array_equal(got, oracle.matmul_int8(A, B, trans_b=0, **q))
 
 
-@pytest.mark.parametrize("cfg", [None, 0, 1, 4, 8])
+@pytest.mark.parametrize("cfg", [None, 0, 1, 4, 8, 9])
 @pytest.mark.parametrize("mnk", [(300, 272, 208), (256, 512, 128), (33, 144, 4096)])
 def test_matmul_int8_row_major_b_on_mfma(cfg, mnk):
     """Row-major B: the n-major byte tile is read with the 8-bit transposing LDS read."""
@@ -188,7 +201,7 @@ def test_matmul_int8_full_size_sampled_rows():
     rows = np.array([0, 1, 127, 128, 4095, 4096, 8191, 777, 2301, 6000])
     want = oracle.matmul_int8(np.ascontiguousarray(A[rows]), B, trans_b=1, **q)
     print(f"int8 8192^3 kernel={kern} codes={len(np.unique(want))}", flush=True)
-    assert "256x256x64" in kern
+    assert "256x256" in kern
     assert np.array_equal(got[rows], want) and len(np.unique(want)) > 50
 
 

@@ -75,6 +75,16 @@ def test_matmul_a_staged_64_deep_k_sweep(cfg, dtype, k):
     check_full(w, force=f"mfma:{cfg}", expect_kernel="a64")
 
 
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("k", [8, 40, 64, 72, 96, 128, 136, 160, 168, 192, 200, 224, 232, 264, 328, 392, 1096])
+def test_matmul_pair_pipeline_k_major_b_k_sweep(dtype, k):
+    """Configuration 9 with a k-major B stages both operands 64 deep: the same sweep over the number of k-tiles,
+    with a ragged N and M."""
+    w = wl.Workload(f"mm_pair_tb_k{k}", "matmul", dtype, dtype, C.EPI_BIAS, M=300, N=517, K=k, trans_b=1,
+                    dist_b=("normal", 1.0 / np.sqrt(k)), dist_bias=("normal", 0.5))
+    check_full(w, force="mfma:9", expect_kernel="pair")
+
+
 @pytest.mark.parametrize("cfg", [7, 9])
 def test_batched_on_a_staged_64_deep(cfg):
     w = wl.Workload("bmm_a64", "batched", BF16, F32, C.EPI_NONE, alpha=0.5, batch=3, M=264, N=256, K=392,
