@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_conv2d_nhwc_residual.argtypes = [vp, vp, vp, vp, vp, vp] + [i64] * 13 + [i32, i32, f32, f32, i32]
         L.oracle_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32]
         L.oracle_attention_rows.argtypes = [vp, vp, vp, vp, vp] + [i64] * 12 + [i32, f32, i64, vp, vp]
+        L.oracle_attention_causal.argtypes = [vp, vp, vp, vp] + [i64] * 12 + [i32, f32]
+        L.oracle_attention_causal_rows.argtypes = [vp, vp, vp, vp] + [i64] * 10 + [i32, f32, i64, vp, vp]
         L.oracle_conv_out_dim.argtypes = [i64] * 5
         L.oracle_conv_out_dim.restype = i64
         L.oracle_epilogue.argtypes = [ctypes.c_double, ctypes.c_double, f32, i32]
@@ -458,6 +460,30 @@ def attention_rows(Q, K, V, bias, sb, si, *, dtype, alpha=1.0):
                                      ld_bias, stride_bias, dtype, float(alpha),
                                      sb.size, _ptr(sb), _ptr(si))
     _rc(rc, "attention_rows")
+    return out
+
+
+def attention_causal(Q, K, V, *, dtype, alpha=1.0):
+    """Causal attention (row i sees keys j <= i + Nk - Nq) as float64 [batch][Nq][D]."""
+    Q, K, V, batch, Nq, Nk, D, _, _ = _attention_args(Q, K, V, None, dtype)
+    out = np.empty((batch, Nq, D), dtype=np.float64)
+    rc = lib().oracle_attention_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(out),
+                                       batch, Nq, Nk, D, D, D, D, D, Nq * D, Nk * D, Nk * D, Nq * D,
+                                       dtype, float(alpha))
+    _rc(rc, "attention_causal")
+    return out
+
+
+def attention_causal_rows(Q, K, V, sb, si, *, dtype, alpha=1.0):
+    """Rows (sb[s], si[s]) of the causal result: float64 [nsamp][D]."""
+    Q, K, V, batch, Nq, Nk, D, _, _ = _attention_args(Q, K, V, None, dtype)
+    sb = np.ascontiguousarray(sb, dtype=np.int64)
+    si = np.ascontiguousarray(si, dtype=np.int64)
+    out = np.empty((sb.size, D), dtype=np.float64)
+    rc = lib().oracle_attention_causal_rows(_ptr(Q), _ptr(K), _ptr(V), _ptr(out),
+                                            batch, Nq, Nk, D, D, D, D, Nq * D, Nk * D, Nk * D,
+                                            dtype, float(alpha), sb.size, _ptr(sb), _ptr(si))
+    _rc(rc, "attention_causal_rows")
     return out
 
 

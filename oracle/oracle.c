@@ -890,6 +890,83 @@ int oracle_attention_rows(const void* Q, const void* K, const void* V, const flo
     return failed ? -8 : 0;
 }
 
+/* Causal form: row i sees keys 0 .. i + (Nk - Nq) only (the last query sees every key); the
+ * definition above restricted to those keys. */
+static int64_t causal_keys(int64_t i, int64_t Nq, int64_t Nk)
+{
+    int64_t n = i + (Nk - Nq) + 1;
+    return n < 0 ? 0 : (n > Nk ? Nk : n);
+}
+
+int oracle_attention_causal(const void* Q, const void* K, const void* V,
+                            double* out,
+                            int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                            int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                            int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                            int dtype, float alpha)
+{
+    int rc = check_attention(Q, K, V, out, batch, Nq, Nk, D, ldq, ldk, ldv, dtype);
+    if (rc) return rc;
+    if (ldo < D) return -5;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* scores = (double*)malloc((size_t)Nk * sizeof(double));
+        if (!scores) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 4)
+            for (int64_t r = 0; r < batch * Nq; ++r) {
+                int64_t b = r / Nq, i = r % Nq;
+                attention_row(Q, K, V, NULL, dtype, b * stride_q + i * ldq, b * stride_k,
+                              b * stride_v, 0, causal_keys(i, Nq, Nk), D, ldk, ldv,
+                              alpha, scores, out + b * stride_o + i * ldo);
+            }
+        }
+        free(scores);
+    }
+    return failed ? -8 : 0;
+}
+
+int oracle_attention_causal_rows(const void* Q, const void* K, const void* V,
+                                 double* out,
+                                 int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                                 int64_t ldq, int64_t ldk, int64_t ldv,
+                                 int64_t stride_q, int64_t stride_k, int64_t stride_v,
+                                 int dtype, float alpha,
+                                 int64_t nsamp, const int64_t* sb, const int64_t* si)
+{
+    int rc = check_attention(Q, K, V, out, batch, Nq, Nk, D, ldq, ldk, ldv, dtype);
+    if (rc) return rc;
+    if (nsamp < 0 || !sb || !si) return -5;
+    for (int64_t s = 0; s < nsamp; ++s)
+        if (sb[s] < 0 || sb[s] >= batch || si[s] < 0 || si[s] >= Nq) return -7;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* scores = (double*)malloc((size_t)Nk * sizeof(double));
+        if (!scores) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t s = 0; s < nsamp; ++s) {
+                int64_t b = sb[s], i = si[s];
+                attention_row(Q, K, V, NULL, dtype, b * stride_q + i * ldq, b * stride_k,
+                              b * stride_v, 0, causal_keys(i, Nq, Nk), D, ldk, ldv,
+                              alpha, scores, out + s * D);
+            }
+        }
+        free(scores);
+    }
+    return failed ? -8 : 0;
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

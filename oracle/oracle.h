@@ -216,6 +216,24 @@ int oracle_attention_rows(const void* Q, const void* K, const void* V, const flo
                           int dtype, float alpha,
                           int64_t nsamp, const int64_t* sb, const int64_t* si);
 
+/* Causal attention: the same operator in which query row i attends to the keys
+ * j <= i + (Nk - Nq) only (the mask of an autoregressive decoder; with Nq = Nk: j <= i;
+ * with fewer queries than keys the queries are the LAST Nq positions).  No bias.  A row that
+ * sees no key (possible only when Nq > Nk) is 0/0 and comes back NaN. */
+int oracle_attention_causal(const void* Q, const void* K, const void* V,
+                            double* out,
+                            int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                            int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                            int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                            int dtype, float alpha);
+int oracle_attention_causal_rows(const void* Q, const void* K, const void* V,
+                                 double* out,
+                                 int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                                 int64_t ldq, int64_t ldk, int64_t ldv,
+                                 int64_t stride_q, int64_t stride_k, int64_t stride_v,
+                                 int dtype, float alpha,
+                                 int64_t nsamp, const int64_t* sb, const int64_t* si);
+
 /* Output size of one spatial dimension, or -1 if empty/invalid. */
 int64_t oracle_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad, int64_t dil);
 
