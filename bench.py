@@ -152,9 +152,12 @@ def cpu_baseline_attention(w, host, budget_s=15.0):
         sb = r.integers(0, w.batch, size=nrows)
         si = r.integers(0, w.Nq, size=nrows)
         t0 = time.perf_counter()
-        oracle.attention_rows(host["q"], host["k"], host["v"], host["bias"], sb, si, dtype=w.dtype, alpha=w.alpha)
+        if w.causal:
+            oracle.attention_causal_rows(host["q"], host["k"], host["v"], sb, si, dtype=w.dtype, alpha=w.alpha)
+        else:
+            oracle.attention_rows(host["q"], host["k"], host["v"], host["bias"], sb, si, dtype=w.dtype, alpha=w.alpha)
         return time.perf_counter() - t0
-    per_row = 4.0 * w.Nk * w.D
+    per_row = w.flops / (w.batch * w.Nq)           # mean over the rows (a causal row sees a part of the keys)
     rows = 64
     dt = run(rows)
     rows2 = int(min(w.batch * w.Nq, max(rows, rows * budget_s / max(dt, 1e-6))))
@@ -301,7 +304,7 @@ def report(w, r, steps, warmup, with_cpu=True, traffic=None, copy_bw=None):
                     "epilogue": "dequant+bias+requant pair+affine+relu+quantise", "out_dtype": "int8",
                     "kernel": r["kernel"]} if is_int8(w) else
                    {"workload": w.name, "kind": "attention", "batch_x_heads": w.batch, "Nq": w.Nq, "Nk": w.Nk,
-                    "D": w.D, "bias": w.bias, "kernel": r["kernel"]} if is_attention(w) else
+                    "D": w.D, "bias": w.bias, "causal": bool(w.causal), "kernel": r["kernel"]} if is_attention(w) else
                    {"workload": w.name, "kind": w.kind, "gemm_mnk": list(w.gemm_mnk), "batch": w.batch,
                     "epilogue": w.epi, "out_dtype": DTYPE_NAMES[w.out_dtype], "kernel": r["kernel"]}),
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,

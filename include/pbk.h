@@ -270,6 +270,22 @@ pbk_status pbk_attention(const void* Q, const void* K, const void* V, const floa
                          int64_t ld_bias, int64_t stride_bias,
                          pbk_dtype dtype, float alpha, hipStream_t stream);
 
+/*
+ * Causal attention: the same operator in which query row i attends to the keys
+ * j <= i + (Nk - Nq) only (the mask of an autoregressive decoder; Sec. 4.4 operator
+ * with that mask; with Nq = Nk: j <= i; with fewer queries than keys the queries are
+ * the last Nq positions).  No bias.  Key tiles that no query of a workgroup can see
+ * are skipped, not masked: about half the work of the full operator for Nq = Nk.
+ * Arguments, layouts, types and errors as for pbk_attention.  A row that sees no key
+ * (possible only when Nq > Nk) has no defined result.  The matrix-unit kernel takes
+ * the causal form for alpha > 0; otherwise the generic kernel runs it.
+ */
+pbk_status pbk_attention_causal(const void* Q, const void* K, const void* V, void* O,
+                                int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                                int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                                int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                                pbk_dtype dtype, float alpha, hipStream_t stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* pbk_status_string(pbk_status s);
 

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     PBK_EPI_NONE, PBK_EPI_BIAS, PBK_EPI_RELU, PBK_EPI_BIAS_RELU,
     PBK_EPI_BIAS_GELU_TANH, PBK_EPI_GELU_TANH,
     PbkError, lib, lib_path, pbk_matmul, pbk_batched_matmul, pbk_conv2d_nhwc, pbk_conv2d_nhwc_pad4,
-    pbk_conv2d_transpose_nhwc, pbk_attention, pbk_matmul_int8, pbk_conv2d_nhwc_int8,
+    pbk_conv2d_transpose_nhwc, pbk_attention, pbk_attention_causal, pbk_matmul_int8, pbk_conv2d_nhwc_int8,
     pbk_matmul_residual, pbk_conv2d_nhwc_residual, pbk_matmul_int8_bn, pbk_conv2d_nhwc_int8_bn,
     pbk_status_string, pbk_version, pbk_last_kernel, pbk_force_kernel, check, EXPORTED_SYMBOLS,
 )

@@ -15,7 +15,7 @@ PBK_F32, PBK_BF16, PBK_F16, PBK_FP8_E4M3, PBK_FP8_E5M2, PBK_INT8 = 0, 1, 2, 3, 4
  PBK_EPI_BIAS_GELU_TANH, PBK_EPI_GELU_TANH) = range(6)
 
 EXPORTED_SYMBOLS = ("pbk_matmul", "pbk_batched_matmul", "pbk_conv2d_nhwc", "pbk_conv2d_nhwc_pad4",
-                    "pbk_conv2d_transpose_nhwc", "pbk_attention", "pbk_matmul_int8", "pbk_conv2d_nhwc_int8",
+                    "pbk_conv2d_transpose_nhwc", "pbk_attention", "pbk_attention_causal", "pbk_matmul_int8", "pbk_conv2d_nhwc_int8",
                     "pbk_matmul_residual", "pbk_conv2d_nhwc_residual", "pbk_matmul_int8_bn", "pbk_conv2d_nhwc_int8_bn",
                     "pbk_status_string", "pbk_version", "pbk_last_kernel", "pbk_force_kernel")
 
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.pbk_conv2d_nhwc_residual.restype = i32
         L.pbk_attention.argtypes = [vp, vp, vp, vp, vp] + [i64] * 14 + [i32, f32, vp]
         L.pbk_attention.restype = i32
+        L.pbk_attention_causal.argtypes = [vp, vp, vp, vp] + [i64] * 12 + [i32, f32, vp]
+        L.pbk_attention_causal.restype = i32
         L.pbk_status_string.argtypes = [i32]
         L.pbk_status_string.restype = ctypes.c_char_p
         L.pbk_version.restype = i32
@@ -188,6 +190,13 @@ def pbk_attention(Q, K, V, bias, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo,
     return lib().pbk_attention(_ptr(Q), _ptr(K), _ptr(V), _ptr(bias), _ptr(O), batch, Nq, Nk, D,
                                ldq, ldk, ldv, ldo, stride_q, stride_k, stride_v, stride_o,
                                ld_bias, stride_bias, dtype, float(alpha), _stream(stream))
+
+
+def pbk_attention_causal(Q, K, V, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo,
+                         stride_q, stride_k, stride_v, stride_o, dtype, alpha, stream=None) -> int:
+    return lib().pbk_attention_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), batch, Nq, Nk, D,
+                                      ldq, ldk, ldv, ldo, stride_q, stride_k, stride_v, stride_o,
+                                      dtype, float(alpha), _stream(stream))
 
 
 def pbk_status_string(status: int) -> str:

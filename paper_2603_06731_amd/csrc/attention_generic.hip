@@ -46,8 +46,14 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(AttnProblem p) {
     for (int e = 0; e < AG_DREG; ++e) o[e] = 0.0f;
     float m = -INFINITY, l = 0.0f;
 
-    for (int j0 = 0; j0 < p.Nk; j0 += AG_CHUNK) {
-        const int n = p.Nk - j0 < AG_CHUNK ? p.Nk - j0 : AG_CHUNK;
+    // causal: the row's keys are 0 .. i + (Nk - Nq); none at all gives 0 / 0
+    int nk = p.Nk;
+    if (p.causal) {
+        const long long vis = (long long)i + p.Nk - p.Nq + 1;
+        nk = vis < 0 ? 0 : vis < p.Nk ? (int)vis : p.Nk;
+    }
+    for (int j0 = 0; j0 < nk; j0 += AG_CHUNK) {
+        const int n = nk - j0 < AG_CHUNK ? nk - j0 : AG_CHUNK;
         float cmax = -INFINITY;
         for (int t = lane; t < n; t += 64) {
             const T* k = K + (int64_t)(j0 + t) * p.ldk;

@@ -30,7 +30,7 @@
 //                 is free as long as both operands agree); A = V^T produced by
 //                 the transposing LDS read from the d-contiguous V tile with the
 //                 matching key order.  No weight ever changes lane or touches LDS.
-#include "gemm_mfma_kernel.h"
+#include "gemm_mfma_launch.h"
 
 namespace pbk {
 namespace {
@@ -64,8 +64,11 @@ __device__ __forceinline__ void dma16_s(int4v rsrc, unsigned lds_addr, unsigned 
 // HAS_BIAS: an additive bias is read.  PRE: scores are multiplied by alpha*log2(e) (and the
 // bias added) before the row maximum is taken; without it (no bias, alpha > 0) the maximum is
 // taken on the raw scores and the scaling rides in the multiply-add in front of the exponential.
-template <typename T, int D, bool HAS_BIAS, bool PRE>
-__global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProblem p, int q_tiles, int total) {
+// CAUSAL: query q attends to keys <= q + (Nk - Nq).  The key tiles beyond the workgroup's last visible key
+// are not visited at all; in the blocks that the diagonal crosses the hidden scores are set to -inf like
+// the keys beyond Nk.
+template <typename T, int D, bool HAS_BIAS, bool PRE, bool CAUSAL>
+__global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProblem p, int q_tiles, int total, int xcds) {
     constexpr int KS = D / 16;                    // k16 steps of Q K^T
     constexpr int JD = D / 32;                    // 32-wide blocks of the head dimension
     constexpr int NPV = 2 * JD;                   // MFMAs of O^T += V^T P^T per 32-key block
@@ -86,11 +89,14 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
 
     // workgroups are dealt round-robin to the 8 XCDs: regroup so that one XCD (one L2)
     // owns a contiguous run of (batch, query tile) pairs and re-uses that batch's K and V
-    const int xq = total / 8, xr = total % 8;
-    const int xcd = blockIdx.x % 8, local = blockIdx.x / 8;
+    const int xq = total / xcds, xr = total % xcds;
+    const int xcd = blockIdx.x % xcds, local = blockIdx.x / xcds;
     const int id = xcd * xq + (xcd < xr ? xcd : xr) + local;
     const int b = id / q_tiles;
-    const int q0 = (id - b * q_tiles) * ATT_BQ + wave * 32;
+    // (causal: the last query tiles have the most keys to visit and are started first)
+    const int q_tile = CAUSAL ? q_tiles - 1 - (id - b * q_tiles) : id - b * q_tiles;
+    const int q0 = q_tile * ATT_BQ + wave * 32;
+    const int c_off = p.Nk - p.Nq;                 // causal: key visible iff key <= query + c_off
 
     const char* Kb = (const char*)p.K + (int64_t)b * p.stride_k * 2;
     const char* Vb = (const char*)p.V + (int64_t)b * p.stride_v * 2;
@@ -148,7 +154,13 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         }
     };
 
-    const int NT = (p.Nk + ATT_BKV - 1) / ATT_BKV;
+    int NT = (p.Nk + ATT_BKV - 1) / ATT_BKV;
+    if (CAUSAL) {
+        // the workgroup's last visible key (at least one tile is walked, so that every wave meets the barriers)
+        const long long last = (long long)q_tile * ATT_BQ + ATT_BQ - 1 + c_off;
+        const int nt_vis = last < 0 ? 1 : (int)(last / ATT_BKV) + 1;
+        NT = nt_vis < NT ? nt_vis : NT;
+    }
     issue_k(-1);
     issue_v(0);
     issue_k(0);
@@ -222,7 +234,10 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
             float v = sv[e];
             if (PRE) v *= c1;
             if (HAS_BIAS) v = fmaf(bias[e], LOG2E, v);
-            if (RAGGED && kbase + (e >> 2) * 8 + h * 4 + (e & 3) >= p.Nk) v = -INFINITY;
+            if (RAGGED) {
+                const int key = kbase + (e >> 2) * 8 + h * 4 + (e & 3);
+                if (key >= p.Nk || (CAUSAL && key > q0 + col + c_off)) v = -INFINITY;
+            }
             sv[e] = v;
         }
     };
@@ -284,7 +299,7 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         }
         float bias0[16];
         if (HAS_BIAS) load_bias(0, bias0);
-        if (32 > p.Nk) scale_scores(s_blk[0], 0, bias0, TailYes{}, 0, 16);
+        if (32 > p.Nk || (CAUSAL && 31 > q0 + c_off)) scale_scores(s_blk[0], 0, bias0, TailYes{}, 0, 16);
         else scale_scores(s_blk[0], 0, bias0, TailNo{}, 0, 16);
         float bmax = block_max(s_blk[0]);
         bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
@@ -366,7 +381,8 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
                     load_bias(knext, biasn);
                 }
             }
-            const bool ragged = knext + 32 > p.Nk;           // wave-uniform
+            // wave-uniform: the block reaches beyond Nk, or beyond what the wave's first query sees
+            const bool ragged = knext + 32 > p.Nk || (CAUSAL && knext + 31 > q0 + c_off);
             float bmax = -INFINITY;
             int mfma_idx = 0;
 #pragma unroll
@@ -423,24 +439,32 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
 template <typename T, int D>
 hipError_t launch_d(const AttnProblem& p, hipStream_t stream) {
     constexpr int LDS_BYTES = 2 * 2 * ATT_BKV * D * 2;
-    const void* kern = p.bias ? (const void*)attention_mfma_kernel<T, D, true, true>
-                       : p.alpha > 0.0f ? (const void*)attention_mfma_kernel<T, D, false, false>
-                                        : (const void*)attention_mfma_kernel<T, D, false, true>;
+    const void* kern = p.causal ? (const void*)attention_mfma_kernel<T, D, false, false, true>
+                       : p.bias ? (const void*)attention_mfma_kernel<T, D, true, true, false>
+                       : p.alpha > 0.0f ? (const void*)attention_mfma_kernel<T, D, false, false, false>
+                                        : (const void*)attention_mfma_kernel<T, D, false, true, false>;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    DeviceShape ds;
+    e = device_shape(dev, &ds);
+    if (e != hipSuccess) return e;
+    int xcds = ds.xcds;
     int q_tiles = (p.Nq + ATT_BQ - 1) / ATT_BQ;
     long long total = (long long)q_tiles * p.batch;
     if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     int tot = (int)total;
     AttnProblem pa = p;
-    void* args[] = {&pa, &q_tiles, &tot};
+    void* args[] = {&pa, &q_tiles, &tot, &xcds};
     return hipLaunchKernel(kern, dim3((unsigned)total), dim3(ATT_NW * 64), args, LDS_BYTES, stream);
 }
 
 template <typename T>
 hipError_t launch_t(const AttnProblem& p, hipStream_t stream, const char** name) {
     switch (p.D) {
-    case 32: *name = "attn_mfma_q128_kv64_d32"; return launch_d<T, 32>(p, stream);
-    case 64: *name = "attn_mfma_q128_kv64_d64"; return launch_d<T, 64>(p, stream);
-    case 128: *name = "attn_mfma_q128_kv64_d128"; return launch_d<T, 128>(p, stream);
+    case 32: *name = p.causal ? "attn_mfma_q128_kv64_d32_causal" : "attn_mfma_q128_kv64_d32"; return launch_d<T, 32>(p, stream);
+    case 64: *name = p.causal ? "attn_mfma_q128_kv64_d64_causal" : "attn_mfma_q128_kv64_d64"; return launch_d<T, 64>(p, stream);
+    case 128: *name = p.causal ? "attn_mfma_q128_kv64_d128_causal" : "attn_mfma_q128_kv64_d128"; return launch_d<T, 128>(p, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -454,6 +478,7 @@ bool al(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a
 bool attention_mfma_supported(const AttnProblem& p) {
     if (p.dtype != DT_BF16 && p.dtype != DT_F16) return false;
     if (p.D != 32 && p.D != 64 && p.D != 128) return false;
+    if (p.causal && (p.bias || !(p.alpha > 0.0f))) return false;      // the causal form is built for the plain variant
     if (!al(p.Q, 16) || !al(p.K, 16) || !al(p.V, 16) || !al(p.O, 8)) return false;
     if (p.ldq % 8 || p.ldk % 8 || p.ldv % 8 || p.ldo % 4) return false;
     if (p.stride_q % 8 || p.stride_k % 8 || p.stride_v % 8 || p.stride_o % 4) return false;

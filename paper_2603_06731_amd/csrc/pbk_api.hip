@@ -395,12 +395,12 @@ pbk_status pbk_conv2d_nhwc_int8_bn(const int8_t* x, const int8_t* w, void* y,
     return s;
 }
 
-pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,
-                         int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
-                         int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
-                         int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
-                         int64_t ld_bias, int64_t stride_bias,
-                         pbk_dtype dtype, float alpha, hipStream_t stream) {
+static pbk_status attention_common(const void* Q, const void* K, const void* V, const float* bias, void* O,
+                                   int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                                   int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                                   int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                                   int64_t ld_bias, int64_t stride_bias,
+                                   pbk_dtype dtype, float alpha, int causal, hipStream_t stream) {
     if (dtype != PBK_F32 && dtype != PBK_BF16 && dtype != PBK_F16) return PBK_ERR_DTYPE;
     if (batch < 0 || Nq < 0 || Nk < 0 || D < 1) return PBK_ERR_SHAPE;
     if (batch > INT_MAX || Nq > INT_MAX || Nk > INT_MAX || D > INT_MAX) return PBK_ERR_SHAPE;
@@ -422,7 +422,7 @@ pbk_status pbk_attention(const void* Q, const void* K, const void* V, const floa
     p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.ldo = ldo;
     p.stride_q = stride_q; p.stride_k = stride_k; p.stride_v = stride_v; p.stride_o = stride_o;
     p.ld_bias = bias ? ld_bias : 0; p.stride_bias = bias ? stride_bias : 0;
-    p.dtype = dtype; p.alpha = alpha;
+    p.dtype = dtype; p.alpha = alpha; p.causal = causal;
 
     int cfg = -1;
     const int force = forced_choice(&cfg);
@@ -439,6 +439,25 @@ pbk_status pbk_attention(const void* Q, const void* K, const void* V, const floa
     }
     g_last_kernel = name;
     return PBK_OK;
+}
+
+pbk_status pbk_attention(const void* Q, const void* K, const void* V, const float* bias, void* O,
+                         int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                         int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                         int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                         int64_t ld_bias, int64_t stride_bias,
+                         pbk_dtype dtype, float alpha, hipStream_t stream) {
+    return attention_common(Q, K, V, bias, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo, stride_q, stride_k, stride_v, stride_o,
+                            ld_bias, stride_bias, dtype, alpha, 0, stream);
+}
+
+pbk_status pbk_attention_causal(const void* Q, const void* K, const void* V, void* O,
+                                int64_t batch, int64_t Nq, int64_t Nk, int64_t D,
+                                int64_t ldq, int64_t ldk, int64_t ldv, int64_t ldo,
+                                int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                                pbk_dtype dtype, float alpha, hipStream_t stream) {
+    return attention_common(Q, K, V, nullptr, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo, stride_q, stride_k, stride_v, stride_o,
+                            0, 0, dtype, alpha, 1, stream);
 }
 
 const char* pbk_status_string(pbk_status s) {

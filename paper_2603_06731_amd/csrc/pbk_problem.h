@@ -69,6 +69,7 @@ struct AttnProblem {
     int64_t ld_bias, stride_bias;
     int dtype;                                           // of Q, K, V and O
     float alpha;
+    int causal;                                          // 1: row i attends to keys j <= i + (Nk - Nq) only (no bias then)
 };
 
 __host__ __device__ inline bool epi_has_bias(int epi) {

@@ -248,6 +248,11 @@ def run_attention(w: wl.AttentionWorkload, dev: dict, out=None, stream=None):
     import paper_2603_06731_amd as pbk
     if out is None:
         out = device_empty(w.batch * w.Nq * w.D, w.dtype)
+    if w.causal:
+        st = pbk.pbk_attention_causal(dev["q"], dev["k"], dev["v"], out, w.batch, w.Nq, w.Nk, w.D,
+                                      w.D, w.D, w.D, w.D, w.Nq * w.D, w.Nk * w.D, w.Nk * w.D, w.Nq * w.D,
+                                      w.dtype, w.alpha, stream)
+        return st, out
     ld_bias = w.Nk if w.bias != "none" else 0
     stride_bias = w.Nq * w.Nk if w.bias == "per_batch" else 0
     st = pbk.pbk_attention(dev["q"], dev["k"], dev["v"], dev["bias"], out, w.batch, w.Nq, w.Nk, w.D,
@@ -258,10 +263,14 @@ def run_attention(w: wl.AttentionWorkload, dev: dict, out=None, stream=None):
 
 def oracle_attention_full(w: wl.AttentionWorkload, host: dict) -> np.ndarray:
     import oracle
+    if w.causal:
+        return oracle.attention_causal(host["q"], host["k"], host["v"], dtype=w.dtype, alpha=w.alpha)
     return oracle.attention(host["q"], host["k"], host["v"], host["bias"], dtype=w.dtype, alpha=w.alpha)
 
 
 def oracle_attention_rows(w: wl.AttentionWorkload, host: dict, sb, si) -> np.ndarray:
     import oracle
+    if w.causal:
+        return oracle.attention_causal_rows(host["q"], host["k"], host["v"], sb, si, dtype=w.dtype, alpha=w.alpha)
     return oracle.attention_rows(host["q"], host["k"], host["v"], host["bias"], sb, si,
                                  dtype=w.dtype, alpha=w.alpha)

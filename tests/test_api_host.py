@@ -109,6 +109,18 @@ def test_attention_argument_errors(pbk):
     assert call(D=600, ldq=600, ldk=600, ldv=600, ldo=600, sq=4800, sk=4800, sv=4800, so=4800, dtype=F32) == 7
 
 
+def test_causal_attention_argument_errors(pbk):
+    BF16 = 1
+    P = 0x1000
+    att = pbk.pbk_attention_causal
+
+    def call(Q=P, K=P, V=P, O=P, batch=2, Nq=8, Nk=8, D=16, ldq=16, ldk=16, ldv=16, ldo=16,
+             sq=128, sk=128, sv=128, so=128, dtype=BF16):
+        return att(Q, K, V, O, batch, Nq, Nk, D, ldq, ldk, ldv, ldo, sq, sk, sv, so, dtype, 1.0)
+    assert call(dtype=5) == 5 and call(Nk=0) == 2 and call(batch=0) == 0
+    assert call(V=None) == 1 and call(ldk=8) == 3 and call(so=100) == 3 and call(Q=P + 1) == 4
+
+
 def test_conv_variant_argument_errors(pbk):
     F32 = 0
     P = 0x1000

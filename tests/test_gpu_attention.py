@@ -125,6 +125,80 @@ def test_attention_causal_mask_through_bias(force):
     assert np.array_equal(got[:, 0, :], v0)
 
 
+# (batch, Nq, Nk, D) with Nk >= Nq: every row sees at least one key
+CAUSAL_SHAPES = [
+    (2, 128, 128, 64),
+    (3, 200, 300, 64),
+    (1, 577, 577, 64),
+    (2, 10, 10, 64),
+    (1, 1, 1, 32),
+    (2, 130, 131, 128),
+    (1, 256, 256, 128),
+    (2, 297, 400, 32),
+    (1, 33, 500, 32),
+    (1, 1, 700, 64),         # one query at the end of a long context: sees every key
+]
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("shape", CAUSAL_SHAPES)
+def test_attention_causal_mfma(dtype, shape):
+    b, nq, nk, d = shape
+    w = wl.AttentionWorkload(f"att_causal_{b}x{nq}x{nk}x{d}", dtype, b, nq, nk, d, alpha=scale(d), causal=True)
+    check_attention(w, expect_kernel="causal")
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("shape", [(2, 50, 300, 64), (1, 17, 513, 40), (2, 9, 9, 3), (1, 70, 70, 200)])
+def test_attention_causal_generic(dtype, shape):
+    b, nq, nk, d = shape
+    w = wl.AttentionWorkload("att_causal_generic", dtype, b, nq, nk, d, alpha=scale(d), causal=True)
+    check_attention(w, force="generic", expect_kernel="attn_generic")
+
+
+def test_attention_causal_first_row_is_the_first_value_and_equals_the_masked_bias_form():
+    import torch
+    import paper_2603_06731_amd as pbk
+    b, n, d = 2, 333, 64
+    w = wl.AttentionWorkload("att_causal_row0", BF16, b, n, n, d, alpha=scale(d), causal=True)
+    host = wl.make_attention_inputs(w)
+    dev = T.upload(host)
+    st, out = T.run_attention(w, dev)
+    assert st == 0 and "causal" in pbk.pbk_last_kernel()
+    got = T.to_host_f64(out, BF16).reshape(b, n, d)
+    assert np.array_equal(got[:, 0, :], wl.widen(host["v"][:, 0, :], BF16))
+    # the same mask given as a bias of -inf: the two kernels agree to the rounding of the output
+    wb = wl.AttentionWorkload("att_causal_bias", BF16, b, n, n, d, alpha=scale(d), bias="shared")
+    hb = dict(host)
+    hb["bias"] = np.where(np.arange(n)[None, :] <= np.arange(n)[:, None], 0.0, -np.inf).astype(np.float32)
+    st, outb = T.run_attention(wb, T.upload(hb))
+    assert st == 0
+    gotb = T.to_host_f64(outb, BF16).reshape(b, n, d)
+    assert T.rel_err(got, gotb, gotb) <= ATT_TIGHT[BF16]
+
+
+@pytest.mark.parametrize("force", [None, "generic"])
+def test_attention_causal_more_queries_than_keys(force):
+    """Nq > Nk: the first Nq - Nk rows see no key (0/0: NaN on both sides), the others are defined."""
+    import paper_2603_06731_amd as pbk
+    b, nq, nk, d = 2, 200, 130, 64
+    w = wl.AttentionWorkload("att_causal_tall", BF16, b, nq, nk, d, alpha=scale(d), causal=True)
+    host = wl.make_attention_inputs(w)
+    with T.forced_kernel(force):
+        st, out = T.run_attention(w, T.upload(host))
+    assert st == 0, pbk.pbk_status_string(st)
+    ref = T.oracle_attention_full(w, host)
+    got = T.to_host_f64(out, BF16).reshape(ref.shape)
+    empty = nq - nk
+    assert np.isnan(ref[:, :empty]).all() and np.isnan(got[:, :empty]).all()
+    assert T.rel_err(got[:, empty:], ref[:, empty:], ref[:, empty:]) <= ATT_TIGHT[BF16]
+
+
+def test_attention_causal_nonpositive_scale_takes_the_generic_kernel():
+    w = wl.AttentionWorkload("att_causal_alpha0", BF16, 2, 150, 150, 64, alpha=0.0, causal=True)
+    check_attention(w, expect_kernel="attn_generic")
+
+
 @pytest.mark.parametrize("force", [None, "generic"])
 def test_attention_views_strides_and_guard_bands(force):
     """Row strides larger than D with NaN planted in the gaps, K and V shared by
@@ -172,7 +246,8 @@ def test_attention_is_deterministic():
 
 PAPER_SHAPES = ["attn_h16_n512_d64", "attn_h16_n2048_d64", "attn_h16_n8192_d64", "attn_h16_n512_d128",
                 "attn_h16_n2048_d128", "attn_h16_n8192_d128", "attn_h16_n577_d64", "attn_h12_n10_d64",
-                "attn_h6_n297_d64", "attn_h8_n500_d32", "attn_h32_n1024_d128"]
+                "attn_h6_n297_d64", "attn_h8_n500_d32", "attn_h32_n1024_d128",
+                "attn_h16_n2048_d64_causal", "attn_h16_n8192_d64_causal", "attn_h16_n8192_d128_causal"]
 
 
 @pytest.mark.parametrize("name", PAPER_SHAPES)

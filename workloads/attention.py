@@ -21,6 +21,7 @@ class AttentionWorkload:
     D: int
     alpha: float = 1.0           # score scale (an fp32 value)
     bias: str = "none"           # "none" | "shared" ([Nq][Nk]) | "per_batch" ([batch][Nq][Nk])
+    causal: bool = False         # row i attends to keys j <= i + (Nk - Nq) only (no bias then)
     dist_q: tuple = ("normal", 1.0)
     dist_k: tuple = ("normal", 1.0)
     dist_v: tuple = ("normal", 1.0)
@@ -30,8 +31,12 @@ class AttentionWorkload:
 
     @property
     def flops(self) -> int:
-        """Both contractions: 2*Nq*Nk*D each."""
-        return 4 * self.batch * self.Nq * self.Nk * self.D
+        """Both contractions: 2*D per (query, visible key) pair each."""
+        pairs = self.Nq * self.Nk
+        if self.causal:
+            off = self.Nk - self.Nq
+            pairs = sum(min(self.Nk, max(0, i + off + 1)) for i in range(self.Nq))
+        return 4 * self.batch * pairs * self.D
 
     @property
     def algorithmic_bytes(self) -> int:
@@ -45,8 +50,8 @@ def _scale(d: int) -> float:
     return float(np.float32(1.0 / math.sqrt(d)))
 
 
-def _paper_shape(name, heads, n, d, dtype=gen.DTYPE_BF16):
-    return AttentionWorkload(name, dtype, heads, n, n, d, alpha=_scale(d))
+def _paper_shape(name, heads, n, d, dtype=gen.DTYPE_BF16, causal=False):
+    return AttentionWorkload(name, dtype, heads, n, n, d, alpha=_scale(d), causal=causal)
 
 
 # (batch = 1) x heads, sequence length, head size: the rows of the paper's attention table
@@ -62,6 +67,10 @@ ATTENTION_CONFIGS = {w.name: w for w in [
     _paper_shape("attn_h6_n297_d64", 6, 297, 64),
     _paper_shape("attn_h8_n500_d32", 8, 500, 32),
     _paper_shape("attn_h32_n1024_d128", 32, 1024, 128),
+    # the long rows again with the decoder mask
+    _paper_shape("attn_h16_n2048_d64_causal", 16, 2048, 64, causal=True),
+    _paper_shape("attn_h16_n8192_d64_causal", 16, 8192, 64, causal=True),
+    _paper_shape("attn_h16_n8192_d128_causal", 16, 8192, 128, causal=True),
 ]}
 
 
