@@ -117,9 +117,12 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
     if (fp8) {
         // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
         // only the 64-deep configurations are built for it
-        if (cfg != 1 && cfg != 4) {       // (also a forced 5-8)
+        const bool kmajor = p.trans_b && !p.is_conv;
+        if (force_cfg != 1 && force_cfg != 4 && !(force_cfg == 9 && kmajor)) {       // (also a forced 5-8)
             long long t256 = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
-            cfg = (p.M >= 256 && p.N >= 256 && t256 >= 128) ? 4 : 1;
+            cfg = (p.M >= 256 && p.N >= 256 && t256 >= 128) ? (kmajor ? 9 : 4) : 1;
+        } else {
+            cfg = force_cfg;
         }
     }
     const int group_m = group_m_override() > 0 ? group_m_override() : 8;

@@ -31,6 +31,10 @@ hipError_t launch_fp8_cfg(const Problem& q, hipStream_t stream, int cfg, int gro
     switch (cfg) {
     case 1: return launch_typed_modes<T, TO, 128, 128, 64, 2, 2, 2, 1>(q, stream, group_m);
     case 4: return launch_typed_modes<T, TO, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
+    case 9:     // both operands k-major: 16x16x128 blocks in the pair pipeline (one MFMA k-step per pair of k-tiles)
+        if (q.trans_b && !q.is_conv)
+            return launch_one<T, TO, 256, 256, 32, 2, 4, MODE_TRANS_B, 5, 1, 16, 2>(q, stream, group_m);
+        return launch_typed_modes<T, TO, 256, 256, 64, 2, 4, 2, 1>(q, stream, group_m);
     default: return hipErrorInvalidValue;
     }
 }

@@ -122,6 +122,24 @@ template <> struct MfmaOp<fp8_e5m2_t> {
     }
 };
 
+// (FP8 has no 16-byte-fragment 16x16 instruction at its full rate; these exist so that the 16-bit pipelines
+// still parse for an FP8 type: the FP8 form of the pair pipeline issues MfmaOp16x128 instead)
+template <> struct MfmaOp16<fp8_e4m3_t> { static __device__ __forceinline__ f32x4 run(short8v, short8v, f32x4 c) { return c; } };
+template <> struct MfmaOp16<fp8_e5m2_t> { static __device__ __forceinline__ f32x4 run(short8v, short8v, f32x4 c) { return c; } };
+// FP8, 16x16 blocks: v_mfma_f32_16x16x128_f8f6f4, 32 bytes (32 values) per lane and operand: lane l supplies,
+// for the operand row l % 16, the 32 consecutive k that start at 32 (l / 16)
+template <typename T> struct MfmaOp16x128;
+template <> struct MfmaOp16x128<fp8_e4m3_t> {
+    static __device__ __forceinline__ f32x4 run(int8v a, int8v b, f32x4 c) {
+        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+    }
+};
+template <> struct MfmaOp16x128<fp8_e5m2_t> {
+    static __device__ __forceinline__ f32x4 run(int8v a, int8v b, f32x4 c) {
+        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 1, 1, 0, 0, 0, 0);
+    }
+};
+
 // int8: v_mfma_i32_32x32x32_i8, 16 bytes (16 values) per lane and operand; the 32-bit integer
 // accumulators travel in the same registers, typed as floats only in name
 typedef __attribute__((ext_vector_type(16))) int i32x16;
@@ -582,8 +600,11 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
     // raised wave priority around the MFMA groups: measured +1..2.5 % for one 256x256 workgroup per CU
     // and for the convolution, -1 % for two 128x256 workgroups per CU on plain matrices
     constexpr bool PRIO = BM == 256 || MODE == MODE_CONV;
-    static_assert(MI == 32 || (MI == 16 && (sizeof(T) == 2 || (std::is_same<T, int8_t>::value && MODE == MODE_TRANS_B))),
-                  "16x16 blocks are built for the 16-bit types and for int8 with both operands k-major");
+    // FP8 in the pair pipeline: one v_mfma_f32_16x16x128 per 64-deep piece of both (k-major) operands
+    constexpr bool F8PAIR = PAIRB && MfmaOp<T>::kChunks == 2;
+    static_assert(MI == 32 || (MI == 16 && (sizeof(T) == 2 || (std::is_same<T, int8_t>::value && MODE == MODE_TRANS_B) ||
+                                            (F8PAIR && MODE == MODE_TRANS_B))),
+                  "16x16 blocks are built for the 16-bit types and for 8-bit types with both operands k-major");
     constexpr bool CONVT = MODE == MODE_CONVT;               // transposed convolution: gather form
     constexpr bool CONV = MODE == MODE_CONV || CONVT;        // A is an image, rows are output pixels
     constexpr bool TRANS_B = MODE == MODE_TRANS_B;
@@ -1200,6 +1221,138 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     const int row = wm * WTM + (rh * FMH + i) * 16 + f16_row;
                     return *(const short8v*)(sa + kmajor_offset<64, true>(row, h * 4 + f16_kc));
                 };
+                auto prio_up = [&]() { if (PRIO) __builtin_amdgcn_s_setprio(2); };
+                auto prio_down = [&]() { if (PRIO) __builtin_amdgcn_s_setprio(0); __builtin_amdgcn_sched_barrier(0); };
+                if constexpr (F8PAIR) {
+                    // ---- FP8: a pair of k-tiles (128 values) is ONE k-step of v_mfma_f32_16x16x128.  A pair is two
+                    // halves of QM MFMAs (rows half 0, rows half 1); the barrier stands between them, when the A
+                    // fragments of rows half 1 have been read.  B of pair p+2 goes out during the first half, A of pair
+                    // p+2 during the second; the next pair's fragments are read under the second half: its A
+                    // fragments of rows half 0 into af8[0] (free after the first half), its B fragment j into bf8[j]
+                    // right after the MFMAs of column j (the second half runs column by column for that).
+                    int8v af8[2][FMH], bf8[FN];
+                    auto frag8 = [&](const char* piece, int row) __attribute__((always_inline)) -> int8v {
+                        const int4v lo = *(const int4v*)(piece + kmajor_offset<64, true>(row, 2 * f16_kc));
+                        const int4v hi = *(const int4v*)(piece + kmajor_offset<64, true>(row, 2 * f16_kc + 1));
+                        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    };
+                    auto a8 = [&](int t, int rh, int i) __attribute__((always_inline)) -> int8v {
+                        return frag8(lds + a_lds(t), wm * WTM + (rh * FMH + i) * 16 + f16_row);
+                    };
+                    auto b8 = [&](int sidx, int j) __attribute__((always_inline)) -> int8v {
+                        return frag8(lds + b_at(sidx), wn * WTN + j * 16 + f16_row);
+                    };
+                    // first half: rows half 0, MFMA (i, j) in row order; mid(k) after MFMA k; STEADY: B load r after MFMA 4 r + 2
+                    auto half0 = [&](auto steady_tag, auto&& mid) __attribute__((always_inline)) {
+                        constexpr bool STEADY = decltype(steady_tag)::value;
+#pragma unroll
+                        for (int i = 0; i < FMH; ++i)
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) {
+                                acc[i][j] = MfmaOp16x128<T>::run(bf8[j], af8[0][i], acc[i][j]);
+                                mid(i * FN + j);
+                                if (STEADY) {
+#pragma unroll
+                                    for (int r = 0; r < CBP; ++r)
+                                        if ((2 * r + 1) * QM / (2 * CBP) == i * FN + j) { issue_b(r, TailNo{}); __builtin_amdgcn_sched_barrier(0); }
+                                }
+                            }
+                    };
+                    // second half: rows half 1, column by column; mid(k) after MFMA k; STEADY: A load r after MFMA r QM / CA
+                    auto half1 = [&](auto steady_tag, auto&& mid) __attribute__((always_inline)) {
+                        constexpr bool STEADY = decltype(steady_tag)::value;
+#pragma unroll
+                        for (int j = 0; j < FN; ++j)
+#pragma unroll
+                            for (int i = 0; i < FMH; ++i) {
+                                acc[FMH + i][j] = MfmaOp16x128<T>::run(bf8[j], af8[1][i], acc[FMH + i][j]);
+                                mid(j * FMH + i);
+                                if (STEADY) {
+#pragma unroll
+                                    for (int r = 0; r < CA; ++r)
+                                        if (r * (QM / CA) == j * FMH + i) { issue_a(r, TailNo{}); __builtin_amdgcn_sched_barrier(0); }
+                                }
+                            }
+                    };
+                    // reads of the next pair (even tile tn, B stage sn) under the second half: B column j after its
+                    // last MFMA (k = j FMH + FMH - 1), A fragment i of rows half 0 after MFMA j FMH + i of column 0 .. 
+                    auto next_reads = [&](int k, int tn, int sn) __attribute__((always_inline)) {
+                        if (k < FMH) { af8[0][k] = a8(tn, 0, k); __builtin_amdgcn_sched_barrier(0); }
+                        if ((k % FMH) == FMH - 1) { bf8[k / FMH] = b8(sn, k / FMH); __builtin_amdgcn_sched_barrier(0); }
+                    };
+                    auto pair_steady8 = [&](int t) __attribute__((always_inline)) {
+                        begin_b((t + 4) * BK, b_at(stage_add(bstage, 4)));
+                        begin_a((t + 4) * BK, a_lds(t + 4));
+                        prio_up();
+                        half0(BoolTag<true>{}, [&](int k) {
+                            if (k < FMH) { af8[1][k] = a8(t, 1, k); __builtin_amdgcn_sched_barrier(0); }
+                        });
+                        prio_down();
+                        wait_vmcnt<CBP>();
+                        __syncthreads();          // also: everyone is done reading what the next loads overwrite
+                        const int sn = stage_add(bstage, 2);
+                        prio_up();
+                        half1(BoolTag<true>{}, [&](int k) { next_reads(k, t + 2, sn); });
+                        prio_down();
+                        bstage = sn;
+                    };
+                    // drain: the pair of tiles t, t+1 (t+1 may lie beyond K: zeros), loads in bursts and only where tiles exist
+                    auto drain_pair8 = [&](int t, bool have_next) __attribute__((always_inline)) {
+                        int burst = 0;
+                        if (t + 4 < KT) {
+                            begin_b((t + 4) * BK, b_at(stage_add(bstage, 4)));
+#pragma unroll
+                            for (int r = 0; r < CBP; ++r) issue_b(r, TailYes{});
+                            burst = CBP;
+                        }
+                        prio_up();
+                        half0(BoolTag<false>{}, [&](int k) {
+                            if (k < FMH) { af8[1][k] = a8(t, 1, k); __builtin_amdgcn_sched_barrier(0); }
+                        });
+                        prio_down();
+                        if (have_next) {
+                            if (burst) wait_vmcnt<CBP>(); else wait_vmcnt<0>();
+                            __syncthreads();
+                            if (t + 4 < KT) {
+                                begin_a((t + 4) * BK, a_lds(t + 4));
+#pragma unroll
+                                for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                            }
+                        }
+                        const int sn = stage_add(bstage, 2);
+                        prio_up();
+                        half1(BoolTag<false>{}, [&](int k) { if (have_next) next_reads(k, t + 2, sn); });
+                        prio_down();
+                        bstage = sn;
+                    };
+                    if (KT > 0) {
+                        begin_a(0, a_lds(0));
+#pragma unroll
+                        for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                        begin_b(0, b_at(0));
+#pragma unroll
+                        for (int r = 0; r < CBP; ++r) issue_b(r, TailYes{});
+                        if (2 < KT) {
+                            begin_a(2 * BK, a_lds(2));
+#pragma unroll
+                            for (int r = 0; r < CA; ++r) issue_a(r, TailYes{});
+                            begin_b(2 * BK, b_at(2));
+#pragma unroll
+                            for (int r = 0; r < CBP; ++r) issue_b(r, TailYes{});
+                            wait_vmcnt<CA + CBP>();
+                        } else {
+                            wait_vmcnt<0>();
+                        }
+                        __syncthreads();
+#pragma unroll
+                        for (int i = 0; i < FMH; ++i) af8[0][i] = a8(0, 0, i);
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) bf8[j] = b8(0, j);
+                        int t = 0;
+                        for (; t + 6 <= KF; t += 2) pair_steady8(t);
+                        for (; t < KT; t += 2) drain_pair8(t, t + 2 < KT);
+                    }
+                } else {
                 // quarter Q of the pair whose even tile is t: tile Q/2, rows half Q%2, B fragments in bf[Q/2].
                 // STEADY: B load r of the pair goes after MFMA (2r+1) 3QM/(4CB) of the pair, A load r after
                 // MFMA 3QM + r QM/CA.
@@ -1233,8 +1386,6 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                             }
                         }
                 };
-                auto prio_up = [&]() { if (PRIO) __builtin_amdgcn_s_setprio(2); };
-                auto prio_down = [&]() { if (PRIO) __builtin_amdgcn_s_setprio(0); __builtin_amdgcn_sched_barrier(0); };
                 // steady pair: tiles t, t+1; tiles t+4, t+5 are full
                 auto pair_steady = [&](int t) {
                     begin_b((t + 4) * BK, b_at(stage_add(bstage, 4)));
@@ -1369,6 +1520,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                         if (t + 1 < KT) drain_tile(IntTag<1>{}, t + 1, t + 2 < KT);
                     }
                 }
+                }   // !F8PAIR
             } else {
                 constexpr int NT = 2 * FMH * FN;           // MFMAs per k-tile
                 constexpr int NB = FMH * FN;               // of which before the barrier
