@@ -126,8 +126,8 @@ template <> struct MfmaOp<fp8_e5m2_t> {
 // still parse for an FP8 type: the FP8 form of the pair pipeline issues MfmaOp16x128 instead)
 template <> struct MfmaOp16<fp8_e4m3_t> { static __device__ __forceinline__ f32x4 run(short8v, short8v, f32x4 c) { return c; } };
 template <> struct MfmaOp16<fp8_e5m2_t> { static __device__ __forceinline__ f32x4 run(short8v, short8v, f32x4 c) { return c; } };
-// FP8, 16x16 blocks: v_mfma_f32_16x16x128_f8f6f4, 32 bytes (32 values) per lane and operand: lane l supplies,
-// for the operand row l % 16, the 32 consecutive k that start at 32 (l / 16)
+// FP8, 16x16 blocks: v_mfma_f32_16x16x128_f8f6f4, 32 bytes (32 values) per lane and operand: lane l supplies 32
+// values of the operand row l % 16; which k they are is free as long as both operands are loaded alike
 template <typename T> struct MfmaOp16x128;
 template <> struct MfmaOp16x128<fp8_e4m3_t> {
     static __device__ __forceinline__ f32x4 run(int8v a, int8v b, f32x4 c) {
@@ -1232,8 +1232,11 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                     // right after the MFMAs of column j (the second half runs column by column for that).
                     int8v af8[2][FMH], bf8[FN];
                     auto frag8 = [&](const char* piece, int row) __attribute__((always_inline)) -> int8v {
-                        const int4v lo = *(const int4v*)(piece + kmajor_offset<64, true>(row, 2 * f16_kc));
-                        const int4v hi = *(const int4v*)(piece + kmajor_offset<64, true>(row, 2 * f16_kc + 1));
+                        // the lane's 32 values are chunks kc and 4 + kc of the row's eight (the sum over k is order-free
+                        // and both operands are read alike): each read is then the bank-conflict-free pattern of the
+                        // 16-bit fragments (chunks 2 kc, 2 kc + 1: every second LDS cycle a conflict, by the counter)
+                        const int4v lo = *(const int4v*)(piece + kmajor_offset<64, true>(row, f16_kc));
+                        const int4v hi = *(const int4v*)(piece + kmajor_offset<64, true>(row, 4 + f16_kc));
                         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     };
                     auto a8 = [&](int t, int rh, int i) __attribute__((always_inline)) -> int8v {
