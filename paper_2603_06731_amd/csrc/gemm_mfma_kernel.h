@@ -1540,7 +1540,7 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
                             const int idx = (st * FMH + i) * FN + j;
     #pragma unroll
                             for (int r = 0; r < L; ++r) {
-                                if ((r * NT) / L == idx) {
+                                if ((r * NT) / (L > 0 ? L : 1) == idx) {      // (L = 0: the loop is empty)
                                     if (L > CB && r < CA) issue_a(r, TailNo{}); else issue_b(L > CB ? r - CA : r, TailNo{});
                                     __builtin_amdgcn_sched_barrier(0);
                                 }

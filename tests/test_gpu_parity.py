@@ -125,7 +125,8 @@ def test_matmul_generic_odd_shapes(dtype, mnk, trans_b):
                     trans_b=trans_b, dist_b=("normal", 1.0 / np.sqrt(k)))
     # 16-bit operands with enough work (M N >= 4096, K >= 16) take the gathering matrix-unit kernel
     gather = dtype != F32 and m * n >= 4096 and k >= 16
-    check_full(w, expect_kernel="gather" if gather else "generic")
+    # small fp32 problems take the one-wave-per-tile kernel
+    check_full(w, expect_kernel="small_f32" if dtype == F32 else "gather" if gather else "generic")
     check_full(w, force="generic", expect_kernel="generic")
 
 
@@ -431,7 +432,9 @@ def test_fp32_matmul_on_mfma(cfg, mnk, trans_b):
     w = wl.Workload("f32_mfma", "matmul", F32, F32, C.EPI_BIAS_GELU_TANH, alpha=0.75, M=m, N=n, K=k, trans_b=trans_b,
                     dist_a=("uniform", 1.0), dist_b=("uniform", 1.0), dist_bias=("uniform", 1.0))
     if cfg is None and m * n < 1024 * 1024:
-        check_full(w, expect_kernel="generic")          # too little work: the dispatcher keeps the generic kernel
+        # too little work for 128-wide tiles: the one-wave-per-tile kernel up to 1024 tiles of 16 x 16, else the generic one
+        small = ((m + 15) // 16) * ((n + 15) // 16) <= 1024
+        check_full(w, expect_kernel="small_f32" if small else "generic")
     else:
         check_full(w, force=None if cfg is None else f"mfma:{cfg}", expect_kernel="mfma_f32")
 
