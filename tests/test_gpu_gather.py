@@ -174,3 +174,40 @@ def test_paper_example_full_size_against_an_aligned_twin():
         times[cin] = e0.elapsed_time(e1) / 20 * 1e3
         print(f"paper conv Cin={cin}: kernel={kern} {times[cin]:.1f} us err={err:.2e}", flush=True)
     assert times[127] <= 2.0 * times[128], times
+
+
+def test_matmul_k1143_beside_aligned_twin_and_generic_kernel():
+    """3528 x 512 x 1143 (the matmul form of the paper's example, lda = K) on the gathering kernel, beside
+    K = 1152 on the direct-to-LDS kernel and the generic kernel, both B layouts: timing table and the 2x bar."""
+    import torch
+    import paper_2603_06731_amd as pbk
+    M, N = 3528, 512
+
+    def timed(K, trans_b, force):
+        a = T.to_device(wl.tensor((M, K), BF16, 1, "normal"))
+        b = T.to_device(wl.tensor(((N, K) if trans_b else (K, N)), BF16, 2, "normal", 1.0 / np.sqrt(K)))
+        out = T.device_empty(M * N, BF16)
+        with T.forced_kernel(force):
+            def call():
+                return pbk.pbk_matmul(a, b, out, None, M, N, K, K, (K if trans_b else N), N, BF16, BF16, trans_b, 1.0,
+                                      C.EPI_NONE)
+            assert call() == 0
+            kern = pbk.pbk_last_kernel()
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+            for _ in range(3):
+                call()
+            e0.record()
+            for _ in range(20):
+                call()
+            e1.record(); torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 20 * 1e3
+        print(f"{M}x{N}x{K} trans_b={trans_b} {kern}: {us:.1f} us", flush=True)
+        return us, kern
+    for trans_b in (0, 1):
+        g, kg = timed(1143, trans_b, None)
+        al, ka = timed(1152, trans_b, None)
+        timed(1152, trans_b, "gather")
+        gen, _ = timed(1143, trans_b, "generic")
+        assert "gather" in kg and "gather" not in ka and "mfma" in ka
+        assert g <= 2.0 * al and g < gen, (g, al, gen)
