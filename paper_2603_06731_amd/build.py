@@ -11,13 +11,17 @@ LIB = os.path.join(HERE, "libpbk.so")
 # (source, object stem, extra defines).  The 16-bit kernels compile once per element type and group of
 # tile configurations (csrc/gemm_mfma_launch.h: kGroupMask16), in parallel.
 N_GROUPS_16 = 5
-SOURCES = [("pbk_api.hip", "pbk_api", []), ("gemm_generic.hip", "gemm_generic", []), ("gemm_mfma.hip", "gemm_mfma", []),
-           ("gemm_mfma_gather.hip", "gemm_mfma_gather", []), ("gemm_small_f32.hip", "gemm_small_f32", [])]
+# (the units that take longest to compile come first: the pool starts them first)
+SOURCES = [("gemm_mfma_fp8_tu.hip", f"gemm_mfma_fp8_{name}_{out}",
+            [f"-DPBK_FP8_TYPE=fp8_{name}_t", f"-DPBK_FP8_NAME={name}", f"-DPBK_FP8_OUT={out}_t", f"-DPBK_FP8_OUTNAME={out}"])
+           for name in ("e4m3", "e5m2") for out in ("bf16", "f16")]
+SOURCES += [("gemm_mfma_int8.hip", "gemm_mfma_int8", [])]
 SOURCES += [("gemm_mfma_16bit.hip", f"gemm_mfma_{name}_g{g}",
              [f"-DPBK_16BIT_TYPE={name}_t", f"-DPBK_16BIT_NAME={name}", f"-DPBK_GROUP={g}"])
-            for g in range(N_GROUPS_16) for name in ("bf16", "f16")]
-SOURCES += [(f, f[:-4], []) for f in ("gemm_mfma_fp8.hip", "gemm_mfma_fp8_e5m2.hip", "gemm_mfma_int8.hip", "gemm_mfma_f32.hip",
-                                      "attention_generic.hip", "attention_mfma.hip")]
+            for g in reversed(range(N_GROUPS_16)) for name in ("bf16", "f16")]
+SOURCES += [(f, f[:-4], []) for f in ("gemm_mfma_gather.hip", "gemm_mfma_f32.hip", "attention_mfma.hip", "gemm_mfma_fp8.hip",
+                                      "gemm_mfma.hip", "pbk_api.hip", "gemm_generic.hip", "gemm_small_f32.hip",
+                                      "attention_generic.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -39,15 +39,4 @@ hipError_t launch_fp8_cfg(const Problem& q, hipStream_t stream, int cfg, int gro
     }
 }
 
-template <typename T>
-hipError_t launch_fp8_type(const Problem& p, hipStream_t stream, int cfg, int group_m) {
-    const Problem q = to_k_units(p);
-    // an F32 output does not use the 16-bit output type at all
-    if (q.out_dtype == DT_F16) return launch_fp8_cfg<T, f16_t>(q, stream, cfg, group_m);
-    return launch_fp8_cfg<T, bf16_t>(q, stream, cfg, group_m);
-}
-
-hipError_t launch_mfma_fp8_e4m3(const Problem& p, hipStream_t stream, int cfg, int group_m);
-hipError_t launch_mfma_fp8_e5m2(const Problem& p, hipStream_t stream, int cfg, int group_m);
-
 }  // namespace pbk

@@ -1,16 +1,20 @@
-// FP8 E4M3 instantiations of the MFMA contraction kernel (v_mfma_f32_32x32x64_f8f6f4, 32 bytes
-// per lane and operand), and the dispatch between the two FP8 types.
+// FP8 operands: dispatch to the translation unit that holds the operand type and the 16-bit output type
+// (gemm_mfma_fp8_tu.hip); an F32 output does not use the 16-bit output type at all and takes the bf16 unit.
 #include "gemm_mfma_8bit.h"
 
 namespace pbk {
 
-hipError_t launch_mfma_fp8_e4m3(const Problem& p, hipStream_t stream, int cfg, int group_m) {
-    return launch_fp8_type<fp8_e4m3_t>(p, stream, cfg, group_m);
-}
+hipError_t launch_mfma_fp8_e4m3_bf16(const Problem& q, hipStream_t stream, int cfg, int group_m);
+hipError_t launch_mfma_fp8_e4m3_f16(const Problem& q, hipStream_t stream, int cfg, int group_m);
+hipError_t launch_mfma_fp8_e5m2_bf16(const Problem& q, hipStream_t stream, int cfg, int group_m);
+hipError_t launch_mfma_fp8_e5m2_f16(const Problem& q, hipStream_t stream, int cfg, int group_m);
 
 hipError_t launch_mfma_fp8(const Problem& p, hipStream_t stream, int cfg, int group_m) {
-    return p.in_dtype == DT_FP8_E4M3 ? launch_mfma_fp8_e4m3(p, stream, cfg, group_m)
-                                     : launch_mfma_fp8_e5m2(p, stream, cfg, group_m);
+    const Problem q = to_k_units(p);
+    const bool f16_out = q.out_dtype == DT_F16;
+    if (p.in_dtype == DT_FP8_E4M3)
+        return f16_out ? launch_mfma_fp8_e4m3_f16(q, stream, cfg, group_m) : launch_mfma_fp8_e4m3_bf16(q, stream, cfg, group_m);
+    return f16_out ? launch_mfma_fp8_e5m2_f16(q, stream, cfg, group_m) : launch_mfma_fp8_e5m2_bf16(q, stream, cfg, group_m);
 }
 
 }  // namespace pbk
