@@ -67,6 +67,11 @@ static int choose_config(const Problem& p) {
     // (9 = 7 with one barrier per two k-tiles: 8192^3 739 against 757 us, the MLP shape 711 against 726 us,
     // interleaved runs; 6 % on a 24-tile problem that is not power limited)
     if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 3072) return 9;
+    // convolutions whose channel count is a multiple of 64 (the image is then staged in 64-deep pieces): 9 from one
+    // round of 256x256 tiles and K = 1024 up (32x56x56x256 -> 256, 3x3: 131 against 151 us; 64x28x28x256 -> 512: 121
+    // against 133 us; K = 576 equal; 1x1 filters and fewer than 100 tiles: 6 or 1 stay ahead by 10-15 %)
+    if (p.is_conv && !p.conv.transposed && p.conv.Cin % 64 == 0 && p.M >= 256 && p.N >= 256 && t256 >= 256 && p.K >= 1024)
+        return 9;
     if (p.M >= 128 && p.N >= 256 && t >= 256) return 6;
     return 1;
 }
@@ -113,7 +118,8 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
     int cfg = (force_cfg >= 0 && force_cfg < kNumMfmaConfigs) ? force_cfg : choose_config(p);
     if (p.is_conv && p.conv.transposed && cfg != 0 && cfg != 1 && cfg != 6) cfg = choose_config(p);   // the ones built
     if (!fp8 && ((cfg >= 2 && cfg <= 4) || cfg == 8)) cfg = choose_config(p);   // 16-bit types: 0, 1, 5, 6, 7, 9 are built
-    if (cfg == 9 && p.is_conv) cfg = 7;       // 9 is built for plain matrices
+    // 9 takes a convolution whose channel count is a multiple of 64 (not the transposed form)
+    if (cfg == 9 && p.is_conv && (p.conv.transposed || p.conv.Cin % 64 != 0)) cfg = 7;
     if (fp8) {
         // the FP8 instruction consumes a 64-deep k-tile (in 2-byte units) in two steps:
         // only the 64-deep configurations are built for it

@@ -587,15 +587,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // L1->L2 read requests of the 64-deep configurations), and that path is as loaded as the MFMA pipe.
 // ASTG 2: the same staging of A with SIX stages of B (NSTAGE = 5 sizes the LDS: 2 x 32 + 6 x 16 KiB of the 160)
 // and one barrier per PAIR of k-tiles.  With a k-major B (MODE_TRANS_B) the six stages are three pieces of
-// B staged 64 deep like A.
+// B staged 64 deep like A.  A convolution (MODE_CONV) takes the pair pipeline when Cin is a multiple of 64: a 64-deep
+// piece of the image then lies inside one filter tap.
 template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int MODE, int NSTAGE, int OCC, int MI = 32,
           int ASTG = 0>
 __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mfma_kernel(Problem p, TileMap tmap) {
     constexpr bool S16 = MI == 16;
     constexpr bool ADBL = ASTG != 0;          // A staged 64 deep
     constexpr bool PAIRB = ASTG == 2;         // ... with one barrier per pair of k-tiles
-    static_assert(!ADBL || (MI == 16 && (MODE == MODE_DENSE || (PAIRB && MODE == MODE_TRANS_B)) && BK == 32 &&
-                            NSTAGE == (PAIRB ? 5 : 4)), "ASTG: see above");
+    static_assert(!ADBL || (MI == 16 && (MODE == MODE_DENSE || (PAIRB && (MODE == MODE_TRANS_B || MODE == MODE_CONV))) &&
+                            BK == 32 && NSTAGE == (PAIRB ? 5 : 4)), "ASTG: see above");
     constexpr int BKA = ADBL ? 64 : BK;          // depth of one staged piece of A
     // raised wave priority around the MFMA groups: measured +1..2.5 % for one 256x256 workgroup per CU
     // and for the convolution, -1 % for two 128x256 workgroups per CU on plain matrices
@@ -1168,13 +1169,32 @@ __global__ __launch_bounds__(WM * WN * 64, (OCC * WM * WN + 3) / 4) void gemm_mf
             int4v ad_ra = make_rsrc(a_tile), ad_rb = make_rsrc(b_tile);
             unsigned ad_sa = 0, ad_sb = 0;
             int ad_ka = 0, ad_kb = 0;
-            auto begin_a = [&](int k0, int dst) { ad_ka = k0; ad_sa = lds_base + dst; ad_ra = make_rsrc(a_tile + (int64_t)k0 * 2); };
+            // convolution: tap offsets of the piece being issued (uniform: the whole 64-deep piece lies in one tap)
+            int ad_dh = 0, ad_dw = 0;
+            unsigned ad_delta = 0;
+            auto begin_a = [&](int k0, int dst) {
+                ad_ka = k0; ad_sa = lds_base + dst;
+                if (CONV) {
+                    const int tap = k0 / p.conv.Cin, c = k0 - tap * p.conv.Cin;
+                    const int kh = tap / p.conv.KW, kw = tap - kh * p.conv.KW;
+                    ad_dh = kh * p.conv.dil_h; ad_dw = kw * p.conv.dil_w;
+                    ad_delta = (unsigned)(((ad_dh * p.conv.W + ad_dw) * p.conv.Cin + c) * 2);
+                } else {
+                    ad_ra = make_rsrc(a_tile + (int64_t)k0 * 2);
+                }
+            };
             auto begin_b = [&](int k0, int dst) {
                 ad_kb = k0; ad_sb = lds_base + dst;
                 ad_rb = make_rsrc(TRANS_B ? b_tile + (int64_t)k0 * 2 : b_tile + (int64_t)k0 * p.ldb * 2);
             };
             auto issue_a = [&](int r, auto tail_tag) {
                 unsigned off = a_voff[r];
+                if (CONV) {
+                    off = a_voff[r] + ad_delta + (unsigned)(a_kofs[r] * 2);
+                    const int ih = a_ih0[r] + ad_dh, iw = a_iw0[r] + ad_dw;
+                    const bool ok = a_ok[r] && ih >= 0 && ih < p.conv.H && iw >= 0 && iw < p.conv.W;
+                    off = ok ? off : kOob;
+                }
                 if (decltype(tail_tag)::value && ad_ka + a_kofs[r] >= p.K) off = kOob;
                 dma16(ad_ra, ad_sa + (wave * CA + r) * 1024, off);
             };

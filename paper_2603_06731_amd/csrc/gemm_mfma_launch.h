@@ -88,7 +88,10 @@ hipError_t launch_one(const Problem& p, hipStream_t stream, int group_m) {
 template <typename T, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int OCC = 1, int MI = 32, int ASTG = 0>
 hipError_t launch_modes(const Problem& p, hipStream_t stream, int group_m) {
     if constexpr (ASTG == 2) {            // built for plain matrices (B row-major or k-major) only
-        if (p.is_conv) return hipErrorInvalidValue;
+        if (p.is_conv) {          // the image in 64-deep pieces: each must lie inside one filter tap
+            if (p.conv.transposed || p.conv.Cin % 64 != 0) return hipErrorInvalidValue;
+            return launch_one<T, T, BM, BN, BK, WM, WN, MODE_CONV, NSTAGE, OCC, MI, ASTG>(p, stream, group_m);
+        }
         if (p.trans_b) return launch_one<T, T, BM, BN, BK, WM, WN, MODE_TRANS_B, NSTAGE, OCC, MI, ASTG>(p, stream, group_m);
         return launch_one<T, T, BM, BN, BK, WM, WN, MODE_DENSE, NSTAGE, OCC, MI, ASTG>(p, stream, group_m);
     } else {

@@ -180,6 +180,26 @@ def test_conv_small_mfma(case, cfg):
     check_full(w, force=None if cfg is None else f"mfma:{cfg}", expect_kernel="mfma")
 
 
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("case", [
+    # n, H, W, Cin, Cout, KH, KW, stride, pad, dil: channel counts that are multiples of 64, so that the pair
+    # pipeline stages the image 64 deep; 2 to 50 k-tiles (prologue only, drain only, the steady state), padding
+    # on every side, stride, dilation, ragged M and Cout
+    (3, 9, 9, 64, 8, 1, 1, (1, 1), (0, 0), (1, 1)),
+    (2, 14, 13, 64, 264, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (1, 23, 21, 128, 136, 3, 3, (2, 2), (0, 0), (1, 1)),
+    (2, 17, 19, 64, 72, 5, 3, (1, 2), (2, 1), (2, 1)),
+    (1, 20, 20, 192, 256, 1, 3, (1, 1), (0, 1), (1, 1)),
+    (1, 12, 12, 320, 40, 2, 2, (1, 1), (1, 0), (1, 1)),
+])
+def test_conv_pair_pipeline(case, dtype):
+    n, H, W, Cin, Cout, KH, KW, stride, pad, dil = case
+    w = wl.Workload("conv_pair", "conv", dtype, dtype, C.EPI_BIAS_RELU, n=n, H=H, W=W, Cin=Cin, Cout=Cout,
+                    KH=KH, KW=KW, stride=stride, pad=pad, dil=dil,
+                    dist_b=("normal", float(np.sqrt(2.0 / (KH * KW * Cin)))))
+    check_full(w, force="mfma:9", expect_kernel="pair")
+
+
 @pytest.mark.parametrize("dtype,out_dtype", [(F16, F32), (F32, F32), (BF16, BF16)])
 def test_conv_generic_tiny_channels(dtype, out_dtype):
     # Cin = 3, Cout = 3, 5x5 filter: the shape family of the paper's second worked example
