@@ -61,6 +61,9 @@ def bound_of(w):
     return ("mfma", peak) if ai >= ridge else ("hbm", PEAK_HBM_GBS)
 
 
+ZERO_OPERANDS = False      # set by --zero-operands
+
+
 def time_workload(w, steps, warmup):
     """Returns dict with wall ms/step over the timed region and per-launch event times."""
     import torch
@@ -88,6 +91,12 @@ def time_workload(w, steps, warmup):
         run = T.run_workload
     if not is_int8(w):
         dev = T.upload(host)
+    if ZERO_OPERANDS:
+        # power-limit probe: the same launches on all-zero A and B (the matrix units then draw far less power and
+        # the chip holds its nominal clock); the figure says what the kernel sustains when the clock is not cut
+        for key in ("a", "b", "q", "k", "v"):
+            if key in dev and hasattr(dev[key], "zero_"):
+                dev[key].zero_()
     # Working sets that fit the 256 MB memory-side cache are rotated over several copies of the inputs and
     # the output (enough to exceed twice that cache, at most 8), so that a launch does not find the operands
     # of the previous one still cached; larger ones need no rotation.
@@ -299,7 +308,7 @@ def report(w, r, steps, warmup, with_cpu=True, traffic=None, copy_bw=None):
         "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": r["wall_ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": DTYPE_NAMES[in_dtype_of(w)], "data": "synthetic",
+        "dtype": DTYPE_NAMES[in_dtype_of(w)], "data": "zeros (power-limit probe, not a benchmark result)" if ZERO_OPERANDS else "synthetic",
         "config": ({"workload": w.name, "kind": "matmul_int8", "gemm_mnk": [w.M, w.N, w.K], "trans_b": 1,
                     "epilogue": "dequant+bias+requant pair+affine+relu+quantise", "out_dtype": "int8",
                     "kernel": r["kernel"]} if is_int8(w) else
@@ -344,17 +353,22 @@ def main():
     ap.add_argument("--extra", action="store_true", help="with --all: include the FP8, int8 and attention workloads")
     ap.add_argument("--no-traffic", action="store_true", help="do not measure HBM traffic with rocprofv3 child runs")
     ap.add_argument("--no-copy", action="store_true", help="do not time the device copy / fill")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="power-limit probe: time the same launches on all-zero operands (not a benchmark result: "
+                         "the line is marked \"data\": \"zeros\")")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
+    global ZERO_OPERANDS
+    ZERO_OPERANDS = args.zero_operands
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the contraction shards by output tiles without "
                  "any exchange; nothing multi-GPU is implemented). Use --gpus 1.")
 
     # HBM traffic counters: child runs under the profiler, before this process touches the GPU
     traffic = None
-    if not (args.no_traffic or args.calibrate_copy or args.all):
+    if not (args.no_traffic or args.calibrate_copy or args.all or args.zero_operands):
         traffic = measure_traffic(args.workload)
 
     import torch
