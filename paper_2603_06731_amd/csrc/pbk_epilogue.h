@@ -15,13 +15,14 @@ struct fp8_e4m3_t { uint8_t v; };
 struct fp8_e5m2_t { uint8_t v; };
 
 __device__ __forceinline__ float gelu_tanh_f32(float t) {
-    // 0.5*t*(1+tanh(u)), u = sqrt(2/pi)*(t + 0.044715 t^3); tanh(u) = 1 - 2/(exp(2u)+1)
-    const float c = 0.7978845608028654f;
-    float u = c * (t + 0.044715f * t * t * t);
-    float e = __expf(2.0f * u);
-    // hardware reciprocal (1 ulp) instead of an IEEE division: e = inf gives 0, e = 0 gives 1
-    float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
-    return 0.5f * t * (1.0f + th);
+    // 0.5 t (1 + tanh(u)), u = sqrt(2/pi) (t + 0.044715 t^3), written as t / (1 + exp(-2u)) (the same function:
+    // 1 + tanh(u) = 2 / (1 + exp(-2u))); the exponential in base 2 with the constants folded:
+    // -2u log2(e) = t (k1 + k2 t^2).  Hardware exp2 and reciprocal (1 ulp each); exp2 = inf gives -0, 0 gives t.
+    const float k1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+    const float k2 = k1 * 0.044715f;
+    const float w = t * fmaf(k2, t * t, k1);
+    const float e = __builtin_amdgcn_exp2f(w);
+    return t * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 // ReLU that keeps NaN: "greater than zero, or unordered" selects t (the compare of the paper's fused nest;
