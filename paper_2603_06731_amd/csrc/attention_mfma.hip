@@ -15,7 +15,11 @@
 // j's exponentials run, so the K tiles are shifted by half a tile against the V
 // tiles; the weights of block j multiply V while block j+1's row maximum is
 // found.  Two workgroups share a CU, so that one wave's softmax arithmetic
-// also overlaps the other's MFMAs on every SIMD.
+// also overlaps the other's MFMAs on every SIMD.  The tiles that lie entirely
+// inside the key range (and below the causal diagonal) run in an instance of
+// the loop body without any range test: a body with branches is split into
+// basic blocks, and the compiler then sinks the softmax arithmetic out of the
+// MFMA slots it was written into.
 //
 // Register layouts (v_mfma_f32_32x32x16, D[i][j] += sum_k A[i][k] B[k][j]; a lane
 // supplies row i = lane%32 of A and column j = lane%32 of B, 8 consecutive k
@@ -31,6 +35,7 @@
 //                 the transposing LDS read from the d-contiguous V tile with the
 //                 matching key order.  No weight ever changes lane or touches LDS.
 #include "gemm_mfma_launch.h"
+#include <type_traits>
 
 namespace pbk {
 namespace {
@@ -306,13 +311,48 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         move_reference(bmax);
     }
 
-    // ---- main loop over 64-key tiles, two 32-key blocks each.  For block j (scores already in
-    // registers): phase 1 turns them into weights while the MFMAs of the NEXT block's scores
-    // run; phase 2 multiplies the weights into O while the next block's scores are prepared and
-    // its row maximum is found.  PAR: parity of the tile = LDS slot, compile-time so that
-    // every LDS address is a per-lane register plus an immediate.
-    auto tile = [&](int t, auto par_tag) {
+    // ---- main loop over 64-key tiles, two 32-key blocks each.  A block j (scores already in
+    // registers) takes 2 KS' MFMAs: the KS of the NEXT block's scores, then the NPV of its own
+    // weights times V; the softmax arithmetic is dealt over the slots behind these MFMAs so that
+    // every MFMA has about the same number of vector instructions behind it:
+    //   behind score MFMA ks:        exponentials of weight pairs [ks NP1/KS, (ks+1) NP1/KS)
+    //   behind P V MFMA (st 0, j):   the remaining pairs (they feed st 1), scaling / masking of the next scores
+    //   behind P V MFMA (st 1, j):   row sum of the rounded weights, maximum of the next scores
+    // PAR: parity of the tile = LDS slot, compile-time so that every LDS address is a per-lane
+    // register plus an immediate.  CLEAN: the tile, the two score blocks computed in it and the
+    // next tile's loads are all inside the key range (and below the diagonal): no test, no branch
+    // other than the rare move of the reference point, so the body is one basic block and the
+    // order written here is the order that runs.
+    constexpr int NP1 = 5;                                    // weight pairs finished under the score MFMAs (st 0 needs 4)
+    auto exchange_max = [&](float v) {                       // maximum with lane ^ 32, no LDS round trip
+        const unsigned u = __builtin_bit_cast(unsigned, v);
+        auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+    };
+    auto pair_sum = [&](int w, float acc) {                  // acc + both 16-bit weights of w
+        if constexpr (sizeof(T) == 2 && std::is_same<T, bf16_t>::value) {
+            typedef __attribute__((ext_vector_type(2))) __bf16 b2;
+            const b2 one = {(__bf16)1.0f, (__bf16)1.0f};
+            return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, w), one, acc, false);
+        } else {
+            typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+            const h2 one = {(_Float16)1.0f, (_Float16)1.0f};
+            return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, w), one, acc, false);
+        }
+    };
+    auto issue_in = [&](int t) {                              // tile t's V and K, every row inside the key range
+        const int4v rv = make_rsrc(Vb + (int64_t)t * ATT_BKV * p.ldv * 2);
+        const unsigned sv = lds_base + (2 + (t & 1)) * TILE;
+#pragma unroll
+        for (int r = 0; r < CPW; ++r) dma16_s(rv, sv + (wave * CPW + r) * 1024, v_voff[r]);
+        const int4v rk = make_rsrc(Kb + (int64_t)(t * ATT_BKV + 32) * p.ldk * 2);
+        const unsigned sk = lds_base + (t & 1) * TILE;
+#pragma unroll
+        for (int r = 0; r < CPW; ++r) dma16_s(rk, sk + (wave * CPW + r) * 1024, k_voff[r]);
+    };
+    auto tile = [&](int t, auto par_tag, auto clean_tag) {
         constexpr int PAR = decltype(par_tag)::value;
+        constexpr bool CLEAN = decltype(clean_tag)::value;
         wait_vmcnt<0>();              // this wave's pieces of V(t), K(t) have landed
         __syncthreads();              // everyone's have; everyone is done with V(t-1), K(t-1)
         // the first fragment reads of the tile go out before the (scalar-heavy) issue of the
@@ -328,6 +368,7 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         // are issued after it has been consumed.
         float bias_first[16];
         if (HAS_BIAS) load_bias(t * ATT_BKV + 32, bias_first);
+        else if (CLEAN) issue_in(t + 1);
         else if (t + 1 < NT) { issue_v(t + 1); issue_k(t + 1); }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -339,16 +380,20 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
             const int knext = t * ATT_BKV + 32 * hb + 32;             // first key of the next block
             const float m_use = m_run == -INFINITY ? 0.0f : m_run;
             const float neg_m = -m_use;
+            int pw[8];                 // the block's 16 weights, rounded and packed in pairs
+            auto weights = [&](int i) {
+                const float p0 = fast_exp2(PRE ? s_cur[2 * i] - m_use : fmaf(s_cur[2 * i], c1, neg_m));
+                const float p1 = fast_exp2(PRE ? s_cur[2 * i + 1] - m_use : fmaf(s_cur[2 * i + 1], c1, neg_m));
+                pw[i] = (int)pack2<T>(p0, p1);
+            };
 
-            // ---- phase 1
+            // ---- scores of the next block, weights of this one
             if (hb != 0) {
 #pragma unroll
                 for (int ks = 0; ks < KPF; ++ks) read_k(kcb, ks);
                 read_v(vcb);
             }
             __builtin_amdgcn_sched_barrier(0);
-            int pw[8];                 // the block's 16 weights, rounded and packed in pairs
-            float psum = 0.0f;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks + KPF < KS) read_k(kcb, ks + KPF);
@@ -360,18 +405,12 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
                 s_nxt = MfmaOp<T>::run(kfr[ks & 3], qf[ks], s_nxt);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    if (i < ks * 8 / KS || i >= (ks + 1) * 8 / KS) continue;
-                    const float p0 = fast_exp2(PRE ? s_cur[2 * i] - m_use : fmaf(s_cur[2 * i], c1, neg_m));
-                    const float p1 = fast_exp2(PRE ? s_cur[2 * i + 1] - m_use : fmaf(s_cur[2 * i + 1], c1, neg_m));
-                    psum += p0 + p1;
-                    pw[i] = (int)pack2<T>(p0, p1);
-                }
+                for (int i = 0; i < 8; ++i)
+                    if (i >= ks * NP1 / KS && i < (ks + 1) * NP1 / KS) weights(i);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            l_run += psum;
 
-            // ---- phase 2
+            // ---- weights times V
             float biasn[16];
             if (HAS_BIAS) {
                 if (hb == 0) {
@@ -382,42 +421,69 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
                 }
             }
             // wave-uniform: the block reaches beyond Nk, or beyond what the wave's first query sees
-            const bool ragged = knext + 32 > p.Nk || (CAUSAL && knext + 31 > q0 + c_off);
+            const bool ragged = !CLEAN && (knext + 32 > p.Nk || (CAUSAL && knext + 31 > q0 + c_off));
             float bmax = -INFINITY;
-            int mfma_idx = 0;
+            float psum = 0.0f;
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
                 Frag<1> pf;
                 int4v pv = {pw[4 * st], pw[4 * st + 1], pw[4 * st + 2], pw[4 * st + 3]};
                 pf.c[0] = __builtin_bit_cast(short8v, pv);
 #pragma unroll
-                for (int j = 0; j < JD; ++j, ++mfma_idx) {
+                for (int j = 0; j < JD; ++j) {
                     o_acc[j] = MfmaOp<T>::run(vfr[st][j], pf, o_acc[j]);
                     __builtin_amdgcn_sched_barrier(0);
-                    // the next block's scores: prepared in slices under the first half of the MFMAs,
-                    // maximum and the exchange with lane^32 under the second half
-                    constexpr int HALF = NPV / 2;
-                    if (mfma_idx < HALF) {
-                        if (ragged) scale_scores(s_nxt, knext, biasn, TailYes{}, mfma_idx * 16 / HALF, (mfma_idx + 1) * 16 / HALF);
-                        else scale_scores(s_nxt, knext, biasn, TailNo{}, mfma_idx * 16 / HALF, (mfma_idx + 1) * 16 / HALF);
-                    }
-                    if (mfma_idx == HALF - 1) {
-                        bmax = block_max(s_nxt);
-                        bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+                    if (st == 0) {
+#pragma unroll
+                        for (int i = NP1; i < 8; ++i)
+                            if (i - NP1 >= j * (8 - NP1) / JD && i - NP1 < (j + 1) * (8 - NP1) / JD) weights(i);
+                        if (CLEAN) scale_scores(s_nxt, knext, biasn, TailNo{}, j * 16 / JD, (j + 1) * 16 / JD);
+                        else if (ragged) scale_scores(s_nxt, knext, biasn, TailYes{}, j * 16 / JD, (j + 1) * 16 / JD);
+                        else scale_scores(s_nxt, knext, biasn, TailNo{}, j * 16 / JD, (j + 1) * 16 / JD);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (i >= j * 8 / JD && i < (j + 1) * 8 / JD) psum = pair_sum(pw[i], psum);
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            if (e >= j * 16 / JD && e < (j + 1) * 16 / JD) bmax = fmaxf(bmax, s_nxt[e]);
+                        if (j == JD - 1) {
+                            if (!PRE) bmax *= c1;            // c1 > 0 without PRE: the maximum commutes with the scaling
+                            bmax = exchange_max(bmax);
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            l_run += psum;
             move_reference(bmax);
             if (HAS_BIAS && hb == 0 && t + 1 < NT) { issue_v(t + 1); issue_k(t + 1); }
         }
     };
-    int t = 0;
-    for (; t + 1 < NT; t += 2) {
-        tile(t, IntTag<0>{});
-        tile(t + 1, IntTag<1>{});
+    // leading tiles that need no test: both score blocks computed in tile t end at key 64 t + 95, the loads
+    // issued in it (tile t + 1) end at key 64 t + 159
+    int n_clean = 0;
+    if (!HAS_BIAS) {
+        long long lim = ((long long)p.Nk - 160) / ATT_BKV + 1;
+        if (p.Nk < 160) lim = 0;
+        if (lim > NT - 1) lim = NT - 1;
+        if (CAUSAL) {
+            const long long vis = (long long)q0 + c_off - 95;          // 64 t <= vis
+            const long long l3 = vis < 0 ? 0 : vis / ATT_BKV + 1;
+            if (lim > l3) lim = l3;
+        }
+        n_clean = lim < 0 ? 0 : (int)(lim & ~1LL);
     }
-    if (t < NT) tile(t, IntTag<0>{});
+    int t = 0;
+    for (; t < n_clean; t += 2) {
+        tile(t, IntTag<0>{}, TailYes{});
+        tile(t + 1, IntTag<1>{}, TailYes{});
+    }
+    for (; t + 1 < NT; t += 2) {
+        tile(t, IntTag<0>{}, TailNo{});
+        tile(t + 1, IntTag<1>{}, TailNo{});
+    }
+    if (t < NT) tile(t, IntTag<0>{}, TailNo{});
 
     // ---- normalise and store: the lane holds, for query q0 + lane%32, d = 32 j + 8 g + 4 h + 0..3
     const float l_tot = l_run + __shfl_xor(l_run, 32);
