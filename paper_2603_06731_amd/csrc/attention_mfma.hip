@@ -190,6 +190,8 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         for (int e = 0; e < 16; ++e) o_acc[j][e] = 0.0f;
     float m_run = -INFINITY;      // softmax reference point of the row (log2 domain), same in lane and lane^32
     float l_run = 0.0f;           // this lane's share of the running row sum
+    float neg_m = 0.0f;           // minus the reference point (0 while it is still -inf)
+    float thr = -INFINITY;        // a score above this (before scaling unless PRE) moves the reference point
 
     const float c1 = p.alpha * LOG2E;
     const bool bias_vec = HAS_BIAS && (((uintptr_t)p.bias & 15) == 0) && (p.ld_bias % 4 == 0) && (p.stride_bias % 4 == 0);
@@ -271,23 +273,35 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         for (int e = 0; e < 16; ++e) m = fmaxf(m, sv[e]);
         return PRE ? m : m * c1;          // c1 > 0 without PRE: the maximum commutes with the scaling
     };
+    auto exchange_max = [&](float v) {                       // maximum with lane ^ 32, no LDS round trip
+        const unsigned u = __builtin_bit_cast(unsigned, v);
+        auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+    };
     // The reference point m_run only has to stay within 2^ATT_SLACK of the true running
     // maximum for nothing to overflow: it is moved (and the accumulated sum and output
     // corrected) only when a block exceeds it by more than that.  Weights and sum use the
     // same reference, so the quotient is unchanged.  bmax: block maximum of the row (both halves).
     auto move_reference = [&](float bmax) {
         const bool move = bmax > m_run + ATT_SLACK;                 // same in lane and lane^32
-        if (__builtin_amdgcn_ballot_w64(move) != 0) {
-            const float m_new = move ? bmax : m_run;
-            const float m_sub = m_new == -INFINITY ? 0.0f : m_new;   // every key so far removed by a -inf bias
-            const float corr = fast_exp2(m_run - m_sub);             // 1 where the lane does not move
-            m_run = m_new;
-            l_run *= corr;
+        const float m_new = move ? bmax : m_run;
+        const float m_sub = m_new == -INFINITY ? 0.0f : m_new;   // every key so far removed by a -inf bias
+        const float corr = fast_exp2(m_run - m_sub);             // 1 where the lane does not move
+        m_run = m_new;
+        neg_m = -m_sub;
+        thr = PRE ? m_new + ATT_SLACK : (m_new + ATT_SLACK) / c1;
+        l_run *= corr;
 #pragma unroll
-            for (int j = 0; j < JD; ++j)
+        for (int j = 0; j < JD; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o_acc[j][e] *= corr;
-        }
+            for (int e = 0; e < 16; ++e) o_acc[j][e] *= corr;
+    };
+    // The test that runs for every block is a per-lane one on the lane's own half of the row, against the
+    // threshold kept in the units of the scores; only when some lane of the wave exceeds it are the halves
+    // exchanged and the reference points moved.
+    auto check_reference = [&](float half_max) {
+        if (__builtin_amdgcn_ballot_w64(half_max > thr) != 0)
+            move_reference(exchange_max(PRE ? half_max : half_max * c1));
     };
 
     // ---- prologue: scores of block 0 (keys 0..31, upper half of K slot 1), its reference point
@@ -317,18 +331,13 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
     // every MFMA has about the same number of vector instructions behind it:
     //   behind score MFMA ks:        exponentials of weight pairs [ks NP1/KS, (ks+1) NP1/KS)
     //   behind P V MFMA (st 0, j):   the remaining pairs (they feed st 1), scaling / masking of the next scores
-    //   behind P V MFMA (st 1, j):   row sum of the rounded weights, maximum of the next scores
+    //   behind P V MFMA (st 1, j):   row sum of the rounded weights, the lane's maximum of the next scores
     // PAR: parity of the tile = LDS slot, compile-time so that every LDS address is a per-lane
     // register plus an immediate.  CLEAN: the tile, the two score blocks computed in it and the
     // next tile's loads are all inside the key range (and below the diagonal): no test, no branch
     // other than the rare move of the reference point, so the body is one basic block and the
     // order written here is the order that runs.
     constexpr int NP1 = 5;                                    // weight pairs finished under the score MFMAs (st 0 needs 4)
-    auto exchange_max = [&](float v) {                       // maximum with lane ^ 32, no LDS round trip
-        const unsigned u = __builtin_bit_cast(unsigned, v);
-        auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-        return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
-    };
     auto pair_sum = [&](int w, float acc) {                  // acc + both 16-bit weights of w
         if constexpr (sizeof(T) == 2 && std::is_same<T, bf16_t>::value) {
             typedef __attribute__((ext_vector_type(2))) __bf16 b2;
@@ -378,12 +387,10 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
             const int kcb = PAR * TILE + 32 * hb * (D * 2);           // K rows of the next block
             const int vcb = (2 + PAR) * TILE + 32 * hb * (D * 2);     // V rows of this block
             const int knext = t * ATT_BKV + 32 * hb + 32;             // first key of the next block
-            const float m_use = m_run == -INFINITY ? 0.0f : m_run;
-            const float neg_m = -m_use;
             int pw[8];                 // the block's 16 weights, rounded and packed in pairs
             auto weights = [&](int i) {
-                const float p0 = fast_exp2(PRE ? s_cur[2 * i] - m_use : fmaf(s_cur[2 * i], c1, neg_m));
-                const float p1 = fast_exp2(PRE ? s_cur[2 * i + 1] - m_use : fmaf(s_cur[2 * i + 1], c1, neg_m));
+                const float p0 = fast_exp2(PRE ? s_cur[2 * i] + neg_m : fmaf(s_cur[2 * i], c1, neg_m));
+                const float p1 = fast_exp2(PRE ? s_cur[2 * i + 1] + neg_m : fmaf(s_cur[2 * i + 1], c1, neg_m));
                 pw[i] = (int)pack2<T>(p0, p1);
             };
 
@@ -423,7 +430,6 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
             // wave-uniform: the block reaches beyond Nk, or beyond what the wave's first query sees
             const bool ragged = !CLEAN && (knext + 32 > p.Nk || (CAUSAL && knext + 31 > q0 + c_off));
             float bmax = -INFINITY;
-            float psum = 0.0f;
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
                 Frag<1> pf;
@@ -443,20 +449,15 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
                     } else {
 #pragma unroll
                         for (int i = 0; i < 8; ++i)
-                            if (i >= j * 8 / JD && i < (j + 1) * 8 / JD) psum = pair_sum(pw[i], psum);
+                            if (i >= j * 8 / JD && i < (j + 1) * 8 / JD) l_run = pair_sum(pw[i], l_run);
 #pragma unroll
                         for (int e = 0; e < 16; ++e)
                             if (e >= j * 16 / JD && e < (j + 1) * 16 / JD) bmax = fmaxf(bmax, s_nxt[e]);
-                        if (j == JD - 1) {
-                            if (!PRE) bmax *= c1;            // c1 > 0 without PRE: the maximum commutes with the scaling
-                            bmax = exchange_max(bmax);
-                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            l_run += psum;
-            move_reference(bmax);
+            check_reference(bmax);
             if (HAS_BIAS && hb == 0 && t + 1 < NT) { issue_v(t + 1); issue_k(t + 1); }
         }
     };
