@@ -148,6 +148,16 @@ def test_attention_causal_mfma(dtype, shape):
     check_attention(w, expect_kernel="causal")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("nk", [159, 160, 161, 223, 224, 225, 287, 288, 289, 352])
+def test_attention_interior_loop_boundaries(nk, causal):
+    """The kernel walks its leading 64-key tiles in a loop body without range tests and the rest in the
+    general one; the first tile that needs a test depends on Nk (the next tile's loads must lie inside) and,
+    for the causal form, on the wave's first query.  Key counts on both sides of every such boundary."""
+    w = wl.AttentionWorkload(f"att_edge_{nk}", BF16, 2, 150, nk, 64, alpha=scale(64), causal=causal)
+    check_attention(w, expect_kernel="causal" if causal else "attn_mfma")
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("shape", [(2, 50, 300, 64), (1, 17, 513, 40), (2, 9, 9, 3), (1, 70, 70, 200)])
 def test_attention_causal_generic(dtype, shape):
