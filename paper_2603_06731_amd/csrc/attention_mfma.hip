@@ -216,17 +216,13 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
     auto read_k = [&](int cbyte, int ks) {        // cbyte: slot and block offset, compile-time at every call
         kfr[ks & 3].c[0] = *(const short8v*)(lds + koff[ks] + cbyte);
     };
-    // V^T fragments of one 32-key block: 2 steps of 16 keys x JD blocks of 32 d
+    // V^T fragments of one 32-key block: 2 steps of 16 keys x JD blocks of 32 d, read one per score MFMA
     Frag<1> vfr[2][JD];
-    auto read_v = [&](int cbyte) {
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int j = 0; j < JD; ++j) {
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, lds + voff[j] + cbyte + (st * 16) * (D * 2)));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, lds + voff[j] + cbyte + (st * 16 + 8) * (D * 2)));
-                vfr[st][j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
+    auto read_v1 = [&](int cbyte, int f) {       // fragment f = st * JD + j, in the order the P V MFMAs use them
+        const int st = f / JD, j = f % JD;
+        short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, lds + voff[j] + cbyte + (st * 16) * (D * 2)));
+        short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PBK_LDS_PTR(short4v, lds + voff[j] + cbyte + (st * 16 + 8) * (D * 2)));
+        vfr[st][j].c[0] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
     // Scores of a block, in place.  Register 4g + t is key kbase + 8 g + 4 h + t.  Elements [e0, e1).
@@ -368,7 +364,6 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
         // next tile's loads, which hides their LDS latency
 #pragma unroll
         for (int ks = 0; ks < KPF; ++ks) read_k(PAR * TILE, ks);
-        read_v((2 + PAR) * TILE);
         __builtin_amdgcn_sched_barrier(0);
         // Without a bias the next tile's loads go out right away.  With one, the bias is read
         // with ordinary loads whose completion (vmcnt counts every vector memory operation, in
@@ -395,15 +390,12 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
             };
 
             // ---- scores of the next block, weights of this one
-            if (hb != 0) {
-#pragma unroll
-                for (int ks = 0; ks < KPF; ++ks) read_k(kcb, ks);
-                read_v(vcb);
-            }
-            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks + KPF < KS) read_k(kcb, ks + KPF);
+                // one V fragment of this block per score MFMA (there are KS = 2 JD of each), in the order of
+                // their use: no burst of LDS reads stands between the blocks
+                read_v1(vcb, ks);
                 __builtin_amdgcn_sched_barrier(0);
                 if (ks == 0) {
 #pragma unroll
@@ -439,6 +431,12 @@ __global__ __launch_bounds__(ATT_NW * 64, 2) void attention_mfma_kernel(AttnProb
                 for (int j = 0; j < JD; ++j) {
                     o_acc[j] = MfmaOp<T>::run(vfr[st][j], pf, o_acc[j]);
                     __builtin_amdgcn_sched_barrier(0);
+                    if (hb == 0 && st == 1 && j == 0) {
+                        // the score MFMAs are done with the K fragment registers: the first fragments of the
+                        // tile's second block are fetched now (same K slot, rows 32..63)
+#pragma unroll
+                        for (int ks = 0; ks < KPF; ++ks) read_k(PAR * TILE + 32 * (D * 2), ks);
+                    }
                     if (st == 0) {
 #pragma unroll
                         for (int i = NP1; i < 8; ++i)
