@@ -19,7 +19,7 @@ SOURCES += [("gemm_mfma_int8.hip", "gemm_mfma_int8", [])]
 SOURCES += [("gemm_mfma_16bit.hip", f"gemm_mfma_{name}_g{g}",
              [f"-DPBK_16BIT_TYPE={name}_t", f"-DPBK_16BIT_NAME={name}", f"-DPBK_GROUP={g}"])
             for g in reversed(range(N_GROUPS_16)) for name in ("bf16", "f16")]
-SOURCES += [(f, f[:-4], []) for f in ("gemm_mfma_gather.hip", "gemm_mfma_f32.hip", "attention_mfma.hip", "gemm_mfma_fp8.hip",
+SOURCES += [(f, f[:-4], []) for f in ("gemm_mfma_bstat.hip", "gemm_mfma_gather.hip", "gemm_mfma_f32.hip", "attention_mfma.hip", "gemm_mfma_fp8.hip",
                                       "gemm_mfma.hip", "pbk_api.hip", "gemm_generic.hip", "gemm_small_f32.hip",
                                       "attention_generic.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

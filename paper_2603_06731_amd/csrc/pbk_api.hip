@@ -30,7 +30,8 @@ bool aligned(const void* p, int64_t a) { return (reinterpret_cast<uintptr_t>(p) 
 // kernel), "mfma" (the matrix-unit path, automatic tile configuration), "mfma:<id>" (one tile
 // configuration) or "gather" (the matrix-unit kernel that stages through registers).  The environment variables PBK_FORCE_KERNEL and PBK_GROUP_M are read ONCE,
 // at the first call of the process; pbk_force_kernel() overrides the former per thread.
-// force: 0 automatic, 1 generic, 2 mfma, 3 the gathering mfma kernel, 4 the small fp32 kernel; cfg: -1 or id
+// force: 0 automatic, 1 generic, 2 mfma, 3 the gathering mfma kernel, 4 the small fp32 kernel, 5 "bstat" (the
+// B-stationary kernel for short contractions); cfg: -1 or id
 struct Choice { int force; int cfg; };
 
 bool parse_choice(const char* e, Choice* c) {
@@ -40,6 +41,7 @@ bool parse_choice(const char* e, Choice* c) {
     if (!std::strcmp(e, "mfma")) { c->force = 2; return true; }
     if (!std::strcmp(e, "gather")) { c->force = 3; return true; }
     if (!std::strcmp(e, "small")) { c->force = 4; return true; }
+    if (!std::strcmp(e, "bstat")) { c->force = 5; return true; }
     if (!std::strncmp(e, "mfma:", 5) && e[5] >= '0' && e[5] <= '9') { c->force = 2; c->cfg = std::atoi(e + 5); return true; }
     return false;
 }
@@ -88,9 +90,14 @@ pbk_status dispatch(const pbk::Problem& p_in, hipStream_t stream) {
     const bool want_gather = !can_mfma && can_gather && (long long)p.M * p.N >= 4096 && p.K >= 16;
     // fp32 problems of a few hundred 16 x 16 tiles: one wave per tile
     const bool can_small = pbk::small_f32_supported(p);
-    if ((force == 2 && !can_mfma && !can_gather) || (force == 3 && !can_gather) || (force == 4 && !can_small))
+    // short contractions over many rows: the B-stationary kernel
+    const bool can_bstat = pbk::mfma_bstat_supported(p);
+    if ((force == 2 && !can_mfma && !can_gather) || (force == 3 && !can_gather) || (force == 4 && !can_small) ||
+        (force == 5 && !can_bstat))
         return PBK_ERR_UNSUPPORTED;
-    if (force == 4 || (force == 0 && can_small && pbk::small_f32_preferred(p) && !(can_mfma && pbk::mfma_preferred(p))))
+    if (force == 5 || (force == 0 && can_bstat && pbk::mfma_bstat_preferred(p)))
+        e = pbk::launch_mfma_bstat(p, stream, &name);
+    else if (force == 4 || (force == 0 && can_small && pbk::small_f32_preferred(p) && !(can_mfma && pbk::mfma_preferred(p))))
         e = pbk::launch_small_f32(p, stream, &name);
     else if (can_mfma && force != 1 && force != 3 && (force == 2 || pbk::mfma_preferred(p)))
         e = pbk::launch_mfma(p, stream, cfg, &name);
