@@ -263,6 +263,9 @@ __global__ __launch_bounds__(SWAVES * 64, 2) void gemm_mfma_bstat_kernel(Problem
             }
             stage = stage + 1 == S_STAGES ? 0 : stage + 1;
         }
+        // the last two requests for A lie beyond the rows and only clear a stage: they have ended (all but the
+        // last step's stores have) before the wave gives its LDS back
+        wait_vmcnt<NS>();
     };
     const int act = (p.epi == EPI_RELU || p.epi == EPI_BIAS_RELU) ? 1
                   : (p.epi == EPI_GELU_TANH || p.epi == EPI_BIAS_GELU_TANH) ? 2 : 0;
