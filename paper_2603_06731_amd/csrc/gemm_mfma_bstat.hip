@@ -344,7 +344,7 @@ bool mfma_bstat_supported(const Problem& p) {
 bool mfma_bstat_preferred(const Problem& p) {
     if (p.M < 512 || p.N < 256) return false;
     const long long steps = (long long)((p.M + SBM - 1) / SBM) * ((p.N + SBN - 1) / SBN) * p.batch;
-    return steps >= 2048;
+    return steps >= 1536;
 }
 
 hipError_t launch_mfma_bstat(const Problem& p, hipStream_t stream, const char** name) {

@@ -189,6 +189,14 @@ pbk_status conv_common(const void* x, const void* w, void* y, const float* bias,
     p.conv.pad_h = (int)pad_h; p.conv.pad_w = (int)pad_w;
     p.conv.dil_h = (int)dil_h; p.conv.dil_w = (int)dil_w;
     p.conv.transposed = transposed;
+    // A 1x1 filter at stride 1 without padding IS the matmul [N H W][Cin] x [Cin][Cout] (Sec. 4.5: the virtual
+    // matmul's rows are then the pixels themselves): it takes the plain-matrix kernels, which carry no tap
+    // arithmetic, and with few input channels the store-bound B-stationary one.
+    if (KH == 1 && KW == 1 && stride_h == 1 && stride_w == 1 && pad_h == 0 && pad_w == 0 && !transposed &&
+        OH == H && OW == W) {
+        p.is_conv = 0;
+        p.lda = Cin;
+    }
     if (quant) set_quant(p, q_scale, bias, q_mid, q_mul, q_add, q_relu, q_out);
     return dispatch(p, stream);
 }

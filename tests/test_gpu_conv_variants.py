@@ -113,3 +113,35 @@ def test_conv_transpose_large_sampled():
     err = T.rel_err(got, ref, pre)
     print(f"convT_big kernel={kern} samples={len(i)} err={err:.3e}", flush=True)
     assert "mfma" in kern and err <= T.TIGHT[BF16], err
+
+
+# ------------------------------------------------------ pointwise convolutions
+
+@pytest.mark.parametrize("dtype,out_dtype", [(BF16, BF16), (F16, F32), (F32, F32)])
+@pytest.mark.parametrize("case", [  # n, H, W, Cin, Cout
+    (3, 20, 17, 64, 264),
+    (2, 9, 9, 136, 40),
+    (1, 30, 30, 24, 8),
+])
+def test_pointwise_conv_runs_as_the_plain_matmul(case, dtype, out_dtype):
+    """A 1x1 filter at stride 1 without padding is the matmul [N H W][Cin] x [Cin][Cout]: the call takes the
+    plain-matrix kernels (the B-stationary one, which declines every convolution, accepts it) and matches the
+    convolution oracle."""
+    n, H, W, Cin, Cout = case
+    w = wl.Workload("conv_1x1", "conv", dtype, out_dtype, C.EPI_BIAS_RELU, n=n, H=H, W=W, Cin=Cin, Cout=Cout,
+                    KH=1, KW=1, stride=(1, 1), pad=(0, 0), dist_b=("normal", he(1, 1, Cin)))
+    check(w)
+    if dtype != F32 and Cin <= 128:
+        check(w, force="bstat", expect_kernel="bstat")
+
+
+def test_strided_or_padded_1x1_conv_stays_a_convolution():
+    import paper_2603_06731_amd as pbk
+    for stride, pad in (((2, 2), (0, 0)), ((1, 1), (1, 1))):
+        w = wl.Workload("conv_1x1_s", "conv", BF16, BF16, C.EPI_BIAS, n=2, H=12, W=12, Cin=64, Cout=64,
+                        KH=1, KW=1, stride=stride, pad=pad, dist_b=("normal", he(1, 1, 64)))
+        check(w)
+        host = wl.make_inputs(w)
+        with T.forced_kernel("bstat"):
+            st, _ = T.run_workload(w, T.upload(host))
+        assert st != 0 and "not supported" in pbk.pbk_status_string(st)
