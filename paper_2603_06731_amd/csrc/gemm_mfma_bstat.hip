@@ -332,6 +332,7 @@ hipError_t launch_bstat_type(const Problem& p, hipStream_t stream) {
 bool mfma_bstat_supported(const Problem& p) {
     if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16) return false;
     if (p.is_conv || p.K > 128 || p.R) return false;
+    if (p.M > 0x7FFFFFFF - 4 * SBM) return false;       // (the walk requests pieces up to two steps beyond its last row)
     // whole aligned 16-byte chunks of C (the stores are 16 bytes per lane, per-lane offsets 32-bit)
     const int esz = p.out_dtype == DT_F32 ? 4 : 2, epc = 16 / esz;
     if (p.N % epc || p.ldc % epc || p.stride_c % epc || (reinterpret_cast<uintptr_t>(p.C) & 15)) return false;
