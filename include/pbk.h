@@ -305,7 +305,7 @@ const char* pbk_last_kernel(void);
  * the fallback kernel, "mfma" the matrix-unit path with its automatic tile choice,
  * "mfma:<id>" one tile configuration (operands that the direct-to-LDS kernel cannot take
  * go to the gathering matrix-unit kernel instead), "gather" that kernel, "small" the
- * one-wave-per-tile fp32 kernel, "bstat" the B-stationary kernel for short contractions (K <= 128) over
+ * one-wave-per-tile fp32 kernel, "bstat" the B-stationary kernel for short contractions (K <= 256) over
  * many rows; a problem the choice cannot run gives PBK_ERR_UNSUPPORTED.  NULL or "" returns to the default.  The default is automatic
  * choice, or what the environment variable PBK_FORCE_KERNEL (same strings) held when the
  * process made its first call.  An unknown string is PBK_ERR_UNSUPPORTED and changes nothing.

@@ -66,7 +66,10 @@ static int choose_config(const Problem& p) {
     // (K = 1024 / 2048: the two 128x256 workgroups are 2-5 % ahead; K = 4096 and 8192: 10 % behind)
     // (9 = 7 with one barrier per two k-tiles: 8192^3 739 against 757 us, the MLP shape 711 against 726 us,
     // interleaved runs; 6 % on a 24-tile problem that is not power limited)
-    if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 512 && p.K >= 3072) return 9;
+    // (a sweep of 6 against 9 over 256- to 4096-tile problems: 9 is 5-13 % ahead from K = 2048 up, also on one
+    // round of 256 tiles (4096^2 x 3072: 78 against 86 us, 8192 x 2048 x 8192: 186 against 212 us); K = 1024
+    // is a tie, below that 6 wins by up to 17 % unless the output is far larger than the last-level cache)
+    if (!p.is_conv && !p.trans_b && p.M >= 256 && p.N >= 256 && t256 >= 256 && p.K >= 2048) return 9;
     // convolutions whose channel count is a multiple of 64 (the image is then staged in 64-deep pieces): 9 from one
     // round of 256x256 tiles and K = 1024 up (32x56x56x256 -> 256, 3x3: 131 against 151 us; 64x28x28x256 -> 512: 121
     // against 133 us; K = 576 equal; 1x1 filters and fewer than 100 tiles: 6 or 1 stay ahead by 10-15 %)

@@ -1,4 +1,4 @@
-// Matrix-unit contraction for SHORT contractions with many output rows (K <= 128: the attention-score
+// Matrix-unit contraction for SHORT contractions with many output rows (K <= 256: the attention-score
 // product Q K^T with the head dimension as K, 1x1 projections).  Such a problem is bound by the stores of
 // its output, and a tile-per-workgroup kernel spends its time in a chain of latencies per tile (first
 // loads, a few k-tiles, the stores) while every workgroup fetches (BM + BN) K operand values for BM BN
@@ -7,7 +7,7 @@
 // Here the B operand of a workgroup's 256 columns is STATIONARY IN REGISTERS (paper Sec. 4.3: the operand
 // that is reused across a loop is kept in the fastest buffer): each of the 4 waves keeps the MFMA
 // fragments of its 64 columns over the whole contraction (K/2 registers per lane) and the workgroup walks
-// down its share of the rows in steps of 64.  Per step it fetches only the 64 x K piece of A
+// down its share of the rows in steps of 64 (32 when K > 128).  Per step it fetches only the 64 x K piece of A
 // (direct-to-LDS loads of whole 128-byte lines into a ring of three stages: the pieces of the next two steps
 // are in flight), runs 16 (K/32) MFMAs per wave in two halves of 32 rows and stores 64 x 256 outputs: the
 // pointwise tail is applied to the accumulators (Sec. 4.3 fusion), the rounded values pass once through the
@@ -16,7 +16,7 @@
 // Nothing in the loop waits for a store: every step issues a FIXED number of loads and stores (buffer
 // operations whose offset is out of range where nothing is to be moved), a wave's memory operations
 // complete in issue order, and so "the piece of this step has landed" is an s_waitcnt on a constant count
-// of younger operations.  Two workgroups share a compute unit (65 KiB of LDS, 170 registers).
+// of younger operations.  Two workgroups share a compute unit (65 KiB of LDS, 170 registers; 253 at K = 256).
 // A in LDS: per 64-deep piece [64 rows][64 k] with the main kernel's 16-byte-chunk swizzle; B passes once
 // through LDS, 32 KiB at a time: k-major (trans_b) in the layout of A's pieces, row-major as [64 k][256 n]
 // in the main kernel's n-major layout, read with the transposing LDS read.
@@ -25,11 +25,10 @@
 namespace pbk {
 namespace {
 
-constexpr int SBM = 64, SBN = 256;          // rows per step, columns per workgroup
+constexpr int SBM = 64, SBN = 256;          // rows per step (32 when K > 128: the LDS ring holds three pieces of A), columns per workgroup
 constexpr int SWAVES = 4;                   // waves, side by side along n
 constexpr int SWTN = SBN / SWAVES;          // 64 columns per wave
-constexpr int SFM = SBM / 16, SFN = SWTN / 16;
-constexpr int S_PIECE = SBM * 64 * 2;       // 8 KiB: 64 rows x 64 k
+constexpr int SFN = SWTN / 16;
 constexpr int S_STAGES = 3;                 // LDS stages of A: the pieces of the next two steps are in flight
 constexpr int S_SLICE = 4096;               // a wave's LDS slice for the epilogue's change of lane ownership
 
@@ -43,8 +42,10 @@ struct StatMap {
 template <typename T, bool TRANS_B, int KP>       // KP: 64-deep pieces of the contraction (K <= 64 KP)
 __global__ __launch_bounds__(SWAVES * 64, 2) void gemm_mfma_bstat_kernel(Problem p, StatMap map) {
     constexpr int KS = 2 * KP;                    // MFMA k-steps
+    constexpr int ROWS = KP <= 2 ? SBM : SBM / 2; // rows per step
+    constexpr int S_PIECE = ROWS * 64 * 2;        // a 64-deep piece of a step's rows: 8 or 4 KiB
     constexpr int A_STAGE = KP * S_PIECE;
-    constexpr int A_LOADS = KP * 8 / SWAVES;      // 1 KiB direct-to-LDS loads per wave and step
+    constexpr int A_LOADS = KP * (ROWS / 8) / SWAVES;      // 1 KiB direct-to-LDS loads per wave and step
     extern __shared__ __attribute__((aligned(1024))) char lds[];     // S_STAGES A stages | 4 epilogue slices | bias
 
     const int t = threadIdx.x, lane = t & 63;
@@ -130,8 +131,8 @@ __global__ __launch_bounds__(SWAVES * 64, 2) void gemm_mfma_bstat_kernel(Problem
 #pragma unroll
     for (int r = 0; r < A_LOADS; ++r) {
         const int blk = wave * A_LOADS + r;
-        const int piece = blk >> 3;
-        const int row = (blk & 7) * 8 + (lane >> 3), slot = lane & 7;
+        const int piece = blk / (ROWS / 8);
+        const int row = (blk % (ROWS / 8)) * 8 + (lane >> 3), slot = lane & 7;
         const int chunk = slot ^ kmajor_swz<64, true>(row);
         const int k = piece * 64 + chunk * 8;
         a_row[r] = row;
@@ -161,11 +162,11 @@ __global__ __launch_bounds__(SWAVES * 64, 2) void gemm_mfma_bstat_kernel(Problem
         constexpr int CPR = ROW_BYTES / 16;
         constexpr int RP = 256 / ROW_BYTES;                 // rows per 256 bytes
         constexpr int ROWS_PER_ST = 64 / CPR;               // rows one store instruction covers
-        constexpr int HALF_ROWS = SBM / 2, HFM = SFM / 2;   // a step is worked off in two halves of 32 rows
+        constexpr int HALF_ROWS = 32, HFM = 2, NHALF = ROWS / HALF_ROWS;   // a step is worked off in halves of 32 rows (one or two)
         constexpr int PASS_ROWS = S_SLICE / ROW_BYTES < HALF_ROWS ? S_SLICE / ROW_BYTES : HALF_ROWS;
         constexpr int PASSES = HALF_ROWS / PASS_ROWS;
         constexpr int ST_PER_PASS = PASS_ROWS / ROWS_PER_ST;
-        constexpr int NS = 2 * PASSES * ST_PER_PASS;        // store instructions per wave and step, issued unconditionally
+        constexpr int NS = NHALF * PASSES * ST_PER_PASS;        // store instructions per wave and step, issued unconditionally
         static_assert(NS <= 32, "vmcnt range");
         const int ld_row = lane / CPR, ld_chunk = lane % CPR;
         // (out of range for a lane whose columns lie beyond N: adding a row offset below 2^31 keeps it there)
@@ -181,8 +182,8 @@ __global__ __launch_bounds__(SWAVES * 64, 2) void gemm_mfma_bstat_kernel(Problem
         // before step s + 2, and the stores of a step have two steps' time to drain.
         int stage = 0, step = 0;
         issue_a(m_begin, 0);
-        issue_a(m_begin + SBM, 1);
-        for (int m = m_begin; m < m_end; m += SBM, ++step) {
+        issue_a(m_begin + ROWS, 1);
+        for (int m = m_begin; m < m_end; m += ROWS, ++step) {
             if (step == 0) wait_vmcnt<A_LOADS>();
             else if (step == 1) wait_vmcnt<A_LOADS + NS>();
             else wait_vmcnt<A_LOADS + 2 * NS>();
@@ -191,13 +192,13 @@ __global__ __launch_bounds__(SWAVES * 64, 2) void gemm_mfma_bstat_kernel(Problem
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             const int refill = stage == 0 ? S_STAGES - 1 : stage - 1;
-            issue_a(m + 2 * SBM, refill);
+            issue_a(m + 2 * ROWS, refill);
             const char* sa = lds + stage * A_STAGE;
             const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)(Cbase + (int64_t)m * p.ldc * ESZ), 0, (int)kOob, 0x00020000);
-            // the step in two halves of 32 rows: half the accumulators are live at a time
+            // the step in halves of 32 rows: 32 accumulators are live at a time
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
+            for (int hf = 0; hf < NHALF; ++hf) {
                 f32x4 acc[HFM][SFN];
 #pragma unroll
                 for (int i = 0; i < HFM; ++i)
@@ -288,7 +289,8 @@ hipError_t launch_bstat_one(const Problem& p, hipStream_t stream) {
     e = device_shape(dev, &ds);
     if (e != hipSuccess) return e;
     // the LDS a workgroup needs: two stages of A and the epilogue slices; B is staged 32 KiB at a time
-    int lds_bytes = S_STAGES * KP * S_PIECE + SWAVES * S_SLICE + SBN * 4;
+    constexpr int ROWS = KP <= 2 ? SBM : SBM / 2;
+    int lds_bytes = S_STAGES * KP * ROWS * 128 + SWAVES * S_SLICE + SBN * 4;
     if (lds_bytes < 32768) lds_bytes = 32768;
     static std::atomic<unsigned> attr_done{0};      // bit per device
     const unsigned bit = 1u << (dev & 31);
@@ -323,15 +325,19 @@ template <typename T>
 hipError_t launch_bstat_type(const Problem& p, hipStream_t stream) {
     if (p.K <= 64)
         return p.trans_b ? launch_bstat_one<T, true, 1>(p, stream) : launch_bstat_one<T, false, 1>(p, stream);
-    return p.trans_b ? launch_bstat_one<T, true, 2>(p, stream) : launch_bstat_one<T, false, 2>(p, stream);
+    if (p.K <= 128)
+        return p.trans_b ? launch_bstat_one<T, true, 2>(p, stream) : launch_bstat_one<T, false, 2>(p, stream);
+    if (p.K <= 192)
+        return p.trans_b ? launch_bstat_one<T, true, 3>(p, stream) : launch_bstat_one<T, false, 3>(p, stream);
+    return p.trans_b ? launch_bstat_one<T, true, 4>(p, stream) : launch_bstat_one<T, false, 4>(p, stream);
 }
 
 }  // namespace
 
-// 16-bit plain matrices (no convolution) that meet the direct-to-LDS kernel's alignment rules, K <= 128
+// 16-bit plain matrices (no convolution) that meet the direct-to-LDS kernel's alignment rules, K <= 256
 bool mfma_bstat_supported(const Problem& p) {
     if (p.in_dtype != DT_BF16 && p.in_dtype != DT_F16) return false;
-    if (p.is_conv || p.K > 128 || p.R) return false;
+    if (p.is_conv || p.K > 256 || p.R) return false;
     if (p.M > 0x7FFFFFFF - 4 * SBM) return false;       // (the walk requests pieces up to two steps beyond its last row)
     // whole aligned 16-byte chunks of C (the stores are 16 bytes per lane, per-lane offsets 32-bit)
     const int esz = p.out_dtype == DT_F32 ? 4 : 2, epc = 16 / esz;
@@ -349,7 +355,8 @@ bool mfma_bstat_preferred(const Problem& p) {
 }
 
 hipError_t launch_mfma_bstat(const Problem& p, hipStream_t stream, const char** name) {
-    *name = p.K <= 64 ? "mfma16_bstat_64x256_k64_w1x4_occ2" : "mfma16_bstat_64x256_k128_w1x4_occ2";
+    *name = p.K <= 64 ? "mfma16_bstat_64x256_k64_w1x4_occ2" : p.K <= 128 ? "mfma16_bstat_64x256_k128_w1x4_occ2"
+          : p.K <= 192 ? "mfma16_bstat_32x256_k192_w1x4_occ2" : "mfma16_bstat_32x256_k256_w1x4_occ2";
     return p.in_dtype == DT_BF16 ? launch_bstat_type<bf16_t>(p, stream) : launch_bstat_type<f16_t>(p, stream);
 }
 

@@ -95,7 +95,7 @@ hipError_t launch_mfma(const Problem& p, hipStream_t stream, int force_cfg, cons
 bool mfma_gather_supported(const Problem& p);
 hipError_t launch_mfma_gather(const Problem& p, hipStream_t stream, const char** name);
 
-// Short contractions (K <= 128) over many rows: B stationary in registers, the workgroup walks down M.
+// Short contractions (K <= 256) over many rows: B stationary in registers, the workgroup walks down M.
 bool mfma_bstat_supported(const Problem& p);
 bool mfma_bstat_preferred(const Problem& p);
 hipError_t launch_mfma_bstat(const Problem& p, hipStream_t stream, const char** name);

@@ -1,4 +1,4 @@
-"""Parity of the B-stationary matrix-unit kernel (short contractions, K <= 128, over many rows: the
+"""Parity of the B-stationary matrix-unit kernel (short contractions, K <= 256, over many rows: the
 attention-score product and its relatives) with the CPU oracle, element by element."""
 import numpy as np
 import pytest
@@ -57,6 +57,10 @@ def run_case(batch, M, N, K, dtype, out_dtype, trans_b, epi, alpha=1.0, pad_ld=0
     (77, 520, 96),           # K between the pieces: the second one half empty
     (200, 256, 40),          # K below one piece, not a multiple of 32
     (64, 8, 8),              # one step, one 16-byte piece of K, eight columns
+    (700, 512, 256),         # four pieces, 32-row steps, a ragged last step
+    (333, 264, 192),         # three pieces
+    (96, 256, 136),          # just above two pieces
+    (1000, 328, 232),        # four pieces, the last one ragged
 ])
 def test_bstat_matches_oracle(mnk, dtype, out_dtype, trans_b):
     M, N, K = mnk
@@ -71,9 +75,10 @@ def test_bstat_matches_oracle(mnk, dtype, out_dtype, trans_b):
 def test_bstat_batched_views_and_epilogues(epi, trans_b):
     """Several batch entries, leading dimensions longer than the rows with NaN behind them, every epilogue;
     nothing may be stored outside the views."""
-    err, kern = run_case(3, 712, 328, 128, BF16, BF16, trans_b, epi, alpha=1.0 / np.sqrt(128.0), pad_ld=8,
-                         bias_on=epi in (C.EPI_BIAS, C.EPI_BIAS_RELU))
-    assert "bstat" in kern and err <= T.TIGHT[BF16], (kern, err)
+    for k in (128, 256):
+        err, kern = run_case(3, 712, 328, k, BF16, BF16, trans_b, epi, alpha=1.0 / np.sqrt(128.0), pad_ld=8,
+                             bias_on=epi in (C.EPI_BIAS, C.EPI_BIAS_RELU))
+        assert "bstat" in kern and err <= T.TIGHT[BF16], (kern, err)
 
 
 def test_bstat_is_the_dispatchers_choice_for_the_score_product_and_equals_the_tile_kernel():
@@ -87,8 +92,8 @@ def test_bstat_is_the_dispatchers_choice_for_the_score_product_and_equals_the_ti
 
 def test_bstat_declines_long_contractions_and_convolutions():
     import paper_2603_06731_amd as pbk
-    a = T.to_device(wl.tensor((64, 136), BF16, 1, "normal")); b = T.to_device(wl.tensor((136, 64), BF16, 2, "normal"))
+    a = T.to_device(wl.tensor((64, 264), BF16, 1, "normal")); b = T.to_device(wl.tensor((264, 64), BF16, 2, "normal"))
     out = T.device_empty(64 * 64, BF16, fill=0)
     with T.forced_kernel("bstat"):
-        st = pbk.pbk_matmul(a, b, out, None, 64, 64, 136, 136, 64, 64, BF16, BF16, 0, 1.0, C.EPI_NONE)
+        st = pbk.pbk_matmul(a, b, out, None, 64, 64, 264, 264, 64, 64, BF16, BF16, 0, 1.0, C.EPI_NONE)
     assert st != 0 and "not supported" in pbk.pbk_status_string(st), pbk.pbk_status_string(st)
