@@ -132,6 +132,15 @@ EXTRA_CONFIGS = {
         "fp8_e4m3_8192_nt", "matmul", gen.DTYPE_FP8_E4M3, _BF16, EPI_BIAS_RELU, M=8192, N=8192, K=8192,
         trans_b=1, dist_a=("normal", 1.0), dist_b=("normal", 1.0 / math.sqrt(8192)),
         dist_bias=("normal", 0.1)),
+    # score product with a head dimension of 256 (the shape of cfg3 with twice the contraction)
+    "bf16_attn_scores_d256": Workload(
+        "bf16_attn_scores_d256", "batched", _BF16, _BF16, EPI_NONE,
+        alpha=float(np.float32(1.0 / math.sqrt(256.0))), batch=64, M=2048, N=2048, K=256),
+    # pointwise convolution of a bottleneck block (64 -> 256 channels at 56 x 56): the matmul [N H W][64] x [64][256]
+    "bf16_conv1x1_64_256": Workload(
+        "bf16_conv1x1_64_256", "conv", _BF16, _BF16, EPI_BIAS_RELU, n=128, H=56, W=56,
+        Cin=64, Cout=256, KH=1, KW=1, stride=(1, 1), pad=(0, 0),
+        dist_a=("normal", 1.0), dist_b=("normal", math.sqrt(2.0 / 64.0)), dist_bias=("normal", 0.1)),
 }
 
 
