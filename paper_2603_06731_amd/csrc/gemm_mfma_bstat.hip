@@ -184,6 +184,7 @@ __global__ __launch_bounds__(SWAVES * 64, 2) void gemm_mfma_bstat_kernel(Problem
         issue_a(m_begin, 0);
         issue_a(m_begin + ROWS, 1);
         for (int m = m_begin; m < m_end; m += ROWS, ++step) {
+            asm volatile("" ::: "memory");        // (the previous step's stores are issued: the counts below rely on it)
             if (step == 0) wait_vmcnt<A_LOADS>();
             else if (step == 1) wait_vmcnt<A_LOADS + NS>();
             else wait_vmcnt<A_LOADS + 2 * NS>();
