@@ -285,3 +285,26 @@ def test_int8_relu_keeps_nan(force):
     assert np.isnan(got[:, 5]).all() and np.isnan(want[:, 5]).all()
     keep = np.ones(n, bool); keep[5] = False
     assert np.array_equal(got[:, keep], want[:, keep])
+
+
+@pytest.mark.parametrize("chan", [(32, 48), (64, 272), (24, 20)])
+@pytest.mark.parametrize("out_int8", [True, False])
+def test_pointwise_conv_int8_runs_as_the_plain_matmul(chan, out_int8):
+    """A 1x1 filter at stride 1 without padding goes to the plain-matrix int8 kernels (channel counts that are
+    multiples of 16: the matrix units; others: the generic kernel) and stays bit-exact with the convolution oracle."""
+    import torch
+    import oracle
+    import paper_2603_06731_amd as pbk
+    Cin, Cout = chan
+    n, H, W = 3, 11, 13
+    x = wl.int8_tensor((n, H, W, Cin), 1, "normal", 40.0); w = wl.int8_tensor((1, 1, Cin, Cout), 2, "normal", 30.0)
+    q = params(Cout, 3)
+    want = oracle.conv2d_nhwc_int8(x, w, stride=(1, 1), pad=(0, 0), dil=(1, 1), out_int8=out_int8, **q)
+    out = torch.empty(want.size, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+    d = {k2: dev_or_none(v) if isinstance(v, np.ndarray) else v for k2, v in q.items()}
+    st = pbk.pbk_conv2d_nhwc_int8(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), out, n, H, W, Cin, Cout,
+                                  1, 1, 1, 1, 0, 0, 1, 1, d["scale"], d["bias"], q["mid_scale"], d["mul"], d["add"],
+                                  q["relu"], q["out_scale"], INT8 if out_int8 else F32, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    assert ("mfma" in pbk.pbk_last_kernel()) == (Cin % 16 == 0 and Cout % 16 == 0), pbk.pbk_last_kernel()
+    assert np.array_equal(out.cpu().numpy().reshape(want.shape), want)

@@ -117,3 +117,21 @@ def test_plain_calls_are_unaffected_after_a_residual_call():
     assert pbk.pbk_matmul(dA, dB, out, None, m, n, k, k, n, n, BF16, BF16, 0, 1.0, 0, None) == 0
     ref, pre = oracle.matmul(A, B, dtype=BF16, want_preact=True)
     assert T.rel_err(T.to_host_f64(out, BF16).reshape(ref.shape), ref, pre) <= T.TIGHT[BF16]
+
+
+def test_pointwise_conv_residual():
+    """The last convolution of a bottleneck block, 1x1: relu(conv1x1(x) + bias + shortcut); the boundary hands it
+    to the plain-matrix kernels with the residual operand in place."""
+    import oracle
+    import paper_2603_06731_amd as pbk
+    n, H, W, Cin, Cout = 2, 12, 11, 64, 264
+    x = wl.tensor((n, H, W, Cin), BF16, 1, "normal"); w = wl.tensor((1, 1, Cin, Cout), BF16, 2, "normal", 0.17)
+    bias = wl.tensor((Cout,), F32, 3, "normal", 0.1); r = wl.tensor((n, H, W, Cout), BF16, 4, "normal")
+    out = out_tensor(n * H * W * Cout, BF16)
+    st = pbk.pbk_conv2d_nhwc_residual(T.to_device(x), T.to_device(w), out, T.to_device(bias), T.to_device(r),
+                                      n, H, W, Cin, Cout, 1, 1, 1, 1, 0, 0, 1, 1, BF16, BF16, 1.0, 1.0, C.EPI_BIAS_RELU, None)
+    assert st == 0, pbk.pbk_status_string(st)
+    ref, pre = oracle.conv2d_nhwc_residual(x, w, bias, r, dtype=BF16, r_dtype=BF16, pad=(0, 0), epi=C.EPI_BIAS_RELU,
+                                           want_preact=True)
+    err = T.rel_err(T.to_host_f64(out, BF16).reshape(ref.shape), ref, pre)
+    assert "mfma" in pbk.pbk_last_kernel() and err <= T.TIGHT[BF16], (pbk.pbk_last_kernel(), err)
